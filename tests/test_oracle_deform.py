@@ -1,0 +1,224 @@
+"""Pins for the oracle's deformation routines.
+
+Checked against what the mathematics fixes: identity for zero displacement, exact bilinear
+interpolation of affine-linear images, quarter turns as index permutations, scipy.ndimage's
+Gaussian filter / direct 2-D convolution / map_coordinates as independent library routines.
+"""
+import numpy as np
+import pytest
+import scipy.ndimage as ndi
+
+from paper_1003_0358_amd import datagen
+
+
+def _img(seed=0):
+    return datagen.stroke_images(4, seed=seed)[0].reshape(4, 28, 28)
+
+
+# ---- Gaussian taps and smoothing -------------------------------------------
+def test_taps(oracle):
+    g = oracle.gauss_taps(6.0, 21)
+    assert g.size == 21                                   # appendix "Deformations": 21 x 21 kernel
+    assert g.sum() == pytest.approx(1.0, abs=1e-15)
+    assert np.allclose(g, g[::-1], rtol=0, atol=0)
+    assert g[10] == g.max()
+    # ratio of neighbouring taps is fixed by sigma alone
+    assert g[11] / g[10] == pytest.approx(np.exp(-1 / 72.0), rel=1e-14)
+    assert g[0] / g[10] == pytest.approx(np.exp(-100 / 72.0), rel=1e-14)
+    # sigma 0: no smoothing
+    assert list(oracle.gauss_taps(0.0, 5)) == [0, 0, 1, 0, 0]
+
+
+def test_smoothing_impulse_response_is_outer_product(oracle):
+    f = np.zeros((28, 28)); f[13, 15] = 1.0
+    out = oracle.smooth_field(f, 6.0, 21, 1.0)
+    g = oracle.gauss_taps(6.0, 21)
+    want = np.zeros((28, 28))
+    for dr in range(-10, 11):
+        for dc in range(-10, 11):
+            r, c = 13 + dr, 15 + dc
+            if 0 <= r < 28 and 0 <= c < 28:
+                want[r, c] = g[dr + 10] * g[dc + 10]
+    assert np.allclose(out, want, rtol=0, atol=1e-16)
+    # an off-centre impulse puts the right tap at the right place (no transposition)
+    f = np.zeros((28, 28)); f[2, 20] = 1.0
+    out = oracle.smooth_field(f, 3.0, 21, 2.0)
+    g = oracle.gauss_taps(3.0, 21)
+    assert out[5, 19] == pytest.approx(2.0 * g[10 + 3] * g[10 - 1], rel=1e-14)
+
+
+def test_smoothing_matches_scipy_gaussian_and_direct_2d(oracle):
+    rng = np.random.default_rng(0)
+    f = rng.uniform(-1, 1, (28, 28))
+    out = oracle.smooth_field(f, 6.0, 21, 36.0)
+    # library routine: separable Gaussian of radius 10, zeros outside
+    ref = 36.0 * ndi.gaussian_filter(f, sigma=6.0, radius=10, mode="constant", cval=0.0)
+    assert np.allclose(out, ref, rtol=0, atol=1e-12)
+    # the full 21 x 21 = 441-tap sum, which is how the paper's convolution kernel forms it
+    g = oracle.gauss_taps(6.0, 21)
+    ref2 = 36.0 * ndi.convolve(f, np.outer(g, g), mode="constant", cval=0.0)
+    assert np.allclose(out, ref2, rtol=0, atol=1e-12)
+    # rms displacement for the paper's sigma = 6, alpha = 36 is of the order of a pixel
+    assert 0.3 < np.sqrt((out ** 2).mean()) < 3.0
+
+
+def test_smoothing_constant_interior(oracle):
+    # where all taps are inside the field, smoothing a constant returns the constant (taps sum to 1)
+    f = np.full((40, 36), 0.75)
+    out = oracle.smooth_field(f, 2.0, 5, 4.0)
+    assert np.allclose(out[2:-2, 2:-2], 3.0, rtol=0, atol=1e-14)
+    assert out[0, 0] < 3.0                                # zero padding lowers the border
+    # non-square field keeps its orientation
+    f = np.zeros((40, 36)); f[30, 5] = 1
+    out = oracle.smooth_field(f, 2.0, 5, 1.0)
+    assert out[30, 5] == out.max() and out.shape == (40, 36)
+
+
+# ---- resampling -------------------------------------------------------------
+@pytest.mark.parametrize("mode", ["f64", "f32"])
+def test_zero_displacement_is_identity(oracle, mode):
+    img = _img()[0]
+    z = np.zeros((28, 28))
+    out = oracle.resample(img, 1.0, 0.0, 1.0, 1.0, z, z, mode)
+    want = img.astype(np.float64) / 127.5 - 1.0 if mode == "f64" else datagen.to_inputs(img)
+    assert np.array_equal(out, want)                       # exact
+    # whole pipeline with alpha = beta = gamma = 0
+    full = oracle.deform_batch(_img().reshape(4, 784), seed=5, first_index=0, alpha=0.0, beta_deg=0.0,
+                               gamma_pct=0.0, mode=mode)
+    allw = _img().reshape(4, 784)
+    want = allw.astype(np.float64) / 127.5 - 1.0 if mode == "f64" else datagen.to_inputs(allw)
+    assert np.array_equal(full, want)
+
+
+def test_bilinear_exact_on_affine_linear_image(oracle):
+    # an image that is a plane: P(r,c) = 10 + 3 r + 5 c (all values integers <= 255)
+    r, c = np.meshgrid(np.arange(28), np.arange(28), indexing="ij")
+    img = (10 + 3 * r + 5 * c).astype(np.uint8)
+    rng = np.random.default_rng(1)
+    dx = rng.uniform(-2, 2, (28, 28)); dy = rng.uniform(-2, 2, (28, 28))
+    th = np.deg2rad(6.0); cs, sn, sx, sy = np.cos(th), np.sin(th), 1.1, 0.9
+    out = oracle.resample(img, cs, sn, sx, sy, dx, dy)
+    u, v = c - 13.5, r - 13.5
+    X = sx * (cs * u - sn * v) + 13.5 + dx
+    Y = sy * (sn * u + cs * v) + 13.5 + dy
+    inside = (X >= 0) & (X <= 27) & (Y >= 0) & (Y <= 27)
+    assert inside.sum() > 400
+    want = (10 + 3 * Y + 5 * X) / 127.5 - 1.0
+    assert np.allclose(out[inside], want[inside], rtol=0, atol=1e-10)
+    out32 = oracle.resample(img, cs, sn, sx, sy, dx, dy, "f32")
+    assert np.abs(out32[inside] - want[inside]).max() * 127.5 < 1e-4   # in 0..255 intensity units
+
+
+def test_quarter_turn_is_a_permutation(oracle):
+    img = _img()[1]
+    z = np.zeros((28, 28))
+    th = np.pi / 2
+    out = oracle.resample(img, np.cos(th), np.sin(th), 1.0, 1.0, z, z)
+    # source (X, Y) = (-v, u) + 13.5: out[r][c] = img[c][27 - r]
+    want = np.array([[img[c, 27 - r] for c in range(28)] for r in range(28)]) / 127.5 - 1.0
+    assert np.allclose(out, want, rtol=0, atol=1e-10)
+    # half turn: out[r][c] = img[27-r][27-c]
+    out = oracle.resample(img, -1.0, 0.0, 1.0, 1.0, z, z)
+    assert np.allclose(out, img[::-1, ::-1] / 127.5 - 1.0, rtol=0, atol=1e-12)
+
+
+def test_constant_displacement_is_a_shift_with_zero_fill(oracle):
+    img = _img()[2]
+    dx = np.full((28, 28), 3.0); dy = np.full((28, 28), -2.0)
+    out = oracle.resample(img, 1.0, 0.0, 1.0, 1.0, dx, dy)
+    want = np.zeros((28, 28))
+    want[2:, :25] = img[:26, 3:]                            # out[r][c] = img[r-2][c+3]
+    assert np.array_equal(out, want / 127.5 - 1.0)
+    # half-pixel shift averages neighbours
+    out = oracle.resample(img, 1.0, 0.0, 1.0, 1.0, np.full((28, 28), 0.5), np.zeros((28, 28)))
+    nb = np.concatenate([img[:, 1:], np.zeros((28, 1))], axis=1)
+    assert np.allclose(out, (img + nb) / 2 / 127.5 - 1.0, rtol=0, atol=1e-13)
+
+
+def test_scaling_direction_and_axes(oracle):
+    # sx multiplies source x offsets: a single bright pixel right of centre moves towards the centre
+    img = np.zeros((28, 28), np.uint8); img[13:15, 21] = 255
+    z = np.zeros((28, 28))
+    out = oracle.resample(img, 1.0, 0.0, 1.25, 1.0, z, z)
+    cols = np.where(out.max(axis=0) > -1.0)[0]
+    assert cols.min() >= 18 and cols.max() <= 20          # 13.5 + 7.5/1.25 = 19.5
+    # sy acts on rows only
+    img = np.zeros((28, 28), np.uint8); img[21, 13:15] = 255
+    out = oracle.resample(img, 1.0, 0.0, 1.0, 1.25, z, z)
+    rows = np.where(out.max(axis=1) > -1.0)[0]
+    assert rows.min() >= 18 and rows.max() <= 20
+
+
+def test_resample_matches_scipy_map_coordinates(oracle):
+    img = _img()[3]
+    rng = np.random.default_rng(2)
+    dx = oracle.smooth_field(rng.uniform(-1, 1, (28, 28)), 6.0, 21, 36.0)
+    dy = oracle.smooth_field(rng.uniform(-1, 1, (28, 28)), 6.0, 21, 36.0)
+    th = np.deg2rad(-7.5); cs, sn, sx, sy = np.cos(th), np.sin(th), 0.85, 1.15
+    out = oracle.resample(img, cs, sn, sx, sy, dx, dy)
+    r, c = np.meshgrid(np.arange(28.0), np.arange(28.0), indexing="ij")
+    u, v = c - 13.5, r - 13.5
+    X = sx * (cs * u - sn * v) + 13.5 + dx
+    Y = sy * (sn * u + cs * v) + 13.5 + dy
+    # order-1 spline = bilinear; 'grid-constant' pads with zeros and interpolates across the border
+    ref = ndi.map_coordinates(img.astype(np.float64), [Y, X], order=1, mode="grid-constant", cval=0.0)
+    assert np.allclose(out, ref / 127.5 - 1.0, rtol=0, atol=1e-12)
+    # far outside: background
+    out = oracle.resample(img, 1.0, 0.0, 1.0, 1.0, np.full((28, 28), 1e6), np.full((28, 28), -1e9))
+    assert np.array_equal(out, np.full((28, 28), -1.0))
+
+
+# ---- the whole pipeline -----------------------------------------------------
+def test_pipeline_is_the_composition_of_its_steps(oracle):
+    imgs = _img(seed=3)
+    out = oracle.deform_batch(imgs.reshape(4, 784), seed=11, first_index=100)
+    for k in range(4):
+        s3, Dx, Dy = oracle.draw_image_randoms(11, 100 + k)
+        # counters 0,1,2 then the two fields, from the stream of the image's global index
+        allr = oracle.rng_sym(11, 100 + k, 0, 3 + 2 * 784)
+        assert np.array_equal(s3, allr[:3]) and np.array_equal(Dx, allr[3:787]) and np.array_equal(Dy, allr[787:])
+        cs, sn, sx, sy = oracle.affine_scalars(7.5, 15.0, s3)
+        th = np.deg2rad(7.5 * float(s3[0]))
+        assert (cs, sn) == pytest.approx((np.cos(th), np.sin(th)), abs=1e-15)
+        assert sx == pytest.approx(1 + 0.15 * float(s3[1]), abs=1e-15)
+        assert sy == pytest.approx(1 + 0.15 * float(s3[2]), abs=1e-15)
+        gx = oracle.smooth_field(Dx.reshape(28, 28), 6.0, 21, 36.0)
+        gy = oracle.smooth_field(Dy.reshape(28, 28), 6.0, 21, 36.0)
+        want = oracle.resample(imgs[k], cs, sn, sx, sy, gx, gy)
+        assert np.array_equal(out[k], want.ravel())
+
+
+def test_parameter_ranges(oracle):
+    th, sx, sy = [], [], []
+    for k in range(2000):
+        s3, _, _ = oracle.draw_image_randoms(0, k)
+        cs, sn, a, b = oracle.affine_scalars(7.5, 15.0, s3)
+        th.append(np.rad2deg(np.arctan2(sn, cs))); sx.append(a); sy.append(b)
+    th, sx, sy = map(np.array, (th, sx, sy))
+    assert -7.5 <= th.min() < -7.0 and 7.0 < th.max() <= 7.5    # rotation uniform in +-7.5 degrees
+    assert 0.85 <= sx.min() < 0.86 and 1.14 < sx.max() <= 1.15  # scaling uniform in +-15 %
+    assert 0.85 <= sy.min() < 0.86 and 1.14 < sy.max() <= 1.15
+    assert abs(np.corrcoef(sx, sy)[0, 1]) < 0.1                 # x and y scales are independent
+
+
+def test_chunking_and_seed(oracle):
+    imgs = datagen.stroke_images(6, seed=1)[0]
+    a = oracle.deform_batch(imgs, seed=9, first_index=0)
+    b = np.concatenate([oracle.deform_batch(imgs[:2], seed=9, first_index=0),
+                        oracle.deform_batch(imgs[2:], seed=9, first_index=2)])
+    assert np.array_equal(a, b)                            # randomness depends on (seed, global index) only
+    c = oracle.deform_batch(imgs, seed=10, first_index=0)
+    assert np.abs(a - c).max() > 0.1
+    assert a.min() >= -1.0 and a.max() <= 1.0
+    # deformation moves things but keeps most of the ink
+    ink0 = (datagen.to_inputs(imgs) + 1).sum(axis=1)
+    ink1 = (a + 1).sum(axis=1)
+    assert np.all(ink1 > 0.5 * ink0) and np.all(ink1 < 1.6 * ink0)
+
+
+def test_f32_mode_tracks_f64(oracle):
+    imgs = datagen.stroke_images(64, seed=2)[0]
+    a = oracle.deform_batch(imgs, seed=3, first_index=0, mode="f64")
+    b = oracle.deform_batch(imgs, seed=3, first_index=0, mode="f32")
+    assert b.dtype == np.float32
+    assert np.abs(a - b).max() < 1e-5
