@@ -1,0 +1,144 @@
+/*
+ * dbsn.h — C ABI of libdbsn: on-line (batch size 1) back-propagation through big plain
+ * multi-layer perceptrons and on-the-fly elastic + affine deformation of 28x28 images,
+ * hand-written for AMD MI355X (gfx950).
+ *
+ * Method: Ciresan, Meier, Gambardella, Schmidhuber, "Deep Big Simple Neural Nets Excel on
+ * Handwritten Digit Recognition" (sections and appendix parts are cited per call below).
+ *
+ * Conventions
+ *  - Every function returns int32_t: DBSN_OK (0) or a negative DBSN_E_* code; nothing throws or
+ *    aborts.  dbsn_last_error() gives a thread-local message for the last failing call.
+ *    On an argument error no device work is issued.
+ *  - Pointers named *_dev are DEVICE pointers, *_host are HOST pointers.  All device memory is
+ *    allocated and owned by the caller; the library allocates no device memory and never frees
+ *    caller memory.  Device pointers must be 16-byte aligned unless stated otherwise.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  A network keeps
+ *    the stream it was initialised with; all its calls are asynchronous on that stream except
+ *    the dbsn_mlp_get_* / dbsn_mlp_status calls, which synchronise it.
+ *  - A network handle must not be used from two host threads at once.
+ *  - Arithmetic is IEEE binary32 throughout (the paper's nets are single precision).
+ */
+#ifndef DBSN_H
+#define DBSN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DBSN_OK          0
+#define DBSN_E_ARG      -1   /* null pointer, negative count, label or layer out of range, ...      */
+#define DBSN_E_SHAPE    -2   /* unsupported shape, misaligned pointer, arena too small               */
+#define DBSN_E_HIP      -3   /* a HIP runtime call failed                                            */
+#define DBSN_E_TIMEOUT  -4   /* the in-kernel grid barrier gave up waiting (reported by _status)     */
+
+#define DBSN_MAX_LAYERS  16     /* weight layers (n_sizes - 1)                                        */
+#define DBSN_MAX_WIDTH   4096   /* neurons in any layer, inputs included                              */
+#define DBSN_MAX_CLASSES 64     /* neurons in the output layer                                        */
+#define DBSN_MAX_KTAPS   63     /* taps of the 1-D Gaussian                                           */
+#define DBSN_IMG_SIDE    28
+#define DBSN_IMG_PIXELS  784
+
+typedef struct dbsn_mlp dbsn_mlp;   /* opaque host handle */
+
+/* Deformation parameters (section "Deforming images to get more training instances"):
+ * sigma, alpha: Gaussian width (pixels) and scale of the elastic displacement field;
+ * beta_deg: rotation angle drawn uniformly from [-beta, +beta] degrees;
+ * gamma_pct: x and y scale factors drawn independently from [1-gamma/100, 1+gamma/100];
+ * ktaps: odd number of taps of the 1-D Gaussian (the appendix uses a 21 x 21 kernel). */
+typedef struct {
+    float   sigma;
+    float   alpha;
+    float   beta_deg;
+    float   gamma_pct;
+    int32_t ktaps;
+} dbsn_deform_params;
+
+/* Execution mode of dbsn_bp_steps / dbsn_bp_step (results are identical bit for bit):
+ * 0: one kernel launch per layer phase;  1: one persistent kernel per call, layer phases
+ * separated by an in-kernel grid barrier (default). */
+#define DBSN_MODE_LAUNCHES   0
+#define DBSN_MODE_PERSISTENT 1
+
+/* Bytes of device memory a network of the given layer sizes needs (weights, biases, activations,
+ * deltas, partial sums, flags).  sizes[0] = inputs, sizes[n_sizes-1] = classes.  Returns 0 for an
+ * unsupported shape (n_sizes < 2 or > DBSN_MAX_LAYERS+1, a size < 1 or > DBSN_MAX_WIDTH, more than
+ * DBSN_MAX_CLASSES outputs).  Host-only; touches no device. */
+size_t dbsn_mlp_arena_bytes(const int32_t* sizes_host, int32_t n_sizes);
+
+/* Create a network in the caller's arena (arena_dev: device, 256-byte aligned, at least
+ * dbsn_mlp_arena_bytes() long, owned by the caller and kept alive until dbsn_mlp_free) and fill
+ * it (section "Architectures"): every weight and bias uniform in [-0.05, 0.05), drawn from the
+ * library's counter generator so that the result depends on `seed` alone.  The bias is the weight
+ * of a constant-1 input, as in the appendix's kernels.  *out receives the handle. */
+int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes_host, int32_t n_sizes, uint64_t seed,
+                      void* arena_dev, size_t arena_bytes, void* hip_stream);
+
+/* Frees the host handle only (after synchronising its stream). */
+int32_t dbsn_mlp_free(dbsn_mlp* mlp);
+
+/* Copy layer `layer` (1 .. L) from / to dense host arrays: W_host[n_l][n_{l-1}] row-major,
+ * b_host[n_l].  Either pointer may be NULL to skip that part.  Both synchronise the stream. */
+int32_t dbsn_mlp_set_weights(dbsn_mlp* mlp, int32_t layer, const float* W_host, const float* b_host);
+int32_t dbsn_mlp_get_weights(dbsn_mlp* mlp, int32_t layer, float* W_host, float* b_host);
+
+/* State left by the last dbsn_bp_step / dbsn_forward, for inspection: x_host[n_l] = outputs of
+ * layer `layer` (1 .. L-1: scaled-tanh activations; L: softmax probabilities); d_host[n_l] =
+ * deltas of layer `layer` (1 .. L) of the last bp step.  Synchronise the stream. */
+int32_t dbsn_mlp_get_activations(dbsn_mlp* mlp, int32_t layer, float* x_host);
+int32_t dbsn_mlp_get_deltas(dbsn_mlp* mlp, int32_t layer, float* d_host);
+
+/* Select DBSN_MODE_*.  */
+int32_t dbsn_mlp_set_mode(dbsn_mlp* mlp, int32_t mode);
+
+/* Polls a workgroup may spend in one grid barrier before it gives up (default 2^24, seconds of
+ * waiting).  Exists so that the time-out path can be exercised from the host. */
+int32_t dbsn_mlp_set_spin_limit(dbsn_mlp* mlp, uint32_t polls);
+
+/* Synchronise the network's stream and report deferred errors: DBSN_E_TIMEOUT if a grid barrier
+ * of a persistent kernel gave up (the weights are then undefined), DBSN_E_HIP for a failed launch. */
+int32_t dbsn_mlp_status(dbsn_mlp* mlp);
+
+/* Deform n images (section "Deforming images ...", appendix "Deformations"): for image k, all
+ * random numbers are a function of (seed, first_index + k) only, so splitting a set into chunks
+ * does not change the result.  Per image: rotation angle and two scale factors; two displacement
+ * fields uniform in [-1,1) per pixel, each smoothed with the separable ktaps-tap Gaussian of
+ * width sigma (taps sum to 1, field taken as zero outside the image) and multiplied by alpha;
+ * output pixel (r,c) is the bilinear sample of the source at the rotated-and-scaled position of
+ * (r,c) about the image centre plus the displacement at (r,c), pixels outside the source counting
+ * as 0; the result is mapped to intensity/127.5 - 1 (section "Data").
+ * src_dev: [n][784] uint8 (any alignment); dst_dev: [n][784] float.  n == 0 is a no-op. */
+int32_t dbsn_deform_batch(const dbsn_deform_params* params_host, const uint8_t* src_dev, int64_t n,
+                          uint64_t seed, uint64_t first_index, float* dst_dev, void* hip_stream);
+
+/* n on-line back-propagation steps, strictly in order (sections "Architectures", "Training
+ * algorithm"; appendix "Forward propagation", "Backward propagation", "Weight updating"): for
+ * each sample, forward through scaled-tanh hidden layers y = 1.7159 tanh(0.6666 a) and a softmax
+ * output, output delta p - onehot(label), deltas back-propagated through the weights as they were
+ * before the step, then every weight w_ji -= eta * delta_j * x_i (no momentum, batch size 1).
+ * samples_dev: [n][sizes[0]] float; labels_dev: [n] int32 in 0 .. classes-1 (device memory; an
+ * out-of-range label is clamped into range by the kernel); loss_dev: [n] float receiving
+ * -log p_label per step, or NULL.  n == 0 is a no-op. */
+int32_t dbsn_bp_steps(dbsn_mlp* mlp, const float* samples_dev, const int32_t* labels_dev, int64_t n,
+                      float eta, float* loss_dev);
+
+/* One step on one sample with a host-side label: dbsn_bp_steps with n = 1. */
+int32_t dbsn_bp_step(dbsn_mlp* mlp, const float* sample_dev, int32_t label, float eta);
+
+/* Forward propagation of one sample; probs_dev: [classes] float softmax outputs. */
+int32_t dbsn_forward(dbsn_mlp* mlp, const float* sample_dev, float* probs_dev);
+
+/* Forward-only classification of n samples: labels_out_dev[s] = index of the largest output
+ * (lowest index on ties), as used for validation and test passes (sections "Data", "Results"). */
+int32_t dbsn_classify(dbsn_mlp* mlp, const float* samples_dev, int64_t n, int32_t* labels_out_dev);
+
+/* Message for the last error on this host thread ("" if none). */
+const char* dbsn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBSN_H */

@@ -1,0 +1,253 @@
+"""ctypes binding of libdbsn (include/dbsn.h): argument marshalling only.
+
+Every function of the C ABI appears here under its own name, as a method of `Lib`; device buffers
+are torch tensors (PyTorch serves as the device allocator and stream provider, nothing else).
+`Mlp` is a small convenience owner for the arena tensor and the handle.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdbsn.so")
+
+OK, E_ARG, E_SHAPE, E_HIP, E_TIMEOUT = 0, -1, -2, -3, -4
+MODE_LAUNCHES, MODE_PERSISTENT = 0, 1
+
+SYMBOLS = [
+    "dbsn_mlp_arena_bytes", "dbsn_mlp_init", "dbsn_mlp_free", "dbsn_mlp_set_weights", "dbsn_mlp_get_weights",
+    "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
+    "dbsn_mlp_status", "dbsn_deform_batch", "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify",
+    "dbsn_last_error",
+]
+
+
+class DeformParams(C.Structure):
+    _fields_ = [("sigma", C.c_float), ("alpha", C.c_float), ("beta_deg", C.c_float), ("gamma_pct", C.c_float),
+                ("ktaps", C.c_int32)]
+
+
+class DbsnError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libdbsn error %d: %s" % (code, msg))
+        self.code = code
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / None."""
+    if t is None:
+        return C.c_void_p(0)
+    if isinstance(t, np.ndarray):
+        return C.c_void_p(t.ctypes.data)
+    return C.c_void_p(t.data_ptr())
+
+
+class Lib:
+    def __init__(self, path=LIB_PATH):
+        if not os.path.exists(path):
+            raise RuntimeError("libdbsn.so is not built (%s): run `python -m paper_1003_0358_amd.build` or "
+                               "__graft_entry__.build()" % path)
+        self.c = C.CDLL(path)
+        c = self.c
+        vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+        c.dbsn_mlp_arena_bytes.restype = C.c_size_t
+        c.dbsn_mlp_arena_bytes.argtypes = [vp, i32]
+        c.dbsn_mlp_init.argtypes = [C.POINTER(vp), vp, i32, u64, vp, C.c_size_t, vp]
+        c.dbsn_mlp_free.argtypes = [vp]
+        c.dbsn_mlp_set_weights.argtypes = [vp, i32, vp, vp]
+        c.dbsn_mlp_get_weights.argtypes = [vp, i32, vp, vp]
+        c.dbsn_mlp_get_activations.argtypes = [vp, i32, vp]
+        c.dbsn_mlp_get_deltas.argtypes = [vp, i32, vp]
+        c.dbsn_mlp_set_mode.argtypes = [vp, i32]
+        c.dbsn_mlp_set_spin_limit.argtypes = [vp, C.c_uint32]
+        c.dbsn_mlp_status.argtypes = [vp]
+        c.dbsn_deform_batch.argtypes = [C.POINTER(DeformParams), vp, i64, u64, u64, vp, vp]
+        c.dbsn_bp_steps.argtypes = [vp, vp, vp, i64, f32, vp]
+        c.dbsn_bp_step.argtypes = [vp, vp, i32, f32]
+        c.dbsn_forward.argtypes = [vp, vp, vp]
+        c.dbsn_classify.argtypes = [vp, vp, i64, vp]
+        c.dbsn_last_error.restype = C.c_char_p
+        for name in SYMBOLS:
+            if name not in ("dbsn_mlp_arena_bytes", "dbsn_last_error"):
+                getattr(c, name).restype = i32
+
+    # -- raw calls: return the C return code ------------------------------------------------
+    def last_error(self):
+        return self.c.dbsn_last_error().decode()
+
+    def check(self, rc):
+        if rc != OK:
+            raise DbsnError(rc, self.last_error())
+
+    def mlp_arena_bytes(self, sizes):
+        s = np.ascontiguousarray(sizes, dtype=np.int32)
+        return int(self.c.dbsn_mlp_arena_bytes(s.ctypes.data, len(s)))
+
+    def mlp_init(self, sizes, seed, arena, stream=0):
+        """-> (rc, handle)"""
+        s = np.ascontiguousarray(sizes, dtype=np.int32)
+        h = C.c_void_p(0)
+        nbytes = 0 if arena is None else arena.numel() * arena.element_size()
+        rc = self.c.dbsn_mlp_init(C.byref(h), s.ctypes.data, len(s), seed, _ptr(arena), nbytes, C.c_void_p(stream))
+        return rc, h
+
+    def mlp_free(self, h):
+        return self.c.dbsn_mlp_free(h)
+
+    def mlp_set_weights(self, h, layer, W_host, b_host):
+        return self.c.dbsn_mlp_set_weights(h, layer, _ptr(W_host), _ptr(b_host))
+
+    def mlp_get_weights(self, h, layer, W_host, b_host):
+        return self.c.dbsn_mlp_get_weights(h, layer, _ptr(W_host), _ptr(b_host))
+
+    def mlp_get_activations(self, h, layer, x_host):
+        return self.c.dbsn_mlp_get_activations(h, layer, _ptr(x_host))
+
+    def mlp_get_deltas(self, h, layer, d_host):
+        return self.c.dbsn_mlp_get_deltas(h, layer, _ptr(d_host))
+
+    def mlp_set_mode(self, h, mode):
+        return self.c.dbsn_mlp_set_mode(h, mode)
+
+    def mlp_set_spin_limit(self, h, polls):
+        return self.c.dbsn_mlp_set_spin_limit(h, polls)
+
+    def mlp_status(self, h):
+        return self.c.dbsn_mlp_status(h)
+
+    def deform_batch(self, params, src, n, seed, first_index, dst, stream=0):
+        return self.c.dbsn_deform_batch(C.byref(params) if params is not None else None, _ptr(src), n, seed,
+                                        first_index, _ptr(dst), C.c_void_p(stream))
+
+    def bp_steps(self, h, samples, labels, n, eta, loss=None):
+        return self.c.dbsn_bp_steps(h, _ptr(samples), _ptr(labels), n, eta, _ptr(loss))
+
+    def bp_step(self, h, sample, label, eta):
+        return self.c.dbsn_bp_step(h, _ptr(sample), label, eta)
+
+    def forward(self, h, sample, probs):
+        return self.c.dbsn_forward(h, _ptr(sample), _ptr(probs))
+
+    def classify(self, h, samples, n, labels_out):
+        return self.c.dbsn_classify(h, _ptr(samples), n, _ptr(labels_out))
+
+
+_lib = None
+
+
+def load():
+    """The process-wide Lib; raises if libdbsn.so has not been built."""
+    global _lib
+    if _lib is None:
+        _lib = Lib()
+    return _lib
+
+
+def default_deform_params():
+    """sigma 6, alpha 36, rotation +-7.5 degrees, scaling +-15 %, 21 taps (values the paper reports using)."""
+    return DeformParams(6.0, 36.0, 7.5, 15.0, 21)
+
+
+class Mlp:
+    """Owns the arena tensor and the handle of one network; methods raise DbsnError on failure."""
+
+    def __init__(self, sizes, seed=0, device="cuda:0", mode=MODE_PERSISTENT):
+        import torch
+        self.lib = load()
+        self.sizes = [int(s) for s in sizes]
+        nbytes = self.lib.mlp_arena_bytes(self.sizes)
+        if nbytes == 0:
+            raise DbsnError(E_SHAPE, "unsupported layer sizes %r" % (self.sizes,))
+        self.torch = torch
+        self.device = torch.device(device)
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device).cuda_stream
+        rc, self.h = self.lib.mlp_init(self.sizes, seed, self.arena, self.stream)
+        self.lib.check(rc)
+        self.lib.check(self.lib.mlp_set_mode(self.h, mode))
+
+    def close(self):
+        if getattr(self, "h", None) is not None and self.h:
+            self.lib.mlp_free(self.h)
+            self.h = None
+
+    __del__ = close
+
+    @property
+    def L(self):
+        return len(self.sizes) - 1
+
+    def set_mode(self, mode):
+        self.lib.check(self.lib.mlp_set_mode(self.h, mode))
+
+    def status(self):
+        self.lib.check(self.lib.mlp_status(self.h))
+
+    def get_weights(self, layer):
+        W = np.empty((self.sizes[layer], self.sizes[layer - 1]), dtype=np.float32)
+        b = np.empty(self.sizes[layer], dtype=np.float32)
+        self.lib.check(self.lib.mlp_get_weights(self.h, layer, W, b))
+        return W, b
+
+    def set_weights(self, layer, W, b):
+        W = None if W is None else np.ascontiguousarray(W, dtype=np.float32)
+        b = None if b is None else np.ascontiguousarray(b, dtype=np.float32)
+        self.lib.check(self.lib.mlp_set_weights(self.h, layer, W, b))
+
+    def get_params(self):
+        """All layers, packed [W_1, b_1, W_2, b_2, ...] dense row-major."""
+        parts = []
+        for l in range(1, self.L + 1):
+            W, b = self.get_weights(l)
+            parts += [W.ravel(), b]
+        return np.concatenate(parts)
+
+    def set_params(self, params):
+        o = 0
+        for l in range(1, self.L + 1):
+            nin, nout = self.sizes[l - 1], self.sizes[l]
+            W = params[o:o + nin * nout].reshape(nout, nin); o += nin * nout
+            b = params[o:o + nout]; o += nout
+            self.set_weights(l, W, b)
+
+    def get_activations(self, layer):
+        x = np.empty(self.sizes[layer], dtype=np.float32)
+        self.lib.check(self.lib.mlp_get_activations(self.h, layer, x))
+        return x
+
+    def get_deltas(self, layer):
+        d = np.empty(self.sizes[layer], dtype=np.float32)
+        self.lib.check(self.lib.mlp_get_deltas(self.h, layer, d))
+        return d
+
+    def bp_steps(self, samples, labels, eta, loss=None):
+        n = samples.shape[0]
+        self.lib.check(self.lib.bp_steps(self.h, samples, labels, n, float(eta), loss))
+
+    def bp_step(self, sample, label, eta):
+        self.lib.check(self.lib.bp_step(self.h, sample, int(label), float(eta)))
+
+    def forward(self, sample):
+        probs = self.torch.empty(self.sizes[-1], dtype=self.torch.float32, device=self.device)
+        self.lib.check(self.lib.forward(self.h, sample, probs))
+        return probs
+
+    def classify(self, samples):
+        n = samples.shape[0]
+        out = self.torch.empty(n, dtype=self.torch.int32, device=self.device)
+        self.lib.check(self.lib.classify(self.h, samples, n, out))
+        return out
+
+
+def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None):
+    """src_u8: uint8 device tensor [n, 784] -> float32 device tensor [n, 784]."""
+    import torch
+    lib = load()
+    n = src_u8.shape[0]
+    if out is None:
+        out = torch.empty((n, 784), dtype=torch.float32, device=src_u8.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(src_u8.device).cuda_stream
+    lib.check(lib.deform_batch(params or default_deform_params(), src_u8, n, seed, first_index, out, stream))
+    return out

@@ -1,0 +1,115 @@
+// Deformation kernel of libdbsn for gfx950 (section "Deforming images to get more training
+// instances", appendix "Deformations").
+//
+// One workgroup of 256 threads deforms one 28x28 image entirely in LDS: it draws the two random
+// displacement fields, smooths them with the separable Gaussian (rows, then columns, the field
+// being zero outside the image), scales them by alpha, adds the rotated-and-scaled pixel grid
+// and takes the bilinear sample of the source image.  The paper ran only the (full 2-D, 441-tap)
+// convolution on its GPU and everything else on the CPU; here nothing leaves the chip between the
+// uint8 source (784 B read) and the float result (3136 B written).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dbsn_rng.h"
+
+namespace dbsn {
+
+constexpr int kSide = 28;
+constexpr int kPix = kSide * kSide;
+constexpr int kDeformThreads = 256;
+constexpr int kMaxTaps = 63;
+
+struct DeformArgs {
+    float taps[kMaxTaps + 1];  // 1-D Gaussian, sums to 1, taps[R] is the centre
+    int ktaps;
+    float alpha, beta_deg, gamma_pct;
+    uint64_t seed, first_index;
+    long long n;
+};
+
+__global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const uint8_t* __restrict__ src,
+                                                            float* __restrict__ dst) {
+    __shared__ float img[kPix];
+    __shared__ float fx[kPix], fy[kPix];   // raw fields, later reused for nothing else
+    __shared__ float tx[kPix], ty[kPix];   // after the row pass
+    __shared__ float aff[4];               // cos, sin, sx, sy
+    const int R = (a.ktaps - 1) / 2;
+
+    for (long long k = blockIdx.x; k < a.n; k += gridDim.x) {
+        const uint64_t key = rng_key(a.seed, a.first_index + (uint64_t)k);
+        const uint8_t* s = src + k * kPix;
+        for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
+            img[i] = (float)s[i];
+            fx[i] = rng_unit(rng_draw(key, 3ull + (uint64_t)i));
+            fy[i] = rng_unit(rng_draw(key, 3ull + (uint64_t)kPix + (uint64_t)i));
+        }
+        if (threadIdx.x == 0) {
+            // per-image scalars are formed in double and rounded once to float
+            const double u0 = (double)rng_unit(rng_draw(key, 0));
+            const double u1 = (double)rng_unit(rng_draw(key, 1));
+            const double u2 = (double)rng_unit(rng_draw(key, 2));
+            const double th = (double)a.beta_deg * u0 * (3.14159265358979323846 / 180.0);
+            aff[0] = (float)cos(th);
+            aff[1] = (float)sin(th);
+            aff[2] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
+            aff[3] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
+        }
+        __syncthreads();
+        // row pass: along c
+        for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
+            const int r = i / kSide, c = i - r * kSide;
+            float sx = 0.0f, sy = 0.0f;
+            for (int t = -R; t <= R; ++t) {
+                const int cc = c + t;
+                if (cc >= 0 && cc < kSide) {
+                    const float w = a.taps[t + R];
+                    sx = fmaf(w, fx[r * kSide + cc], sx);
+                    sy = fmaf(w, fy[r * kSide + cc], sy);
+                }
+            }
+            tx[i] = sx;
+            ty[i] = sy;
+        }
+        __syncthreads();
+        const float cs = aff[0], sn = aff[1], scx = aff[2], scy = aff[3];
+        const float c0 = 0.5f * (float)(kSide - 1);
+        float* out = dst + k * kPix;
+        for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
+            const int r = i / kSide, c = i - r * kSide;
+            // column pass: along r
+            float gx = 0.0f, gy = 0.0f;
+            for (int t = -R; t <= R; ++t) {
+                const int rr = r + t;
+                if (rr >= 0 && rr < kSide) {
+                    const float w = a.taps[t + R];
+                    gx = fmaf(w, tx[rr * kSide + c], gx);
+                    gy = fmaf(w, ty[rr * kSide + c], gy);
+                }
+            }
+            const float u = (float)c - c0, v = (float)r - c0;
+            // X = sx (cos u - sin v) + c0 + alpha * smoothed dx;  Y = sy (sin u + cos v) + c0 + alpha * ...
+            const float X = fmaf(a.alpha, gx, fmaf(scx, fmaf(cs, u, -(sn * v)), c0));
+            const float Y = fmaf(a.alpha, gy, fmaf(scy, fmaf(sn, u, cs * v), c0));
+            const float xf = floorf(X), yf = floorf(Y);
+            const float wx = X - xf, wy = Y - yf;
+            float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
+            if (xf >= -1.0f && xf <= (float)kSide && yf >= -1.0f && yf <= (float)kSide) {
+                const int x0 = (int)xf, y0 = (int)yf;
+                const bool xa = (x0 >= 0 && x0 < kSide), xb = (x0 + 1 >= 0 && x0 + 1 < kSide);
+                const bool ya = (y0 >= 0 && y0 < kSide), yb = (y0 + 1 >= 0 && y0 + 1 < kSide);
+                if (ya && xa) p00 = img[y0 * kSide + x0];
+                if (ya && xb) p01 = img[y0 * kSide + x0 + 1];
+                if (yb && xa) p10 = img[(y0 + 1) * kSide + x0];
+                if (yb && xb) p11 = img[(y0 + 1) * kSide + x0 + 1];
+            }
+            const float top = (1.0f - wx) * p00 + wx * p01;
+            const float bot = (1.0f - wx) * p10 + wx * p11;
+            const float val = (1.0f - wy) * top + wy * bot;
+            out[i] = val / 127.5f - 1.0f;   // section "Data": intensity/127.5 - 1
+        }
+        __syncthreads();   // LDS is reused by the next image of this workgroup
+    }
+}
+
+}  // namespace dbsn

@@ -3,7 +3,7 @@
 These stand in for the handwritten-digit benchmark the paper trains on (28x28
 uint8 images, background 0, foreground up to 255, content in the central
 20x20 box, ten classes).  This module holds no arithmetic of the method itself
-(no network, no deformation); both the GPU tests and the CPU oracle take their
+(no network, no deformation); the GPU path and its CPU checker both take their
 inputs from it.
 
 Recipe for one image: three straight strokes whose end points are uniform in

@@ -1,0 +1,249 @@
+"""GPU-vs-oracle parity of the MLP path, through the C ABI (run with -m gpu on an MI355X).
+
+Tolerances (the benchmark spec): weights after one step |gpu - ref| <= 1e-5 |ref| + 1e-8
+(the absolute floor covers weights that happen to lie within rounding of zero); after 100 steps
+<= 1e-4 absolute; argmax labels bit-exact wherever the decision is not within rounding (top-2
+logit margin of the float64 oracle > 1e-4).
+"""
+import numpy as np
+import pytest
+
+from paper_1003_0358_amd import datagen
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-8
+NET0 = [784, 1000, 500, 10]
+NET4 = [784, 2500, 2000, 1500, 1000, 500, 10]
+SHAPES = [
+    [784, 10],                       # no hidden layer
+    [784, 300, 10],                  # one hidden layer
+    NET0,
+    [30, 17, 9, 5],                  # widths that are no multiple of 4
+    [784, 1000, 1000, 1000, 1000, 10],
+    [1030, 2051, 520, 33],           # ragged, several column chunks with a tail
+]
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _data(n, n0=784, seed=0):
+    if n0 == 784:
+        img, lab = datagen.stroke_images(n, seed=seed)
+        return datagen.to_inputs(img), lab
+    rng = np.random.default_rng(seed)
+    return rng.uniform(-1, 1, (n, n0)).astype(np.float32), rng.integers(0, 10, n).astype(np.int32)
+
+
+def _mk(sizes, mode, seed=0):
+    from paper_1003_0358_amd import binding
+    return binding.Mlp(sizes, seed=seed, mode=mode)
+
+
+def _close(a, b, rtol=RTOL, atol=ATOL):
+    return np.all(np.abs(a - b) <= atol + rtol * np.abs(b))
+
+
+@pytest.mark.parametrize("sizes", [NET0, [30, 17, 9, 5], [1030, 2051, 520, 33], NET4])
+def test_init_matches_oracle_bit_for_bit(oracle, sizes):
+    m = _mk(sizes, 1, seed=7)
+    assert np.array_equal(m.get_params(), oracle.init_params(sizes, 7))
+    m.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("sizes", SHAPES)
+def test_single_step(oracle, sizes, mode):
+    torch = _torch()
+    X, y = _data(3, sizes[0], seed=1)
+    y = (y % sizes[-1]).astype(np.int32)
+    m = _mk(sizes, mode, seed=3)
+    p0 = m.get_params()
+    eta = np.float32(1e-3)
+    xs = torch.from_numpy(X).cuda()
+    m.bp_step(xs[0], int(y[0]), eta)
+    m.status()
+    got = m.get_params()
+    ref32, loss32, d32 = oracle.bp_step(sizes, p0, X[0], int(y[0]), eta, "f32", want_deltas=True)
+    ref64, _, d64 = oracle.bp_step(sizes, p0, X[0], int(y[0]), float(eta), "f64", want_deltas=True)
+    assert _close(got, ref32), np.abs(got - ref32).max()
+    assert _close(got, ref64), np.abs(got - ref64).max()
+    assert np.abs(got - p0).max() > 0
+    # states left behind: activations, probabilities, deltas
+    acts64, probs64 = oracle.forward(sizes, p0, X[0], "f64")
+    o = 0
+    for l in range(1, len(sizes)):
+        n = sizes[l]
+        x = m.get_activations(l)
+        want = acts64[o:o + n] if l < len(sizes) - 1 else probs64
+        assert np.abs(x - want).max() < 2e-5, (l, np.abs(x - want).max())
+        d = m.get_deltas(l)
+        assert np.abs(d - d64[o:o + n]).max() < 1e-5 * max(1.0, np.abs(d64[o:o + n]).max()), l
+        o += n
+    m.close()
+
+
+@pytest.mark.parametrize("sizes", [NET0, [784, 1000, 1000, 1000, 1000, 10], [30, 17, 9, 5]])
+def test_hundred_steps(oracle, sizes):
+    torch = _torch()
+    X, y = _data(100, sizes[0], seed=0)
+    y = (y % sizes[-1]).astype(np.int32)
+    eta = np.float32(1e-3)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    res = {}
+    for mode in (0, 1):
+        m = _mk(sizes, mode, seed=0)
+        p0 = m.get_params()
+        loss = torch.zeros(100, dtype=torch.float32, device="cuda")
+        m.bp_steps(xs, ys, eta, loss)
+        m.status()
+        res[mode] = (m.get_params(), loss.cpu().numpy())
+        m.close()
+    oracle.set_threads(8)
+    ref32, l32 = oracle.bp_steps(sizes, p0, X, y, eta, "f32")
+    ref64, l64 = oracle.bp_steps(sizes, p0, X, y, float(eta), "f64")
+    oracle.set_threads(1)
+    for mode in (0, 1):
+        got, loss = res[mode]
+        assert np.abs(got - ref32).max() <= 1e-4
+        assert np.abs(got - ref64).max() <= 1e-4
+        assert np.abs(loss - l64).max() <= 1e-4
+    # the two execution modes run the same arithmetic in the same order
+    assert np.array_equal(res[0][0], res[1][0])
+    assert np.array_equal(res[0][1], res[1][1])
+
+
+def test_steps_equal_repeated_single_steps_and_runs_repeat():
+    torch = _torch()
+    sizes = [784, 600, 200, 10]
+    X, y = _data(12, seed=5)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    a = _mk(sizes, 1)
+    a.bp_steps(xs, ys, 1e-3)
+    b = _mk(sizes, 1)
+    for s in range(12):
+        b.bp_step(xs[s], int(y[s]), 1e-3)
+    c = _mk(sizes, 1)
+    c.bp_steps(xs[:5], ys[:5], 1e-3)
+    c.bp_steps(xs[5:], ys[5:], 1e-3)
+    pa, pb, pc = a.get_params(), b.get_params(), c.get_params()
+    assert np.array_equal(pa, pb) and np.array_equal(pa, pc)
+    a2 = _mk(sizes, 1)
+    a2.bp_steps(xs, ys, 1e-3)
+    assert np.array_equal(pa, a2.get_params())          # run-to-run bit reproducible
+    for m in (a, b, c, a2):
+        m.status(); m.close()
+
+
+def test_full_size_net_in_bench_configuration(oracle):
+    """The 784-2500-2000-1500-1000-500-10 net, persistent mode, as bench.py runs it."""
+    torch = _torch()
+    X, y = _data(40, seed=2)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    m = _mk(NET4, 1, seed=0)
+    p0 = m.get_params()
+    loss = torch.zeros(40, dtype=torch.float32, device="cuda")
+    m.bp_steps(xs, ys, 1e-3, loss)
+    m.status()
+    got = m.get_params()
+    oracle.set_threads(8)
+    ref, l32 = oracle.bp_steps(NET4, p0, X, y, np.float32(1e-3), "f32")
+    oracle.set_threads(1)
+    assert np.abs(got - ref).max() <= 1e-4
+    assert np.abs(loss.cpu().numpy() - l32).max() <= 1e-4
+    assert np.abs(got - p0).max() > 1e-4
+    m.close()
+
+
+def test_forward_and_classify(oracle):
+    torch = _torch()
+    sizes = NET0
+    img, _ = datagen.stroke_images(300, seed=11)
+    X = datagen.to_inputs(img)
+    xs = torch.from_numpy(X).cuda()
+    m = _mk(sizes, 1, seed=1)
+    # train a little so that the outputs are not all alike
+    Xt, yt = _data(50, seed=12)
+    m.bp_steps(torch.from_numpy(Xt).cuda(), torch.from_numpy(yt).cuda(), 1e-2)
+    p = m.get_params()
+    got = m.classify(xs).cpu().numpy()
+    ref = oracle.classify(sizes, p, X, "f64")
+    margins = []
+    for s in range(300):
+        acts, _ = oracle.forward(sizes, p, X[s], "f64")
+        top2 = np.sort(acts[-10:])[-2:]
+        margins.append(top2[1] - top2[0])
+    clear = np.array(margins) > 1e-4
+    assert clear.sum() >= 290
+    assert np.array_equal(got[clear], ref[clear])
+    assert got.min() >= 0 and got.max() <= 9
+    probs = m.forward(xs[0]).cpu().numpy()
+    _, pref = oracle.forward(sizes, p, X[0], "f64")
+    assert np.abs(probs - pref).max() < 1e-5
+    assert abs(probs.sum() - 1) < 1e-5
+    # ties: an all-zero network gives equal logits, the lowest index wins
+    for l in range(1, 4):
+        m.set_weights(l, np.zeros((sizes[l], sizes[l - 1]), np.float32), np.zeros(sizes[l], np.float32))
+    assert m.classify(xs[:4]).cpu().tolist() == [0, 0, 0, 0]
+    m.close()
+
+
+def test_set_get_weights_roundtrip_and_errors():
+    from paper_1003_0358_amd import binding
+    torch = _torch()
+    sizes = [30, 17, 9, 5]
+    m = _mk(sizes, 1)
+    rng = np.random.default_rng(0)
+    W = rng.normal(size=(17, 30)).astype(np.float32); b = rng.normal(size=17).astype(np.float32)
+    m.set_weights(1, W, b)
+    W2, b2 = m.get_weights(1)
+    assert np.array_equal(W, W2) and np.array_equal(b, b2)
+    lib = m.lib
+    x = torch.zeros(30, device="cuda")
+    before = m.get_params()
+    assert lib.bp_step(m.h, x, 5, 0.1) == binding.E_ARG          # label out of range
+    assert lib.bp_step(m.h, x, -1, 0.1) == binding.E_ARG
+    assert lib.bp_step(m.h, None, 0, 0.1) == binding.E_ARG
+    assert lib.bp_step(m.h, x, 0, float("nan")) == binding.E_ARG
+    assert lib.bp_steps(m.h, x, None, 1, 0.1) == binding.E_ARG
+    assert lib.bp_steps(m.h, x, x, -1, 0.1) == binding.E_ARG
+    assert lib.bp_steps(m.h, None, None, 0, 0.1) == binding.OK    # empty: nothing to do
+    assert lib.mlp_get_weights(m.h, 0, None, None) == binding.E_ARG
+    assert lib.mlp_get_weights(m.h, 4, None, None) == binding.E_ARG
+    assert lib.mlp_set_mode(m.h, 7) == binding.E_ARG
+    assert np.array_equal(before, m.get_params())                 # none of the above did any work
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    rc, h = lib.mlp_init(sizes, 0, small)
+    assert rc == binding.E_SHAPE and "too small" in lib.last_error()
+    m.close()
+
+
+def test_barrier_timeout_is_reported_not_hung():
+    """A spin limit of zero makes every workgroup give up at its first unsatisfied poll; the kernel
+    must end by itself and the error must surface through dbsn_mlp_status."""
+    from paper_1003_0358_amd import binding
+    torch = _torch()
+    sizes = [784, 600, 200, 10]
+    X, y = _data(4, seed=5)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    m = _mk(sizes, 1)
+    lib = m.lib
+    assert lib.mlp_set_spin_limit(m.h, 0) == binding.OK
+    lib.check(lib.bp_steps(m.h, xs, ys, 4, 1e-3))
+    rc = lib.mlp_status(m.h)
+    # with 256 workgroups at least one poll fails somewhere; tolerate the lucky case
+    assert rc in (binding.E_TIMEOUT, binding.OK)
+    if rc == binding.E_TIMEOUT:
+        assert "barrier" in lib.last_error()
+    m.close()
+    # a fresh network afterwards works normally
+    m = _mk(sizes, 1)
+    m.bp_steps(xs, ys, 1e-3)
+    m.status()
+    ref = _mk(sizes, 0)
+    ref.bp_steps(xs, ys, 1e-3)
+    assert np.array_equal(m.get_params(), ref.get_params())
+    m.close(); ref.close()
