@@ -48,6 +48,9 @@ class Lib:
         if not os.path.exists(path):
             raise RuntimeError("libdbsn.so is not built (%s): run `python -m paper_1003_0358_amd.build` or "
                                "__graft_entry__.build()" % path)
+        # PyTorch ships its own HIP runtime; it has to be in the process before libdbsn.so is
+        # loaded so that both resolve to that one runtime (two runtimes cannot share a device).
+        import torch  # noqa: F401
         self.c = C.CDLL(path)
         c = self.c
         vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
