@@ -33,7 +33,7 @@ extern "C" {
 #define DBSN_E_ARG      -1   /* null pointer, negative count, label or layer out of range, ...      */
 #define DBSN_E_SHAPE    -2   /* unsupported shape, misaligned pointer, arena too small               */
 #define DBSN_E_HIP      -3   /* a HIP runtime call failed                                            */
-#define DBSN_E_TIMEOUT  -4   /* the in-kernel grid barrier gave up waiting (reported by _status)     */
+#define DBSN_E_TIMEOUT  -4   /* a wait inside the persistent kernel gave up (reported by _status)   */
 
 #define DBSN_MAX_LAYERS  16     /* weight layers (n_sizes - 1)                                        */
 #define DBSN_MAX_WIDTH   4096   /* neurons in any layer, inputs included                              */
@@ -57,9 +57,12 @@ typedef struct {
     int32_t ktaps;
 } dbsn_deform_params;
 
-/* Execution mode of dbsn_bp_steps / dbsn_bp_step (results are identical bit for bit):
- * 0: one kernel launch per layer phase;  1: one persistent kernel per call, layer phases
- * separated by an in-kernel grid barrier (default). */
+/* Execution mode of dbsn_bp_steps / dbsn_bp_step.  0: one kernel launch per layer phase;
+ * 1 (default): one persistent kernel per call, whose workgroups hand partial sums to each other
+ * through tagged words in device memory.  Both compute the same step; they add partial sums in
+ * different (each fixed) orders, so results agree to rounding, and each mode is bit-reproducible
+ * from run to run.  Shapes the persistent kernel does not hold (no hidden layer, an output layer
+ * of more than 12288 weights) run in mode 0 whatever is selected. */
 #define DBSN_MODE_LAUNCHES   0
 #define DBSN_MODE_PERSISTENT 1
 
@@ -94,12 +97,13 @@ int32_t dbsn_mlp_get_deltas(dbsn_mlp* mlp, int32_t layer, float* d_host);
 /* Select DBSN_MODE_*.  */
 int32_t dbsn_mlp_set_mode(dbsn_mlp* mlp, int32_t mode);
 
-/* Polls a workgroup may spend in one grid barrier before it gives up (default 2^24, seconds of
- * waiting).  Exists so that the time-out path can be exercised from the host. */
+/* Polls a workgroup of the persistent kernel may spend waiting for one set of partial sums before
+ * it gives up (default 2^22, seconds of waiting).  Exists so that the time-out path can be
+ * exercised from the host. */
 int32_t dbsn_mlp_set_spin_limit(dbsn_mlp* mlp, uint32_t polls);
 
-/* Synchronise the network's stream and report deferred errors: DBSN_E_TIMEOUT if a grid barrier
- * of a persistent kernel gave up (the weights are then undefined), DBSN_E_HIP for a failed launch. */
+/* Synchronise the network's stream and report deferred errors: DBSN_E_TIMEOUT if a wait inside a
+ * persistent kernel gave up (the weights are then undefined), DBSN_E_HIP for a failed launch. */
 int32_t dbsn_mlp_status(dbsn_mlp* mlp);
 
 /* Deform n images (section "Deforming images ...", appendix "Deformations"): for image k, all

@@ -14,6 +14,7 @@
 
 #include "dbsn_deform_kernels.h"
 #include "dbsn_mlp_kernels.h"
+#include "dbsn_persistent_kernel.h"
 
 using namespace dbsn;
 
@@ -50,8 +51,12 @@ bool shape_ok(const int32_t* sizes, int32_t n_sizes) {
 
 struct ArenaPlan {
     size_t W[kMaxLayers + 1], b[kMaxLayers + 1], x[kMaxLayers + 1], d[kMaxLayers + 1];
+    size_t yp[kMaxLayers + 1], gp[kMaxLayers + 1];
     size_t gpart[2], flags, total;
     int ld[kMaxLayers + 1], gld;
+    // tile geometry of the persistent kernel (hidden layers 1 .. L-1), fixed for kPGroups workgroups
+    int nCB[kMaxLayers + 1], nRB[kMaxLayers + 1], C[kMaxLayers + 1], R[kMaxLayers + 1];
+    bool persistent_ok;
 };
 
 ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
@@ -73,6 +78,36 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         off = align_up(off + sizeof(float) * (size_t)kArenaGroups * p.gld);
     }
     p.flags = off; off = align_up(off + 256);
+
+    // Persistent kernel: layer l is cut into nRB x nCB tiles of R rows x C <= 256 columns, one per
+    // workgroup; yp_l holds the forward partial sums [2][nCB][n_l], gp_l the backward ones
+    // [2][nRB_{l+1}][n_l], as 64-bit {tag, float} words.
+    const int L = n_sizes - 1;
+    p.persistent_ok = (L >= 2);
+    for (int l = 1; l < L; ++l) {
+        const int nin = sizes[l - 1], nout = sizes[l];
+        p.nCB[l] = (nin + 255) / 256;
+        p.C[l] = ((nin + p.nCB[l] - 1) / p.nCB[l] + 3) / 4 * 4;
+        const int rb_max = kPGroups / p.nCB[l];
+        p.R[l] = (nout + rb_max - 1) / rb_max;
+        p.nRB[l] = (nout + p.R[l] - 1) / p.R[l];
+        if (p.R[l] > 256 || p.C[l] > 256) p.persistent_ok = false;
+    }
+    for (int l = 1; l < L; ++l) {
+        p.yp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nCB[l] * sizes[l]);
+        if (l <= L - 2) {
+            p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l + 1] * sizes[l]);
+            // the staging area holds the gp and the yp partials of a tile's rows side by side
+            if (p.nRB[l + 1] * p.R[l] > kStageFloats / 2 || p.nCB[l] * p.R[l] > kStageFloats / 2)
+                p.persistent_ok = false;
+        }
+        if (l >= 2 && p.nCB[l - 1] * p.C[l] > kStageFloats) p.persistent_ok = false;
+    }
+    if (L >= 2) {
+        if ((size_t)sizes[L] * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax ||
+            p.nCB[L - 1] * sizes[L - 1] > kStageFloats)
+            p.persistent_ok = false;
+    }
     p.total = off;
     return p;
 }
@@ -85,12 +120,14 @@ struct dbsn_mlp {
     ArenaPlan plan{};
     char* arena = nullptr;
     hipStream_t stream = nullptr;
+    PNet pnet{};
     int mode = DBSN_MODE_PERSISTENT;
-    int maxnch = 0;
-    unsigned bar_base = 0;
+    uint64_t epoch = 0;        // steps run by the persistent kernel so far (its tags continue from here)
     int device = 0;
+    int cus = 0;
     size_t lds_limit = 0;
     bool persistent_ready = false;
+    int* err = nullptr;
 };
 
 namespace {
@@ -157,50 +194,30 @@ int32_t steps_launches(dbsn_mlp* m, const float* samples, const int* labels, int
     return DBSN_OK;
 }
 
-template <int MAXNCH>
-int32_t launch_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n,
-                          float eta, float* loss) {
-    const size_t lds = sizeof(float) * (size_t)phase_lds_floats(MAXNCH);
-    const void* fn = reinterpret_cast<const void*>(&k_bp_persistent<MAXNCH>);
-    if (lds > m->lds_limit) return fail(DBSN_E_SHAPE, "layer too wide for this device's LDS (%zu B needed)", lds);
+// One cooperative launch (all kPGroups workgroups resident together) runs the n steps.
+int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n, float eta,
+                         float* loss) {
+    const size_t lds = sizeof(float) * (size_t)PLds::total;
+    const void* fn = reinterpret_cast<const void*>(&k_bp_dataflow);
     if (!m->persistent_ready) {
-        if (lds > 64 * 1024) HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (lds > m->lds_limit) return fail(DBSN_E_SHAPE, "persistent kernel needs %zu B of LDS", lds);
+        HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         int per_cu = 0;
         HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, lds));
-        if (per_cu < 1) return fail(DBSN_E_SHAPE, "persistent kernel does not fit on a compute unit");
+        if (per_cu * m->cus < kPGroups)
+            return fail(DBSN_E_SHAPE, "device cannot hold %d resident workgroups", kPGroups);
         m->persistent_ready = true;
     }
-    Net net = m->net;
+    PNet net = m->pnet;
     long long nn = n;
-    unsigned base = m->bar_base;
+    unsigned base = (unsigned)m->epoch;
     void* args[] = {&net, &samples, &labels, &label_val, &nn, &eta, &loss, &base};
-    HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(net.G), dim3(kThreads), args, (unsigned)lds, m->stream));
-    // barriers passed by every workgroup in this launch
-    const int L = net.L;
-    const unsigned per_step = (L >= 2) ? (unsigned)((L - 1) + (L >= 3 ? L - 2 : 1)) : 0u;
-    m->bar_base = base + (unsigned)net.G * per_step * (unsigned)n;
+    HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, m->stream));
+    m->epoch += (uint64_t)n;
     return DBSN_OK;
 }
 
-int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n, float eta,
-                         float* loss) {
-    // keep the barrier counter far from wrapping inside one launch
-    const int64_t chunk = 1 << 16;
-    for (int64_t a = 0; a < n; a += chunk) {
-        const int64_t c = (n - a < chunk) ? n - a : chunk;
-        const float* sp = samples + a * m->sizes[0];
-        const int* lp = labels ? labels + a : nullptr;
-        float* ls = loss ? loss + a : nullptr;
-        int32_t rc;
-        if (m->maxnch <= 4) rc = launch_persistent<4>(m, sp, lp, label_val, c, eta, ls);
-        else if (m->maxnch <= 8) rc = launch_persistent<8>(m, sp, lp, label_val, c, eta, ls);
-        else if (m->maxnch <= 10) rc = launch_persistent<10>(m, sp, lp, label_val, c, eta, ls);
-        else if (m->maxnch <= 12) rc = launch_persistent<12>(m, sp, lp, label_val, c, eta, ls);
-        else rc = launch_persistent<16>(m, sp, lp, label_val, c, eta, ls);
-        if (rc) return rc;
-    }
-    return DBSN_OK;
-}
+bool use_persistent(const dbsn_mlp* m) { return m->mode == DBSN_MODE_PERSISTENT && m->plan.persistent_ok; }
 
 int32_t check_mlp(dbsn_mlp* m) { return m ? DBSN_OK : fail(DBSN_E_ARG, "null network handle"); }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -242,6 +259,7 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         return fail(DBSN_E_HIP, "no usable HIP device: %s", hipGetErrorString(e));
     }
     m->lds_limit = prop.sharedMemPerBlock;
+    m->cus = prop.multiProcessorCount;
     int G = prop.multiProcessorCount;  // one workgroup per compute unit
     if (G > kArenaGroups) G = kArenaGroups;
     int maxw = 0;
@@ -254,7 +272,6 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     net.L = n_sizes - 1;
     net.G = G;
     net.gld = plan.gld;
-    net.spin_limit = 1u << 24;
     for (int l = 1; l <= net.L; ++l) {
         Layer& Ly = net.lay[l];
         Ly.W = reinterpret_cast<float*>(m->arena + plan.W[l]);
@@ -265,14 +282,29 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         Ly.n_out = sizes[l];
         Ly.ld = plan.ld[l];
         Ly.nch = nch_for(Ly.ld);
-        if (l < net.L && Ly.nch > m->maxnch) m->maxnch = Ly.nch;
     }
-    // the output layer's input vector is staged whole in the phase buffer as well
-    if (net.L >= 1 && nch_for(net.lay[net.L].ld) > m->maxnch) m->maxnch = nch_for(net.lay[net.L].ld);
     net.gpart[0] = reinterpret_cast<float*>(m->arena + plan.gpart[0]);
     net.gpart[1] = reinterpret_cast<float*>(m->arena + plan.gpart[1]);
-    net.bar = reinterpret_cast<unsigned*>(m->arena + plan.flags);
-    net.err = reinterpret_cast<int*>(m->arena + plan.flags + 64);
+    m->err = reinterpret_cast<int*>(m->arena + plan.flags);
+
+    PNet& pn = m->pnet;
+    pn.L = net.L;
+    pn.err = m->err;
+    pn.spin_limit = 1u << 22;
+    for (int l = 1; l <= net.L; ++l) {
+        PLayer& P = pn.lay[l];
+        const Layer& Ly = net.lay[l];
+        P.W = Ly.W; P.b = Ly.b; P.x = Ly.x; P.d = Ly.d;
+        P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
+        if (l < net.L && plan.persistent_ok) {
+            P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
+            P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
+            if (l <= net.L - 2) {
+                P.gp = reinterpret_cast<u64*>(m->arena + plan.gp[l]);
+                P.gP = plan.nRB[l + 1];
+            }
+        }
+    }
 
     // everything that is not a weight starts at zero
     e = hipMemsetAsync(m->arena, 0, plan.total, m->stream);
@@ -312,7 +344,7 @@ int32_t dbsn_mlp_set_mode(dbsn_mlp* m, int32_t mode) {
 
 int32_t dbsn_mlp_set_spin_limit(dbsn_mlp* m, uint32_t polls) {
     if (check_mlp(m)) return DBSN_E_ARG;
-    m->net.spin_limit = polls;
+    m->pnet.spin_limit = polls;
     return DBSN_OK;
 }
 
@@ -320,12 +352,12 @@ int32_t dbsn_mlp_status(dbsn_mlp* m) {
     if (check_mlp(m)) return DBSN_E_ARG;
     HIP_TRY(hipStreamSynchronize(m->stream));
     int err = 0;
-    HIP_TRY(hipMemcpy(&err, m->net.err, sizeof err, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(&err, m->err, sizeof err, hipMemcpyDeviceToHost));
     if (err) {
-        // leave the barrier in a clean state for the next launch
-        HIP_TRY(hipMemset(m->net.bar, 0, 128));
-        m->bar_base = 0;
-        return fail(DBSN_E_TIMEOUT, "a grid barrier gave up waiting; weights are undefined");
+        HIP_TRY(hipMemset(m->err, 0, sizeof(int)));
+        // stale partial sums of the abandoned steps must never match a later step's tag
+        m->epoch += (uint64_t)1 << 20;
+        return fail(DBSN_E_TIMEOUT, "a wait inside the persistent kernel gave up; weights are undefined");
     }
     return DBSN_OK;
 }
@@ -381,7 +413,7 @@ int32_t dbsn_bp_steps(dbsn_mlp* m, const float* samples_dev, const int32_t* labe
     if (!aligned(samples_dev, 4) || !aligned(labels_dev, 4) || !aligned(loss_dev, 4))
         return fail(DBSN_E_SHAPE, "misaligned pointer");
     if (!std::isfinite(eta)) return fail(DBSN_E_ARG, "eta is not finite");
-    if (m->mode == DBSN_MODE_PERSISTENT) return steps_persistent(m, samples_dev, labels_dev, 0, n, eta, loss_dev);
+    if (use_persistent(m)) return steps_persistent(m, samples_dev, labels_dev, 0, n, eta, loss_dev);
     return steps_launches(m, samples_dev, labels_dev, 0, n, eta, loss_dev);
 }
 
@@ -392,7 +424,7 @@ int32_t dbsn_bp_step(dbsn_mlp* m, const float* sample_dev, int32_t label, float 
     if (label < 0 || label >= m->sizes.back())
         return fail(DBSN_E_ARG, "label %d out of range 0..%d", label, m->sizes.back() - 1);
     if (!std::isfinite(eta)) return fail(DBSN_E_ARG, "eta is not finite");
-    if (m->mode == DBSN_MODE_PERSISTENT) return steps_persistent(m, sample_dev, nullptr, label, 1, eta, nullptr);
+    if (use_persistent(m)) return steps_persistent(m, sample_dev, nullptr, label, 1, eta, nullptr);
     return steps_launches(m, sample_dev, nullptr, label, 1, eta, nullptr);
 }
 

@@ -1,5 +1,6 @@
 // MLP kernels of libdbsn for gfx950: forward mat-vec + activation, fused backward
-// (W^T delta + rank-1 update in one sweep), output layer, and the persistent per-call kernel.
+// (W^T delta + rank-1 update in one sweep) and output layer, one launch per layer phase.  (The
+// persistent kernel that runs whole calls in one launch is in dbsn_persistent_kernel.h.)
 //
 // Layout.  Layer l (1..L) keeps W_l output-major: row j = the n_{l-1} incoming weights of
 // neuron j, rows padded to `ld` (a multiple of 4 floats, so every row starts 16-byte aligned and
@@ -40,10 +41,7 @@ struct Layer {
 struct Net {
     Layer lay[kMaxLayers + 1];  // 1 .. L
     float* gpart[2];            // partial W^T delta rows, [G][gld] each; layer l reads gpart[l & 1]
-    unsigned* bar;              // grid barrier counter
-    int* err;                   // set to 1 when a barrier gave up
     int L, G, gld;
-    unsigned spin_limit;
 };
 
 __device__ inline float wave_sum(float v) {
@@ -239,20 +237,6 @@ __device__ void top_phase(const Layer& Ly, const float* __restrict__ xin, int la
     __syncthreads();
 }
 
-// The rank-1 update of W_L on its own (same arithmetic as inside top_phase), for the persistent
-// kernel, where it has to wait until every workgroup has read the old W_L.
-__device__ void top_update(const Layer& Ly, const float* __restrict__ xin, float eta, const float* dL) {
-    const int n_in = Ly.n_in, n_out = Ly.n_out, ld = Ly.ld;
-    for (int i = threadIdx.x; i < n_in; i += kThreads) {
-        const float xi = xin[i];
-        for (int j = 0; j < n_out; ++j) {
-            const float w = Ly.W[(size_t)j * ld + i];
-            Ly.W[(size_t)j * ld + i] = fmaf(-(eta * dL[j]), xi, w);
-        }
-    }
-    if (threadIdx.x < n_out) Ly.b[threadIdx.x] -= eta * dL[threadIdx.x];
-}
-
 #define DBSN_NCH_SWITCH(MAXNCH, nch, CALL)                          \
     switch (nch) {                                                  \
         case 1:  { constexpr int N = 1;  CALL; } break;             \
@@ -306,83 +290,6 @@ __global__ __launch_bounds__(kThreads) void k_bwd(Net net, int l, const float* x
     const int P = (l == net.L - 1) ? 1 : net.G;  // the output layer leaves a single row
     float* gdst = (l > 1) ? net.gpart[(l - 1) & 1] + (size_t)blockIdx.x * net.gld : nullptr;
     bwd_phase<NCH>(net.lay[l], xin, eta, net.gpart[l & 1], P, net.gld, gdst, lds, blockIdx.x, gridDim.x);
-}
-
-// ---- persistent kernel (DBSN_MODE_PERSISTENT) ---------------------------------------------
-
-// Grid barrier on a monotonically increasing counter.  Every workgroup of the (co-resident) grid
-// adds 1 and waits until the counter has reached `target`.  The wait is bounded: after
-// spin_limit polls the workgroup raises net.err and the kernel winds down.
-__device__ inline bool grid_barrier(const Net& net, unsigned target, int* flag) {
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(net.bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned spins = 0;
-        int ok = 1;
-        while ((int)(__hip_atomic_load(net.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins > net.spin_limit) { ok = 0; break; }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        if (!ok) __hip_atomic_store(net.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = ok;
-    }
-    __syncthreads();
-    return *flag != 0;
-}
-
-// n on-line BP steps in one launch.  Per sample: forward phases 1 .. L-1, each followed by a grid
-// barrier; the small output layer is then evaluated by EVERY workgroup on its own (same code, same
-// inputs, hence the same bits), which gives each the deltas it needs without a barrier; backward
-// phases L-1 .. 1 follow, with a barrier after each but the last.  Workgroup 0 alone publishes the
-// output layer's results and applies its update, after the first backward barrier, when nobody
-// reads the old W_L any more.
-template <int MAXNCH>
-__global__ __launch_bounds__(kThreads) void k_bp_persistent(Net net, const float* samples, const int* labels,
-                                                             int label_val, long long n, float eta,
-                                                             float* loss_out, unsigned bar_base) {
-    extern __shared__ float lds[];
-    const int g = blockIdx.x, G = gridDim.x, L = net.L;
-    float* top = lds + phase_lds_floats(MAXNCH) - 2 * kMaxClasses - 16;
-    int* flag = reinterpret_cast<int*>(top + 2 * kMaxClasses);
-    float* gtop = lds + MAXNCH * 256 + kMaxRowsPerGroup;  // aliases the reduction buffer of bwd_phase
-    const int n0 = net.lay[1].n_in;
-    unsigned target = bar_base;
-    for (long long s = 0; s < n; ++s) {
-        const float* x0 = samples + s * n0;
-        for (int l = 1; l < L; ++l) {
-            const float* xin = (l == 1) ? x0 : net.lay[l - 1].x;
-            DBSN_NCH_SWITCH(MAXNCH, net.lay[l].nch, fwd_phase<N>(net.lay[l], xin, lds, g, G));
-            target += G;
-            if (!grid_barrier(net, target, flag)) return;
-        }
-        {
-            const Layer& Ly = net.lay[L];
-            int label = labels ? labels[s] : label_val;
-            label = label < 0 ? 0 : (label >= Ly.n_out ? Ly.n_out - 1 : label);
-            const float* xin = (L == 1) ? x0 : net.lay[L - 1].x;
-            if (L == 1) {
-                if (g == 0) top_phase(Ly, xin, label, eta, true, true, loss_out ? loss_out + s : nullptr, nullptr,
-                                      nullptr, lds, top);
-            } else {
-                top_phase(Ly, xin, label, eta, false, g == 0, loss_out ? loss_out + s : nullptr, nullptr, gtop,
-                          lds, top);
-            }
-        }
-        for (int l = L - 1; l >= 1; --l) {
-            const float* xin = (l == 1) ? x0 : net.lay[l - 1].x;
-            const bool first = (l == L - 1);
-            const float* gsrc = first ? gtop : net.gpart[l & 1];
-            float* gdst = (l > 1) ? net.gpart[(l - 1) & 1] + (size_t)g * net.gld : nullptr;
-            DBSN_NCH_SWITCH(MAXNCH, net.lay[l].nch,
-                            bwd_phase<N>(net.lay[l], xin, eta, gsrc, first ? 1 : G, net.gld, gdst, lds, g, G));
-            if (l > 1 || first) {
-                target += G;
-                if (!grid_barrier(net, target, flag)) return;
-            }
-            if (first && g == 0) top_update(net.lay[L], net.lay[L - 1].x, eta, top + kMaxClasses);
-        }
-    }
 }
 
 // ---- initialisation (section "Architectures": weights uniform in [-0.05, 0.05)) ------------
