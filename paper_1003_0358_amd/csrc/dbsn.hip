@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -56,7 +57,8 @@ struct ArenaPlan {
     int ld[kMaxLayers + 1], gld;
     // tile geometry of the persistent kernel (hidden layers 1 .. L-1), fixed for kPGroups workgroups
     int nCB[kMaxLayers + 1], nRB[kMaxLayers + 1], C[kMaxLayers + 1], R[kMaxLayers + 1];
-    bool persistent_ok;
+    int g0[kMaxLayers + 1], ng[kMaxLayers + 1];   // register groups of each layer's tile
+    bool persistent_ok, stationary;
 };
 
 ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
@@ -102,6 +104,18 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
                 p.persistent_ok = false;
         }
         if (l >= 2 && p.nCB[l - 1] * p.C[l] > kStageFloats) p.persistent_ok = false;
+    }
+    // register groups of 4 rows per wavefront: stationary when every layer gets groups of its own
+    int groups = 0;
+    for (int l = 1; l < L; ++l) {
+        p.ng[l] = ((p.R[l] + kWaves - 1) / kWaves + 3) / 4;
+        if (p.ng[l] > kNG) p.persistent_ok = false;
+        groups += p.ng[l];
+    }
+    p.stationary = groups <= kNG;
+    for (int l = 1, at = 0; l < L; ++l) {
+        p.g0[l] = p.stationary ? at : 0;
+        at += p.ng[l];
     }
     if (L >= 2) {
         if ((size_t)sizes[L] * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax ||
@@ -291,6 +305,10 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     pn.L = net.L;
     pn.err = m->err;
     pn.spin_limit = 1u << 22;
+    pn.backoff = 0;
+    pn.stationary = plan.stationary ? 1 : 0;
+    if (const char* e = getenv("DBSN_BACKOFF")) pn.backoff = atoi(e);
+    if (const char* e = getenv("DBSN_STATIONARY")) pn.stationary = (atoi(e) != 0 && plan.stationary) ? 1 : 0;
     for (int l = 1; l <= net.L; ++l) {
         PLayer& P = pn.lay[l];
         const Layer& Ly = net.lay[l];
@@ -298,6 +316,8 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
         if (l < net.L && plan.persistent_ok) {
             P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
+            P.g0 = pn.stationary ? plan.g0[l] : 0;
+            P.ng = plan.ng[l];
             P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
             if (l <= net.L - 2) {
                 P.gp = reinterpret_cast<u64*>(m->arena + plan.gp[l]);

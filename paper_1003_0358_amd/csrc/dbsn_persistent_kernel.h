@@ -1,18 +1,18 @@
 // Persistent on-line back-propagation kernel of libdbsn for gfx950: n strictly sequential
 // batch-size-1 steps in ONE launch, with no grid barrier and no kernel boundary between layers.
 //
-// Why it looks like this.  A step of the paper's big nets moves 144 MB of weights but is a chain
+// Why it looks like this.  A step of the paper's big nets touches 144 MB of weights but is a chain
 // of 2L dependent mat-vec phases; on this chip a kernel boundary or a grid-wide barrier costs
 // 2-4 us, as much as streaming a whole layer.  So the phases are connected by DATAFLOW instead:
 //
-//  * Every layer l is cut into tiles of R_l rows x C_l <= 256 columns; tile (cb, rb) belongs to
-//    workgroup g = rb * nCB_l + cb for the whole life of the network, forward and backward, so a
-//    weight is only ever touched by one workgroup (plain cached loads and stores, one XCD's L2).
+//  * Every hidden layer l is cut into tiles of R_l rows x C_l <= 256 columns; tile (cb, rb)
+//    belongs to workgroup g = rb * nCB_l + cb for the whole life of the network, forward and
+//    backward, so a weight is only ever touched by one workgroup (plain cached loads and stores).
 //  * What crosses workgroups is small: forward, a tile publishes its R partial dot products
 //    yp_l[cb][rows]; backward, its C partial sums gp_{l-1}[rb][cols] of W^T delta.  Each value
 //    travels as ONE 64-bit word {step tag, float} written with a device-scope atomic store, and a
-//    consumer simply polls the words it needs until they carry the current step's tag: the data
-//    is its own flag.  No fence, no L2 write-back, no counter that 256 workgroups hammer.
+//    consumer polls the words it needs until they carry the current step's tag: the data is its
+//    own flag.  No fence, no L2 write-back, no counter that 256 workgroups hammer.
 //  * A consumer adds the partials in index order (deterministic, bit-reproducible), applies the
 //    activation (forward) or its derivative (backward) itself, and goes on.
 //  * Buffers alternate with the parity of the step tag; the output layer needs all of x_{L-1},
@@ -20,8 +20,14 @@
 //  * The 10 x n_{L-1} output layer lives in every workgroup's LDS; each workgroup evaluates it
 //    and applies the same update to its private copy (same code, same inputs, same bits), so the
 //    deltas of the last hidden layer are available everywhere without communication.
-//  * A wavefront holds all its rows of a tile in registers (one 128-bit load per row and lane,
-//    issued BEFORE the wait for the inputs, so the weight stream overlaps the wait).
+//  * Weights live in REGISTERS.  A wavefront owns rows wave, wave+8, ... of a tile, one 128-bit
+//    register quadruple per row and lane, in groups of four rows.  The 256 workgroups x 8
+//    wavefronts x 36 quadruples hold 75 MB: when all tiles of a workgroup fit (they do for every
+//    net of the paper, 48 MB at most) the weights are loaded once per launch, updated in place
+//    for n steps and written back at the end ("stationary"); the memory system then carries
+//    only the small tagged words, and a step costs its chain of hand-overs, not its bytes.
+//    Otherwise each phase loads its tile into the same registers (the loads are issued before
+//    the wait for the inputs, so they overlap it) and the backward phase stores it back.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,8 +38,23 @@ namespace dbsn {
 
 typedef unsigned long long u64;
 
+// Optional per-phase time stamps for tuning (compiled out unless DBSN_PROFILE is defined).
+#ifdef DBSN_PROFILE
+__device__ unsigned long long* g_prof;     // [steps][slots][workgroups]
+__device__ int g_prof_steps, g_prof_slots;
+#define DBSN_PROF(step, slot)                                                                        \
+    do {                                                                                             \
+        if (threadIdx.x == 0 && (step) < g_prof_steps && (slot) < g_prof_slots)                      \
+            g_prof[((size_t)(step) * g_prof_slots + (slot)) * gridDim.x + blockIdx.x] = wall_clock64(); \
+    } while (0)
+#else
+#define DBSN_PROF(step, slot) do { } while (0)
+#endif
+#define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 4 + (sub))
+
 constexpr int kPGroups = 256;        // workgroups of the persistent kernel (tile geometry is fixed for it)
-constexpr int kKR = 12;              // rows a wavefront keeps in registers at a time
+constexpr int kNG = 9;               // register groups of 4 rows per wavefront
+constexpr int kSlots = 4 * kNG;      // rows a wavefront holds: 36 (a tile has at most 8 * 36 = 288 rows)
 constexpr int kStageFloats = 8192;   // LDS staging for polled partials
 constexpr int kTopWMax = 12288;      // floats of W_L kept in LDS
 constexpr int kTopXMax = 4096;
@@ -45,6 +66,7 @@ struct PLayer {
     int n_in, n_out, ld;
     int nCB, nRB, C, R;
     int gP;           // number of partial rows in gp = nRB of layer l+1
+    int g0, ng;       // register groups [g0, g0 + ng) hold this layer's tile
 };
 
 struct PNet {
@@ -52,6 +74,8 @@ struct PNet {
     int* err;
     int L;
     unsigned spin_limit;
+    int backoff;      // pause between two polls of the same words, in units of 64 clocks
+    int stationary;   // 1: every layer has its own register groups for the whole launch
 };
 
 // LDS map (floats)
@@ -62,9 +86,9 @@ struct PLds {
     static constexpr int dL = logit + kMaxClasses;                // [kMaxClasses]
     static constexpr int xkeep = dL + kMaxClasses;                // [kMaxLayers + 1][256]
     static constexpr int stage = xkeep + (kMaxLayers + 1) * 256;  // [kStageFloats]
-    static constexpr int dl = stage + kStageFloats;               // [256]
-    static constexpr int ysum = dl + 256;                         // [256]
-    static constexpr int gred = ysum + 256;                       // [kWaves][256]
+    static constexpr int dl = stage + kStageFloats;               // [kSlots * kWaves]
+    static constexpr int ysum = dl + kSlots * kWaves;             // [kSlots * kWaves]
+    static constexpr int gred = ysum + kSlots * kWaves;           // [kWaves][256]
     static constexpr int xtop = gred + kWaves * 256;              // [kTopXMax]
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
     static constexpr int total = dtop + kTopXMax;
@@ -72,46 +96,45 @@ struct PLds {
 
 __device__ inline u64 pack_tagged(float v, unsigned tag) { return ((u64)tag << 32) | (u64)__float_as_uint(v); }
 
-// Wait for P x len tagged words src[p * stride + j] (p < P, j < len) of step `tag` and put their
-// float payloads at stage[p * len + j].  Each thread keeps up to 4 loads in flight and re-reads
-// only what was not there yet.  Returns false when the spin limit ran out.
-__device__ inline bool poll_to_lds(const u64* src, int P, int len, size_t stride, unsigned tag, float* stage,
-                                   unsigned limit) {
-    const int total = P * len;
+// Wait for tagged words of step `tag` and put their float payloads into LDS.  The words come from
+// two strided sources that share the row length `len`: srcA[p * stride + j] (p < PA) lands at
+// stage[p * len + j], srcB[p * stride + j] (p < PB) behind them at stage[(PA + p) * len + j]
+// (PB may be 0).  Every thread keeps 4 loads in flight; a wavefront re-reads its words until all
+// of them carry the tag (the loop is wavefront-uniform, so there is no divergent control flow
+// around the loads).  Returns false when the spin limit ran out.
+__device__ inline bool poll_to_lds(const u64* srcA, int PA, const u64* srcB, int PB, int len, size_t stride,
+                                   unsigned tag, float* stage, unsigned limit, int backoff) {
+    const int nA = PA * len, total = nA + PB * len;
     bool ok = true;
-    for (int e0 = threadIdx.x; e0 < total && ok; e0 += kThreads * 4) {
+    for (int base = 0; base < total; base += kThreads * 4) {
         const u64* a[4];
         int e[4];
-        bool need[4];
+        bool valid[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            e[k] = e0 + k * kThreads;
-            need[k] = e[k] < total;
-            const int p = need[k] ? e[k] / len : 0;
-            const int j = need[k] ? e[k] - p * len : 0;
-            a[k] = src + (size_t)p * stride + j;
+            e[k] = base + k * kThreads + (int)threadIdx.x;
+            valid[k] = e[k] < total;
+            const bool inA = e[k] < nA;
+            const int idx = valid[k] ? (inA ? e[k] : e[k] - nA) : 0;
+            const int p = idx / len, j = idx - p * len;
+            a[k] = ((inA || !valid[k]) ? srcA : srcB) + (size_t)p * stride + j;
         }
+        u64 v[4];
         unsigned spins = 0;
         for (;;) {
-            u64 v[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (need[k]) v[k] = __hip_atomic_load(a[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int k = 0; k < 4; ++k) v[k] = __hip_atomic_load(a[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             bool pending = false;
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (need[k]) {
-                    if ((unsigned)(v[k] >> 32) == tag) {
-                        stage[e[k]] = __uint_as_float((unsigned)v[k]);
-                        need[k] = false;
-                    } else {
-                        pending = true;
-                    }
-                }
-            if (!pending) break;
+            for (int k = 0; k < 4; ++k) pending |= valid[k] && ((unsigned)(v[k] >> 32) != tag);
+            if (!__any(pending)) break;
             if (++spins > limit) { ok = false; break; }
-            __builtin_amdgcn_s_sleep(1);
+            for (int z = 0; z < backoff; ++z) __builtin_amdgcn_s_sleep(1);
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (valid[k]) stage[e[k]] = __uint_as_float((unsigned)v[k]);
+        if (!ok) break;
     }
     return ok;
 }
@@ -123,10 +146,54 @@ __device__ inline bool all_ok(bool ok, int* err) {
     return r != 0;
 }
 
+// Cross-lane data movement on the vector ALU (DPP), no LDS traffic.
+template <int CTRL>
+__device__ inline float dpp_mov(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kDppRor8 = 0x128;  // rotate within a row of 16 lanes by 8
+constexpr int kDppRor4 = 0x124;  // ... by 4
+
+// Sum of one value over the 64 lanes, result in every lane.
+__device__ inline float wave_sum_dpp(float v) {
+    v += dpp_mov<kDppXor1>(v);
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppRor4>(v);
+    v += dpp_mov<kDppRor8>(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+// Sums of four values over the 64 lanes at once: two halving steps inside every quad of lanes
+// leave value (t & 3) in lane t, the remaining steps add over the 16 quads.  On return lane t
+// holds the wavefront-wide sum of a[t & 3].  13 vector ops and 2 LDS permutes for 4 rows.
+__device__ inline float wave_sum4(float a0, float a1, float a2, float a3) {
+    const int lane = threadIdx.x & 63;
+    const bool b0 = (lane & 1) != 0, b1 = (lane & 2) != 0;
+    const float s0 = (b0 ? a1 : a0) + dpp_mov<kDppXor1>(b0 ? a0 : a1);
+    const float s1 = (b0 ? a3 : a2) + dpp_mov<kDppXor1>(b0 ? a2 : a3);
+    float v = (b1 ? s1 : s0) + dpp_mov<kDppXor2>(b1 ? s0 : s1);
+    v += dpp_mov<kDppRor4>(v);
+    v += dpp_mov<kDppRor8>(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+__device__ inline float dot4(const float4& w, const float4& x) {
+    float acc = w.x * x.x;
+    acc = fmaf(w.y, x.y, acc);
+    acc = fmaf(w.z, x.z, acc);
+    return fmaf(w.w, x.w, acc);
+}
+
 struct TileCtx {
     int cb, rb, c0, r0, Ceff, Reff;
     bool lane_on;
-    const float* wbase;   // &W[r0][c0 + 4 * lane]
+    float* wbase;   // &W[r0][c0 + 4 * lane]
 };
 
 __device__ inline bool tile_ctx(const PLayer& Ly, int g, TileCtx& t) {
@@ -143,27 +210,49 @@ __device__ inline bool tile_ctx(const PLayer& Ly, int g, TileCtx& t) {
     return true;
 }
 
-// rows [first, first + 8 * kKR) of the tile, dealt round-robin to the 8 wavefronts
-__device__ inline void load_rows(float4 (&w)[kKR], const TileCtx& t, int ld, int first) {
-    const int wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int k = 0; k < kKR; ++k) {
-        const int rl = first + wave + kWaves * k;
-        w[k] = (rl < t.Reff && t.lane_on) ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * ld)
-                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+// Register slot s of group G = g0 + s / 4 holds tile row wave + 8 * s.
+#define DBSN_FOR_LAYER_SLOTS(Ly, BODY)                                  \
+    _Pragma("unroll") for (int G_ = 0; G_ < kNG; ++G_) {                 \
+        if (G_ >= (Ly).g0 && G_ < (Ly).g0 + (Ly).ng) {                   \
+            const int sbase_ = 4 * (G_ - (Ly).g0);                       \
+            BODY                                                         \
+        }                                                                \
     }
+
+__device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const PLayer& Ly, const TileCtx& t) {
+    const int wave = threadIdx.x >> 6;
+    DBSN_FOR_LAYER_SLOTS(Ly, {
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+            const int rl = wave + kWaves * (sbase_ + q);
+            wr[4 * G_ + q] = (rl < t.Reff && t.lane_on)
+                                 ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * Ly.ld)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    })
+}
+
+__device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const PLayer& Ly, const TileCtx& t) {
+    const int wave = threadIdx.x >> 6;
+    DBSN_FOR_LAYER_SLOTS(Ly, {
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+            const int rl = wave + kWaves * (sbase_ + q);
+            if (rl < t.Reff && t.lane_on) *reinterpret_cast<float4*>(t.wbase + (size_t)rl * Ly.ld) = wr[4 * G_ + q];
+        }
+    })
 }
 
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
 // partial sums of the rows over the tile's columns, the bias riding on column block 0.
-__device__ bool p_fwd_tile(const PNet& net, int l, int g, const float* __restrict__ x0, unsigned tag, float* lds) {
+__device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g,
+                                           const float* __restrict__ x0, unsigned tag, float* lds, long long ps,
+                                           int ph) {
     const PLayer& Ly = net.lay[l];
     TileCtx t;
     if (!tile_ctx(Ly, g, t)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
-    float4 w[kKR];
-    load_rows(w, t, Ly.ld, 0);  // in flight while the inputs are awaited
+    DBSN_PROF_SUB(ps, ph, 0);
+    if (!net.stationary) load_tile(wr, Ly, t);  // in flight while the inputs are awaited
 
     float* xk = lds + PLds::xkeep + l * 256;
     if (l == 1) {
@@ -172,7 +261,8 @@ __device__ bool p_fwd_tile(const PNet& net, int l, int g, const float* __restric
         const PLayer& Lp = net.lay[l - 1];
         float* stage = lds + PLds::stage;
         const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0;
-        const bool ok = poll_to_lds(src, Lp.nCB, t.Ceff, (size_t)Lp.n_out, tag, stage, net.spin_limit);
+        const bool ok = poll_to_lds(src, Lp.nCB, nullptr, 0, t.Ceff, (size_t)Lp.n_out, tag, stage, net.spin_limit,
+                                    net.backoff);
         if (!all_ok(ok, net.err)) return false;
         if (threadIdx.x < 256) {
             float s = 0.0f;
@@ -184,100 +274,76 @@ __device__ bool p_fwd_tile(const PNet& net, int l, int g, const float* __restric
         }
     }
     __syncthreads();
+    DBSN_PROF_SUB(ps, ph, 1);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     float* ysum = lds + PLds::ysum;
-    for (int first = 0; first < t.Reff; first += kWaves * kKR) {
-        if (first > 0) load_rows(w, t, Ly.ld, first);
-#pragma unroll
-        for (int k = 0; k < kKR; ++k) {
-            const int rl = first + wave + kWaves * k;
-            float acc = w[k].x * x4.x;
-            acc = fmaf(w[k].y, x4.y, acc);
-            acc = fmaf(w[k].z, x4.z, acc);
-            acc = fmaf(w[k].w, x4.w, acc);
-            acc = wave_sum(acc);
-            if (lane == 0 && rl < t.Reff) ysum[rl] = (t.cb == 0) ? acc + Ly.b[t.r0 + rl] : acc;
-        }
-    }
+    DBSN_FOR_LAYER_SLOTS(Ly, {
+        const float v = wave_sum4(dot4(wr[4 * G_ + 0], x4), dot4(wr[4 * G_ + 1], x4), dot4(wr[4 * G_ + 2], x4),
+                                  dot4(wr[4 * G_ + 3], x4));
+        const int rl = wave + kWaves * (sbase_ + (lane & 3));
+        if (lane < 4 && rl < t.Reff) ysum[rl] = (t.cb == 0) ? v + Ly.b[t.r0 + rl] : v;
+    })
     __syncthreads();
+    DBSN_PROF_SUB(ps, ph, 2);
     u64* dst = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + (size_t)t.cb * Ly.n_out + t.r0;
     for (int j = threadIdx.x; j < t.Reff; j += kThreads)
         __hip_atomic_store(dst + j, pack_tagged(ysum[j], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    DBSN_PROF_SUB(ps, ph, 3);
     return true;
 }
 
 // Fused backward sweep of this workgroup's tile of layer l (appendix "Backward propagation" and
 // "Weight updating" in one pass over the tile): deltas of the tile's rows, partial W^T delta of
-// its columns from the OLD weights, rank-1 update of the tile.
-__device__ bool p_bwd_tile(const PNet& net, int l, int g, float eta, unsigned tag, float* lds) {
+// its columns from the OLD weights (published first, it is what other workgroups wait for), then
+// the rank-1 update of the tile.
+__device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float eta,
+                                           unsigned tag, float* lds, long long ps, int ph) {
     const PLayer& Ly = net.lay[l];
     TileCtx t;
     if (!tile_ctx(Ly, g, t)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
-    float4 w[kKR];
-    load_rows(w, t, Ly.ld, 0);
+    DBSN_PROF_SUB(ps, ph, 0);
+    if (!net.stationary) load_tile(wr, Ly, t);
 
     float* dl = lds + PLds::dl;
+    float* sg = lds + PLds::stage;
     if (l == net.L - 1) {
         // the output layer was evaluated in this workgroup: its deltas are already in LDS
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
-            dl[j] = lds[PLds::dtop + t.r0 + j];
-            if (t.cb == 0) {
-                Ly.x[t.r0 + j] = lds[PLds::xtop + t.r0 + j];
-                Ly.d[t.r0 + j] = dl[j];
-            }
-        }
+        for (int j = threadIdx.x; j < t.Reff; j += kThreads) dl[j] = lds[PLds::dtop + t.r0 + j];
     } else {
-        float* sg = lds + PLds::stage;
-        float* sy = lds + PLds::stage + kStageFloats / 2;
+        float* sy = sg + Ly.gP * t.Reff;
         const u64* gsrc = Ly.gp + (size_t)par * Ly.gP * Ly.n_out + t.r0;
         const u64* ysrc = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + t.r0;
-        bool ok = poll_to_lds(gsrc, Ly.gP, t.Reff, (size_t)Ly.n_out, tag, sg, net.spin_limit);
-        ok = poll_to_lds(ysrc, Ly.nCB, t.Reff, (size_t)Ly.n_out, tag, sy, net.spin_limit) && ok;
+        const bool ok = poll_to_lds(gsrc, Ly.gP, ysrc, Ly.nCB, t.Reff, (size_t)Ly.n_out, tag, sg, net.spin_limit,
+                                    net.backoff);
         if (!all_ok(ok, net.err)) return false;
         for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
             float gs = 0.0f, ys = 0.0f;
             for (int p = 0; p < Ly.gP; ++p) gs += sg[p * t.Reff + j];
             for (int p = 0; p < Ly.nCB; ++p) ys += sy[p * t.Reff + j];
             const float y = act(ys);
-            const float d = gs * dact_from_y(y);
-            dl[j] = d;
-            if (t.cb == 0) {
-                Ly.x[t.r0 + j] = y;
-                Ly.d[t.r0 + j] = d;
-            }
+            dl[j] = gs * dact_from_y(y);
+            sg[j] = y;   // kept for the state read-out below (slot j of row p = 0 has been consumed)
         }
     }
     __syncthreads();
+    DBSN_PROF_SUB(ps, ph, 1);
     const float* xk = lds + PLds::xkeep + l * 256;
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
-    float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int first = 0; first < t.Reff; first += kWaves * kKR) {
-        if (first > 0) load_rows(w, t, Ly.ld, first);
-#pragma unroll
-        for (int k = 0; k < kKR; ++k) {
-            const int rl = first + wave + kWaves * k;
-            if (rl < t.Reff) {
-                const float d = dl[rl];
-                const float ed = eta * d;
-                float4 v = w[k];
+    if (l > 1) {
+        float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
+        DBSN_FOR_LAYER_SLOTS(Ly, {
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+                const int rl = wave + kWaves * (sbase_ + q);
+                const float d = (rl < t.Reff) ? dl[rl] : 0.0f;
+                const float4 v = wr[4 * G_ + q];
                 gacc.x = fmaf(v.x, d, gacc.x);
                 gacc.y = fmaf(v.y, d, gacc.y);
                 gacc.z = fmaf(v.z, d, gacc.z);
                 gacc.w = fmaf(v.w, d, gacc.w);
-                v.x = fmaf(-ed, x4.x, v.x);
-                v.y = fmaf(-ed, x4.y, v.y);
-                v.z = fmaf(-ed, x4.z, v.z);
-                v.w = fmaf(-ed, x4.w, v.w);
-                if (t.lane_on)
-                    *reinterpret_cast<float4*>(const_cast<float*>(t.wbase) + (size_t)rl * Ly.ld) = v;
             }
-        }
-    }
-    if (t.cb == 0)
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) Ly.b[t.r0 + j] -= eta * dl[j];
-    if (l > 1) {
+        })
         float* gred = lds + PLds::gred;
         *reinterpret_cast<float4*>(gred + wave * 256 + 4 * lane) = gacc;
         __syncthreads();
@@ -290,13 +356,39 @@ __device__ bool p_bwd_tile(const PNet& net, int l, int g, float eta, unsigned ta
             __hip_atomic_store(dst + threadIdx.x, pack_tagged(s, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+    DBSN_PROF_SUB(ps, ph, 2);
+    // rank-1 update w -= eta * delta_j * x_i (rows beyond the tile hold zeros and stay zero)
+    DBSN_FOR_LAYER_SLOTS(Ly, {
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+            const int rl = wave + kWaves * (sbase_ + q);
+            const float ed = eta * ((rl < t.Reff) ? dl[rl] : 0.0f);
+            float4 v = wr[4 * G_ + q];
+            v.x = fmaf(-ed, x4.x, v.x);
+            v.y = fmaf(-ed, x4.y, v.y);
+            v.z = fmaf(-ed, x4.z, v.z);
+            v.w = fmaf(-ed, x4.w, v.w);
+            wr[4 * G_ + q] = v;
+        }
+    })
+    if (!net.stationary) store_tile(wr, Ly, t);
+    if (t.cb == 0) {
+        // bias update, and the layer's state for dbsn_mlp_get_activations / _get_deltas
+        for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
+            const float d = dl[j];
+            Ly.b[t.r0 + j] -= eta * d;
+            Ly.d[t.r0 + j] = d;
+            Ly.x[t.r0 + j] = (l == net.L - 1) ? lds[PLds::xtop + t.r0 + j] : sg[j];
+        }
+    }
     __syncthreads();
+    DBSN_PROF_SUB(ps, ph, 3);
     return true;
 }
 
 // Output layer in every workgroup, on its private LDS copy of W_L: x_{L-1} from the partials,
 // logits, softmax, loss, delta_L, the deltas of layer L-1 and the rank-1 update of the copy.
-__device__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out, float* lds) {
+__device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
+                                      float* lds, long long ps, int ph) {
     const int L = net.L;
     const PLayer& Ly = net.lay[L];
     const PLayer& Lp = net.lay[L - 1];
@@ -311,9 +403,11 @@ __device__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag
     float* logit = lds + PLds::logit;
     float* dL = lds + PLds::dL;
 
+    DBSN_PROF_SUB(ps, ph, 0);
     const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
-    const bool ok = poll_to_lds(src, Lp.nCB, n, (size_t)Lp.n_out, tag, stage, net.spin_limit);
+    const bool ok = poll_to_lds(src, Lp.nCB, nullptr, 0, n, (size_t)Lp.n_out, tag, stage, net.spin_limit, net.backoff);
     if (!all_ok(ok, net.err)) return false;
+    DBSN_PROF_SUB(ps, ph, 1);
     for (int i = threadIdx.x; i < n; i += kThreads) {
         float s = 0.0f;
         for (int p = 0; p < Lp.nCB; ++p) s += stage[p * n + i];
@@ -323,37 +417,54 @@ __device__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag
     for (int j = wave; j < nc; j += kWaves) {
         float acc = 0.0f;
         for (int i = lane; i < n; i += 64) acc = fmaf(WL[j * n + i], xtop[i], acc);
-        acc = wave_sum(acc);
+        acc = wave_sum_dpp(acc);
         if (lane == 0) logit[j] = acc + bL[j];
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    DBSN_PROF_SUB(ps, ph, 2);
+    {
+        // softmax over nc <= 64 classes, one class per lane, redundantly in every wavefront (no
+        // further barrier needed before delta_L is used); sums are taken in index order
         float m = logit[0];
-        for (int k = 1; k < nc; ++k) m = logit[k] > m ? logit[k] : m;
+        for (int k = 1; k < nc; ++k) m = fmaxf(m, logit[k]);
+        const float e = (lane < nc) ? expf(logit[lane] - m) : 0.0f;
         float s = 0.0f;
-        for (int k = 0; k < nc; ++k) { dL[k] = expf(logit[k] - m); s += dL[k]; }
-        float pl = 0.0f;
-        for (int k = 0; k < nc; ++k) {
-            const float p = dL[k] / s;
-            if (k == label) pl = p;
-            dL[k] = p - (k == label ? 1.0f : 0.0f);
-            if (g == 0) { Ly.x[k] = p; Ly.d[k] = dL[k]; }
+        for (int k = 0; k < nc; ++k) s += __shfl(e, k, 64);
+        const float p = e / s;
+        const float d = p - (lane == label ? 1.0f : 0.0f);
+        if (wave == 0) {
+            const float pl = __shfl(p, label, 64);
+            if (lane < nc) {
+                dL[lane] = d;
+                if (g == 0) { Ly.x[lane] = p; Ly.d[lane] = d; }
+            }
+            if (g == 0 && lane == 0 && loss_out) *loss_out = -logf(pl);
         }
-        if (g == 0 && loss_out) *loss_out = -logf(pl);
+        // deltas of layer L-1 and update of the private W_L, 16 classes at a time from registers
+        for (int i0 = 0; i0 < n; i0 += kThreads) {
+            const int i = i0 + (int)threadIdx.x;
+            const bool on = i < n;
+            const float xi = on ? xtop[i] : 0.0f;
+            float gs = 0.0f;
+            for (int j0 = 0; j0 < nc; j0 += 16) {
+                float wv[16];
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) wv[jj] = (on && j0 + jj < nc) ? WL[(j0 + jj) * n + i] : 0.0f;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    const float dj = __shfl(d, (j0 + jj) & 63, 64);
+                    if (on && j0 + jj < nc) {
+                        gs = fmaf(wv[jj], dj, gs);
+                        WL[(j0 + jj) * n + i] = fmaf(-(eta * dj), xi, wv[jj]);
+                    }
+                }
+            }
+            if (on) dtop[i] = gs * dact_from_y(xi);
+        }
+        if (wave == 0 && lane < nc) bL[lane] -= eta * d;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += kThreads) {
-        float gs = 0.0f;
-        const float xi = xtop[i];
-        for (int j = 0; j < nc; ++j) {
-            const float wv = WL[j * n + i];
-            gs = fmaf(wv, dL[j], gs);
-            WL[j * n + i] = fmaf(-(eta * dL[j]), xi, wv);
-        }
-        dtop[i] = gs * dact_from_y(xi);
-    }
-    if (threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
-    __syncthreads();
+    DBSN_PROF_SUB(ps, ph, 3);
     return true;
 }
 
@@ -371,6 +482,16 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     if (threadIdx.x < LyL.n_out) lds[PLds::bL + threadIdx.x] = LyL.b[threadIdx.x];
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
+
+    float4 wr[kSlots];
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) wr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (net.stationary) {
+        for (int l = 1; l < L; ++l) {
+            TileCtx t;
+            if (tile_ctx(net.lay[l], g, t)) load_tile(wr, net.lay[l], t);
+        }
+    }
     __syncthreads();
 
     bool alive = true;
@@ -379,9 +500,15 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
         const float* x0 = samples + s * n0;
         int label = labels ? labels[s] : label_val;
         label = label < 0 ? 0 : (label >= LyL.n_out ? LyL.n_out - 1 : label);
-        for (int l = 1; l < L && alive; ++l) alive = p_fwd_tile(net, l, g, x0, tag, lds);
-        if (alive) alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, lds);
-        for (int l = L - 1; l >= 1 && alive; --l) alive = p_bwd_tile(net, l, g, eta, tag, lds);
+        for (int l = 1; l < L && alive; ++l) alive = p_fwd_tile(wr, net, l, g, x0, tag, lds, s, l - 1);
+        if (alive) alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, lds, s, L - 1);
+        for (int l = L - 1; l >= 1 && alive; --l) alive = p_bwd_tile(wr, net, l, g, eta, tag, lds, s, L + (L - 1 - l));
+    }
+    if (net.stationary) {
+        for (int l = 1; l < L; ++l) {
+            TileCtx t;
+            if (tile_ctx(net.lay[l], g, t)) store_tile(wr, net.lay[l], t);
+        }
     }
     if (g == 0) {
         __syncthreads();
