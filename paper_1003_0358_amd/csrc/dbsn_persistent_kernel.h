@@ -47,8 +47,14 @@ __device__ int g_prof_steps, g_prof_slots;
         if (threadIdx.x == 0 && (step) < g_prof_steps && (slot) < g_prof_slots)                      \
             g_prof[((size_t)(step) * g_prof_slots + (slot)) * gridDim.x + blockIdx.x] = wall_clock64(); \
     } while (0)
+#define DBSN_PROF_VAL(step, slot, val)                                                               \
+    do {                                                                                             \
+        if (threadIdx.x == 0 && (step) < g_prof_steps && (slot) < g_prof_slots)                      \
+            g_prof[((size_t)(step) * g_prof_slots + (slot)) * gridDim.x + blockIdx.x] = (val);       \
+    } while (0)
 #else
 #define DBSN_PROF(step, slot) do { } while (0)
+#define DBSN_PROF_VAL(step, slot, val) do { } while (0)
 #endif
 #define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 4 + (sub))
 
@@ -87,8 +93,8 @@ struct PLds {
     static constexpr int xkeep = dL + kMaxClasses;                // [kMaxLayers + 1][256]
     static constexpr int stage = xkeep + (kMaxLayers + 1) * 256;  // [kStageFloats]
     static constexpr int dl = stage + kStageFloats;               // [kSlots * kWaves]
-    static constexpr int ysum = dl + kSlots * kWaves;             // [kSlots * kWaves]
-    static constexpr int gred = ysum + kSlots * kWaves;           // [kWaves][256]
+    static constexpr int ysum = dl + kSlots * kWaves;             // [4][kSlots * kWaves]
+    static constexpr int gred = ysum + 4 * kSlots * kWaves;       // [kWaves][256]
     static constexpr int xtop = gred + kWaves * 256;              // [kTopXMax]
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
     static constexpr int total = dtop + kTopXMax;
@@ -97,43 +103,51 @@ struct PLds {
 __device__ inline u64 pack_tagged(float v, unsigned tag) { return ((u64)tag << 32) | (u64)__float_as_uint(v); }
 
 // Wait for tagged words of step `tag` and put their float payloads into LDS.  The words come from
-// two strided sources that share the row length `len`: srcA[p * stride + j] (p < PA) lands at
-// stage[p * len + j], srcB[p * stride + j] (p < PB) behind them at stage[(PA + p) * len + j]
-// (PB may be 0).  Every thread keeps 4 loads in flight; a wavefront re-reads its words until all
-// of them carry the tag (the loop is wavefront-uniform, so there is no divergent control flow
-// around the loads).  Returns false when the spin limit ran out.
+// two strided sources that share the row length `len` <= 512: srcA[p * stride + j] (p < PA) lands
+// at stage[p * pitch + j], srcB[p * stride + j] (p < PB) behind them at stage[(PA + p) * pitch + j]
+// (PB may be 0).  Threads are laid out as rows of 2^lg >= len lanes over consecutive j, so that no
+// division is needed and a wavefront reads runs of consecutive words; every thread keeps up to 8
+// loads in flight, and a wavefront re-reads its batch until all of it carries the tag (the loop
+// is wavefront-uniform: no divergent control flow around the loads).  Returns false when the
+// spin limit ran out.
 __device__ inline bool poll_to_lds(const u64* srcA, int PA, const u64* srcB, int PB, int len, size_t stride,
-                                   unsigned tag, float* stage, unsigned limit, int backoff) {
-    const int nA = PA * len, total = nA + PB * len;
+ unsigned tag, float* stage, int pitch, unsigned limit, int backoff,
+                                   unsigned* rounds = nullptr) {
+    int lg = 5;                                   // rows of 32, 64, 128 or 256 lanes
+    while ((1 << lg) < len) ++lg;
+    const int j = (int)threadIdx.x & ((1 << lg) - 1);
+    const int prow = (int)threadIdx.x >> lg;      // first partial this thread reads
+    const int pstep = kThreads >> lg;             // partials covered by one pass of the workgroup
+    const int P = PA + PB;
+    const bool jon = j < len;
     bool ok = true;
-    for (int base = 0; base < total; base += kThreads * 4) {
-        const u64* a[4];
-        int e[4];
-        bool valid[4];
+    for (int p0 = 0; p0 < P; p0 += 8 * pstep) {
+        const u64* a[8];
+        bool valid[8];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            e[k] = base + k * kThreads + (int)threadIdx.x;
-            valid[k] = e[k] < total;
-            const bool inA = e[k] < nA;
-            const int idx = valid[k] ? (inA ? e[k] : e[k] - nA) : 0;
-            const int p = idx / len, j = idx - p * len;
-            a[k] = ((inA || !valid[k]) ? srcA : srcB) + (size_t)p * stride + j;
+        for (int k = 0; k < 8; ++k) {
+            const int p = p0 + prow + k * pstep;
+            valid[k] = jon && p < P;
+            const u64* base = (p < PA || !valid[k]) ? srcA : srcB;
+            const int pp = !valid[k] ? 0 : (p < PA ? p : p - PA);
+            a[k] = base + (size_t)pp * stride + (valid[k] ? j : 0);
         }
-        u64 v[4];
+        u64 v[8];
         unsigned spins = 0;
         for (;;) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = __hip_atomic_load(a[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(a[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             bool pending = false;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) pending |= valid[k] && ((unsigned)(v[k] >> 32) != tag);
+            for (int k = 0; k < 8; ++k) pending |= valid[k] && ((unsigned)(v[k] >> 32) != tag);
             if (!__any(pending)) break;
             if (++spins > limit) { ok = false; break; }
             for (int z = 0; z < backoff; ++z) __builtin_amdgcn_s_sleep(1);
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (valid[k]) stage[e[k]] = __uint_as_float((unsigned)v[k]);
+        for (int k = 0; k < 8; ++k)
+            if (valid[k]) stage[(p0 + prow + k * pstep) * pitch + j] = __uint_as_float((unsigned)v[k]);
+        if (rounds) *rounds += spins + 1;
         if (!ok) break;
     }
     return ok;
@@ -169,8 +183,9 @@ __device__ inline float wave_sum_dpp(float v) {
 
 // Sums of four values over the 64 lanes at once: two halving steps inside every quad of lanes
 // leave value (t & 3) in lane t, the remaining steps add over the 16 quads.  On return lane t
-// holds the wavefront-wide sum of a[t & 3].  13 vector ops and 2 LDS permutes for 4 rows.
-__device__ inline float wave_sum4(float a0, float a1, float a2, float a3) {
+// holds the sum of a[t & 3] over its row of 16 lanes; the caller adds the four rows with two LDS
+// permutes (xor 16, xor 32), which it can overlap across several groups.  13 vector ops.
+__device__ inline float quad_sum4(float a0, float a1, float a2, float a3) {
     const int lane = threadIdx.x & 63;
     const bool b0 = (lane & 1) != 0, b1 = (lane & 2) != 0;
     const float s0 = (b0 ? a1 : a0) + dpp_mov<kDppXor1>(b0 ? a0 : a1);
@@ -178,9 +193,42 @@ __device__ inline float wave_sum4(float a0, float a1, float a2, float a3) {
     float v = (b1 ? s1 : s0) + dpp_mov<kDppXor2>(b1 ? s0 : s1);
     v += dpp_mov<kDppRor4>(v);
     v += dpp_mov<kDppRor8>(v);
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
+    return v;   // sum over this row of 16 lanes; the caller adds the four rows (xor 16, xor 32)
+}
+
+// sum over p < P of stage[p * len + j], in index order; the LDS reads go out eight at a time
+__device__ inline float sum_partials(const float* stage, int P, int len, int j) {
+    float s = 0.0f;
+    int p = 0;
+    for (; p + 8 <= P; p += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = stage[(p + k) * len + j];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s += v[k];
+    }
+    if (p < P) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = (p + k < P) ? stage[(p + k) * len + j] : 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s += v[k];   // adding the zeros of the tail changes nothing
+    }
+    return s;
+}
+
+// y(a) = A tanh(B a) without the library routine: tanh(t) = 1 - 2 / (exp(2t) + 1) away from zero,
+// the odd Taylor polynomial up to t^7 below |t| = 0.125 (where the first form would cancel).
+// Absolute error below 3e-7 on the whole axis.
+__device__ inline float act_fast(float a) {
+    const float t = kB * a;
+    const float at = fabsf(t);
+    const float e = __expf(2.0f * at);
+    const float big = 1.0f - __fdividef(2.0f, e + 1.0f);
+    const float t2 = t * t;
+    const float small = at * fmaf(t2, fmaf(t2, fmaf(t2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
+    const float r = (at < 0.125f) ? small : big;
+    return kA * copysignf(r, t);
 }
 
 __device__ inline float dot4(const float4& w, const float4& x) {
@@ -213,14 +261,16 @@ __device__ inline bool tile_ctx(const PLayer& Ly, int g, TileCtx& t) {
 // Register slot s of group G = g0 + s / 4 holds tile row wave + 8 * s.
 #define DBSN_FOR_LAYER_SLOTS(Ly, BODY)                                  \
     _Pragma("unroll") for (int G_ = 0; G_ < kNG; ++G_) {                 \
-        if (G_ >= (Ly).g0 && G_ < (Ly).g0 + (Ly).ng) {                   \
-            const int sbase_ = 4 * (G_ - (Ly).g0);                       \
+        if (G_ >= g0_ && G_ < g0_ + ng_) {                               \
+            const int sbase_ = 4 * (G_ - g0_);                           \
             BODY                                                         \
         }                                                                \
     }
+#define DBSN_LAYER_GROUPS(Ly) const int g0_ = (Ly).g0, ng_ = (Ly).ng
 
 __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const PLayer& Ly, const TileCtx& t) {
     const int wave = threadIdx.x >> 6;
+    DBSN_LAYER_GROUPS(Ly);
     DBSN_FOR_LAYER_SLOTS(Ly, {
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {
             const int rl = wave + kWaves * (sbase_ + q);
@@ -233,6 +283,7 @@ __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const PLayer& Ly
 
 __device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const PLayer& Ly, const TileCtx& t) {
     const int wave = threadIdx.x >> 6;
+    DBSN_LAYER_GROUPS(Ly);
     DBSN_FOR_LAYER_SLOTS(Ly, {
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {
             const int rl = wave + kWaves * (sbase_ + q);
@@ -251,6 +302,7 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     if (!tile_ctx(Ly, g, t)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
+    DBSN_LAYER_GROUPS(Ly);
     DBSN_PROF_SUB(ps, ph, 0);
     if (!net.stationary) load_tile(wr, Ly, t);  // in flight while the inputs are awaited
 
@@ -261,14 +313,18 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
         const PLayer& Lp = net.lay[l - 1];
         float* stage = lds + PLds::stage;
         const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0;
-        const bool ok = poll_to_lds(src, Lp.nCB, nullptr, 0, t.Ceff, (size_t)Lp.n_out, tag, stage, net.spin_limit,
-                                    net.backoff);
+        unsigned rounds = 0;
+        const bool ok = poll_to_lds(src, Lp.nCB, nullptr, 0, t.Ceff, (size_t)Lp.n_out, tag, stage, t.Ceff,
+                                    net.spin_limit, net.backoff, &rounds);
+        DBSN_PROF_VAL(ps, (2 * net.L - 1) * 4 + ph, rounds);
+        DBSN_PROF(ps, (2 * net.L - 1) * 5 + ph * 3 + 0);
         if (!all_ok(ok, net.err)) return false;
+        DBSN_PROF(ps, (2 * net.L - 1) * 5 + ph * 3 + 1);
         if (threadIdx.x < 256) {
             float s = 0.0f;
             if (threadIdx.x < t.Ceff) {
-                for (int p = 0; p < Lp.nCB; ++p) s += stage[p * t.Ceff + threadIdx.x];
-                s = act(s);
+                s = act_fast(sum_partials(stage, Lp.nCB, t.Ceff, threadIdx.x));
+                if (t.rb == 0) Lp.x[t.c0 + threadIdx.x] = s;   // state read-out (dbsn_mlp_get_activations)
             }
             xk[threadIdx.x] = s;
         }
@@ -277,17 +333,24 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 1);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     float* ysum = lds + PLds::ysum;
+    // per group: 4 row sums transposed onto the quads, reduced inside each row of 16 lanes on the
+    // vector ALU; the four rows of 16 park their sums in LDS and the publishing thread adds them
+    const int lrow = lane >> 4;
     DBSN_FOR_LAYER_SLOTS(Ly, {
-        const float v = wave_sum4(dot4(wr[4 * G_ + 0], x4), dot4(wr[4 * G_ + 1], x4), dot4(wr[4 * G_ + 2], x4),
+        const float v = quad_sum4(dot4(wr[4 * G_ + 0], x4), dot4(wr[4 * G_ + 1], x4), dot4(wr[4 * G_ + 2], x4),
                                   dot4(wr[4 * G_ + 3], x4));
         const int rl = wave + kWaves * (sbase_ + (lane & 3));
-        if (lane < 4 && rl < t.Reff) ysum[rl] = (t.cb == 0) ? v + Ly.b[t.r0 + rl] : v;
+        if ((lane & 12) == 0) ysum[lrow * (kSlots * kWaves) + rl] = v;
     })
     __syncthreads();
     DBSN_PROF_SUB(ps, ph, 2);
     u64* dst = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + (size_t)t.cb * Ly.n_out + t.r0;
-    for (int j = threadIdx.x; j < t.Reff; j += kThreads)
-        __hip_atomic_store(dst + j, pack_tagged(ysum[j], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
+        constexpr int kYS = kSlots * kWaves;
+        float v = (ysum[j] + ysum[kYS + j]) + (ysum[2 * kYS + j] + ysum[3 * kYS + j]);
+        if (t.cb == 0) v += Ly.b[t.r0 + j];
+        __hip_atomic_store(dst + j, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     DBSN_PROF_SUB(ps, ph, 3);
     return true;
 }
@@ -303,6 +366,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     if (!tile_ctx(Ly, g, t)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
+    DBSN_LAYER_GROUPS(Ly);
     DBSN_PROF_SUB(ps, ph, 0);
     if (!net.stationary) load_tile(wr, Ly, t);
 
@@ -312,31 +376,27 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         // the output layer was evaluated in this workgroup: its deltas are already in LDS
         for (int j = threadIdx.x; j < t.Reff; j += kThreads) dl[j] = lds[PLds::dtop + t.r0 + j];
     } else {
-        float* sy = sg + Ly.gP * t.Reff;
         const u64* gsrc = Ly.gp + (size_t)par * Ly.gP * Ly.n_out + t.r0;
-        const u64* ysrc = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + t.r0;
-        const bool ok = poll_to_lds(gsrc, Ly.gP, ysrc, Ly.nCB, t.Reff, (size_t)Ly.n_out, tag, sg, net.spin_limit,
-                                    net.backoff);
+        unsigned rounds = 0;
+        const bool ok = poll_to_lds(gsrc, Ly.gP, nullptr, 0, t.Reff, (size_t)Ly.n_out, tag, sg, t.Reff,
+                                    net.spin_limit, net.backoff, &rounds);
+        DBSN_PROF_VAL(ps, (2 * net.L - 1) * 4 + ph, rounds);
         if (!all_ok(ok, net.err)) return false;
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
-            float gs = 0.0f, ys = 0.0f;
-            for (int p = 0; p < Ly.gP; ++p) gs += sg[p * t.Reff + j];
-            for (int p = 0; p < Ly.nCB; ++p) ys += sy[p * t.Reff + j];
-            const float y = act(ys);
-            dl[j] = gs * dact_from_y(y);
-            sg[j] = y;   // kept for the state read-out below (slot j of row p = 0 has been consumed)
-        }
+        // the producers multiplied their partial sums by f'(x_l) already (they hold x_l, see below)
+        for (int j = threadIdx.x; j < t.Reff; j += kThreads) dl[j] = sum_partials(sg, Ly.gP, t.Reff, j);
     }
     __syncthreads();
     DBSN_PROF_SUB(ps, ph, 1);
     const float* xk = lds + PLds::xkeep + l * 256;
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
+    // lane s of a wavefront fetches the delta of the wavefront's s-th row; slots read it by lane index
+    const int myrow = wave + kWaves * lane;
+    const float dlane = (lane < kSlots && myrow < t.Reff) ? dl[myrow] : 0.0f;
     if (l > 1) {
         float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
         DBSN_FOR_LAYER_SLOTS(Ly, {
             _Pragma("unroll") for (int q = 0; q < 4; ++q) {
-                const int rl = wave + kWaves * (sbase_ + q);
-                const float d = (rl < t.Reff) ? dl[rl] : 0.0f;
+                const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
                 const float4 v = wr[4 * G_ + q];
                 gacc.x = fmaf(v.x, d, gacc.x);
                 gacc.y = fmaf(v.y, d, gacc.y);
@@ -350,9 +410,15 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         const PLayer& Lp = net.lay[l - 1];
         u64* dst = Lp.gp + (size_t)par * Lp.gP * Lp.n_out + (size_t)t.rb * Lp.n_out + t.c0;
         if (threadIdx.x < t.Ceff) {
+            float v[kWaves];
+#pragma unroll
+            for (int k = 0; k < kWaves; ++k) v[k] = gred[k * 256 + threadIdx.x];
             float s = 0.0f;
 #pragma unroll
-            for (int v = 0; v < kWaves; ++v) s += gred[v * 256 + threadIdx.x];
+            for (int k = 0; k < kWaves; ++k) s += v[k];
+            // this tile's columns are neurons of layer l-1 whose outputs it holds: fold f' in here,
+            // so that the consumer's sum over row blocks is delta_{l-1} itself
+            s *= dact_from_y(xk[threadIdx.x]);
             __hip_atomic_store(dst + threadIdx.x, pack_tagged(s, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
@@ -360,8 +426,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     // rank-1 update w -= eta * delta_j * x_i (rows beyond the tile hold zeros and stay zero)
     DBSN_FOR_LAYER_SLOTS(Ly, {
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {
-            const int rl = wave + kWaves * (sbase_ + q);
-            const float ed = eta * ((rl < t.Reff) ? dl[rl] : 0.0f);
+            const float ed = eta * __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
             float4 v = wr[4 * G_ + q];
             v.x = fmaf(-ed, x4.x, v.x);
             v.y = fmaf(-ed, x4.y, v.y);
@@ -372,12 +437,11 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     })
     if (!net.stationary) store_tile(wr, Ly, t);
     if (t.cb == 0) {
-        // bias update, and the layer's state for dbsn_mlp_get_activations / _get_deltas
+        // bias update, and the layer's deltas for dbsn_mlp_get_deltas
         for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
             const float d = dl[j];
             Ly.b[t.r0 + j] -= eta * d;
             Ly.d[t.r0 + j] = d;
-            Ly.x[t.r0 + j] = (l == net.L - 1) ? lds[PLds::xtop + t.r0 + j] : sg[j];
         }
     }
     __syncthreads();
@@ -387,6 +451,9 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
 
 // Output layer in every workgroup, on its private LDS copy of W_L: x_{L-1} from the partials,
 // logits, softmax, loss, delta_L, the deltas of layer L-1 and the rank-1 update of the copy.
+// Thread i owns column i (input neuron i) of W_L: it forms the products W_L[j][i] x_i, the
+// workgroup adds them per class (quads -> rows of 16 lanes on the vector ALU, then through LDS),
+// and after the softmax the same thread back-propagates and updates its column.
 __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
                                       float* lds, long long ps, int ph) {
     const int L = net.L;
@@ -402,67 +469,91 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     float* bL = lds + PLds::bL;
     float* logit = lds + PLds::logit;
     float* dL = lds + PLds::dL;
+    float* part = lds + PLds::gred;   // [kMaxClasses][32] partial logits: 8 wavefronts x 4 rows of 16 lanes
 
     DBSN_PROF_SUB(ps, ph, 0);
     const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
-    const bool ok = poll_to_lds(src, Lp.nCB, nullptr, 0, n, (size_t)Lp.n_out, tag, stage, net.spin_limit, net.backoff);
+    unsigned rounds = 0;
+    bool ok = true;
+    for (int j0 = 0; j0 < n && ok; j0 += kThreads)
+        ok = poll_to_lds(src + j0, Lp.nCB, nullptr, 0, min(kThreads, n - j0), (size_t)Lp.n_out, tag, stage + j0, n,
+                         net.spin_limit, net.backoff, &rounds);
+    DBSN_PROF_VAL(ps, (2 * net.L - 1) * 4 + ph, rounds);
     if (!all_ok(ok, net.err)) return false;
     DBSN_PROF_SUB(ps, ph, 1);
-    for (int i = threadIdx.x; i < n; i += kThreads) {
-        float s = 0.0f;
-        for (int p = 0; p < Lp.nCB; ++p) s += stage[p * n + i];
-        xtop[i] = act(s);
-    }
-    __syncthreads();
-    for (int j = wave; j < nc; j += kWaves) {
-        float acc = 0.0f;
-        for (int i = lane; i < n; i += 64) acc = fmaf(WL[j * n + i], xtop[i], acc);
-        acc = wave_sum_dpp(acc);
-        if (lane == 0) logit[j] = acc + bL[j];
+
+    // products per class, 16 classes at a time; columns beyond 512 are folded into the same thread
+    for (int j0 = 0; j0 < nc; j0 += 16) {
+        float acc[16];
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.0f;
+        for (int i = threadIdx.x; i < n; i += kThreads) {
+            const float xi = act_fast(sum_partials(stage, Lp.nCB, n, i));
+            if (j0 == 0) {
+                xtop[i] = xi;
+                if (g == 0) Lp.x[i] = xi;   // state read-out (dbsn_mlp_get_activations)
+            }
+            float wv[16];
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) wv[jj] = (j0 + jj < nc) ? WL[(j0 + jj) * n + i] : 0.0f;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) acc[jj] = fmaf(wv[jj], xi, acc[jj]);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float v = quad_sum4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+            const int cls = j0 + 4 * q + (lane & 3);
+            if ((lane & 12) == 0 && cls < nc) part[cls * 32 + wave * 4 + (lane >> 4)] = v;
+        }
     }
     __syncthreads();
     DBSN_PROF_SUB(ps, ph, 2);
-    {
-        // softmax over nc <= 64 classes, one class per lane, redundantly in every wavefront (no
-        // further barrier needed before delta_L is used); sums are taken in index order
-        float m = logit[0];
-        for (int k = 1; k < nc; ++k) m = fmaxf(m, logit[k]);
-        const float e = (lane < nc) ? expf(logit[lane] - m) : 0.0f;
-        float s = 0.0f;
-        for (int k = 0; k < nc; ++k) s += __shfl(e, k, 64);
+    if (wave == 0) {
+        // logits and softmax over nc <= 64 classes, one class per lane
+        float a = -3.0e38f;
+        if (lane < nc) a = sum_partials(part + lane * 32, 32, 1, 0) + bL[lane];
+        float m = a;
+        m = fmaxf(m, dpp_mov<kDppXor1>(m));
+        m = fmaxf(m, dpp_mov<kDppXor2>(m));
+        m = fmaxf(m, dpp_mov<kDppRor4>(m));
+        m = fmaxf(m, dpp_mov<kDppRor8>(m));
+        m = fmaxf(m, __shfl_xor(m, 16, 64));
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        const float e = (lane < nc) ? expf(a - m) : 0.0f;
+        if (lane < nc) logit[lane] = e;       // scratch: exponentials
+        // (LDS serves one wavefront's accesses in program order: the reads below see these writes)
+        const float s = sum_partials(logit, nc, 1, 0);   // index order
         const float p = e / s;
         const float d = p - (lane == label ? 1.0f : 0.0f);
-        if (wave == 0) {
-            const float pl = __shfl(p, label, 64);
-            if (lane < nc) {
-                dL[lane] = d;
-                if (g == 0) { Ly.x[lane] = p; Ly.d[lane] = d; }
-            }
-            if (g == 0 && lane == 0 && loss_out) *loss_out = -logf(pl);
+        const float pl = __shfl(p, label, 64);
+        if (lane < nc) {
+            dL[lane] = d;
+            if (g == 0) { Ly.x[lane] = p; Ly.d[lane] = d; }
         }
-        // deltas of layer L-1 and update of the private W_L, 16 classes at a time from registers
-        for (int i0 = 0; i0 < n; i0 += kThreads) {
-            const int i = i0 + (int)threadIdx.x;
-            const bool on = i < n;
-            const float xi = on ? xtop[i] : 0.0f;
-            float gs = 0.0f;
-            for (int j0 = 0; j0 < nc; j0 += 16) {
-                float wv[16];
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) wv[jj] = (on && j0 + jj < nc) ? WL[(j0 + jj) * n + i] : 0.0f;
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    const float dj = __shfl(d, (j0 + jj) & 63, 64);
-                    if (on && j0 + jj < nc) {
-                        gs = fmaf(wv[jj], dj, gs);
-                        WL[(j0 + jj) * n + i] = fmaf(-(eta * dj), xi, wv[jj]);
-                    }
-                }
-            }
-            if (on) dtop[i] = gs * dact_from_y(xi);
-        }
-        if (wave == 0 && lane < nc) bL[lane] -= eta * d;
+        if (g == 0 && lane == 0 && loss_out) *loss_out = -logf(pl);
     }
+    __syncthreads();
+    // deltas of layer L-1 and update of the private W_L, 16 classes at a time from registers
+    for (int i = threadIdx.x; i < n; i += kThreads) {
+        const float xi = xtop[i];
+        float gs = 0.0f;
+        for (int j0 = 0; j0 < nc; j0 += 16) {
+            float wv[16], dj[16];
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const bool on = j0 + jj < nc;
+                wv[jj] = on ? WL[(j0 + jj) * n + i] : 0.0f;
+                dj[jj] = on ? dL[j0 + jj] : 0.0f;
+            }
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                gs = fmaf(wv[jj], dj[jj], gs);
+                if (j0 + jj < nc) WL[(j0 + jj) * n + i] = fmaf(-(eta * dj[jj]), xi, wv[jj]);
+            }
+        }
+        dtop[i] = gs * dact_from_y(xi);
+    }
+    if (threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
     __syncthreads();
     DBSN_PROF_SUB(ps, ph, 3);
     return true;
