@@ -93,17 +93,16 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         const int rb_max = kPGroups / p.nCB[l];
         p.R[l] = (nout + rb_max - 1) / rb_max;
         p.nRB[l] = (nout + p.R[l] - 1) / p.R[l];
-        if (p.R[l] > 256 || p.C[l] > 256) p.persistent_ok = false;
+        if (p.R[l] > kMaxTileRows || p.C[l] > 256) p.persistent_ok = false;
     }
     for (int l = 1; l < L; ++l) {
         p.yp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nCB[l] * sizes[l]);
         if (l <= L - 2) {
             p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l + 1] * sizes[l]);
             // the staging area holds the gp and the yp partials of a tile's rows side by side
-            if (p.nRB[l + 1] * p.R[l] > kStageFloats / 2 || p.nCB[l] * p.R[l] > kStageFloats / 2)
-                p.persistent_ok = false;
+            // staging of one tile's partials: R rows of nRB_{l+1} words, padded to an odd pitch
+            if (p.R[l] * ((((p.nRB[l + 1] + 3) / 4) * 4) | 1) > kStageFloats) p.persistent_ok = false;
         }
-        if (l >= 2 && p.nCB[l - 1] * p.C[l] > kStageFloats) p.persistent_ok = false;
     }
     // register groups of 4 rows per wavefront: stationary when every layer gets groups of its own
     int groups = 0;
@@ -118,9 +117,7 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         at += p.ng[l];
     }
     if (L >= 2) {
-        if ((size_t)sizes[L] * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax ||
-            p.nCB[L - 1] * sizes[L - 1] > kStageFloats)
-            p.persistent_ok = false;
+        if ((size_t)sizes[L] * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax) p.persistent_ok = false;
     }
     p.total = off;
     return p;
@@ -211,7 +208,7 @@ int32_t steps_launches(dbsn_mlp* m, const float* samples, const int* labels, int
 // One cooperative launch (all kPGroups workgroups resident together) runs the n steps.
 int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n, float eta,
                          float* loss) {
-    const size_t lds = sizeof(float) * (size_t)PLds::total;
+    const size_t lds = sizeof(float) * (size_t)(PLds::total + kProfLdsFloats);
     const void* fn = reinterpret_cast<const void*>(&k_bp_dataflow);
     if (!m->persistent_ready) {
         if (lds > m->lds_limit) return fail(DBSN_E_SHAPE, "persistent kernel needs %zu B of LDS", lds);

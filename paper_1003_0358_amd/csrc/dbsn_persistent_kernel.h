@@ -38,32 +38,50 @@ namespace dbsn {
 
 typedef unsigned long long u64;
 
-// Optional per-phase time stamps for tuning (compiled out unless DBSN_PROFILE is defined).
+// Optional per-phase time stamps for tuning (compiled out unless DBSN_PROFILE is defined): thread 0
+// of every workgroup notes the shader clock in LDS for kProfSteps consecutive steps and copies the
+// notes to global memory when the kernel ends, so that taking a stamp costs no memory traffic.
 #ifdef DBSN_PROFILE
-__device__ unsigned long long* g_prof;     // [steps][slots][workgroups]
-__device__ int g_prof_steps, g_prof_slots;
-#define DBSN_PROF(step, slot)                                                                        \
-    do {                                                                                             \
-        if (threadIdx.x == 0 && (step) < g_prof_steps && (slot) < g_prof_slots)                      \
-            g_prof[((size_t)(step) * g_prof_slots + (slot)) * gridDim.x + blockIdx.x] = wall_clock64(); \
+constexpr int kProfSteps = 8, kProfSlots = 64;
+__device__ unsigned long long* g_prof;     // [kProfSteps][kProfSlots][workgroups]
+__device__ long long g_prof_first;         // first step to record
+#define DBSN_PROF_DECL unsigned long long* prof_lds_ = reinterpret_cast<unsigned long long*>(lds + PLds::total); \
+                       for (int e_ = threadIdx.x; e_ < kProfSteps * kProfSlots; e_ += kThreads) prof_lds_[e_] = 0; \
+                       const long long prof_first_ = g_prof_first
+#define DBSN_PROF_ARGS , unsigned long long* prof_lds_, long long prof_first_
+#define DBSN_PROF_PASS , prof_lds_, prof_first_
+#define DBSN_PROF_VAL(step, slot, val)                                                                  \
+    do {                                                                                                \
+        const long long ps_ = (long long)(step) - prof_first_;                                          \
+        if (threadIdx.x == 0 && ps_ >= 0 && ps_ < kProfSteps && (slot) < kProfSlots)                    \
+            prof_lds_[ps_ * kProfSlots + (slot)] = (val);                                               \
     } while (0)
-#define DBSN_PROF_VAL(step, slot, val)                                                               \
-    do {                                                                                             \
-        if (threadIdx.x == 0 && (step) < g_prof_steps && (slot) < g_prof_slots)                      \
-            g_prof[((size_t)(step) * g_prof_slots + (slot)) * gridDim.x + blockIdx.x] = (val);       \
+#define DBSN_PROF(step, slot) DBSN_PROF_VAL(step, slot, clock64())
+#define DBSN_PROF_FLUSH()                                                                               \
+    do {                                                                                                \
+        __syncthreads();                                                                                \
+        for (int e_ = threadIdx.x; e_ < kProfSteps * kProfSlots; e_ += kThreads)                        \
+            g_prof[(size_t)e_ * gridDim.x + blockIdx.x] = prof_lds_[e_];                                \
     } while (0)
+constexpr int kProfLdsFloats = 2 * kProfSteps * kProfSlots;
 #else
+#define DBSN_PROF_DECL do { } while (0)
+#define DBSN_PROF_ARGS
+#define DBSN_PROF_PASS
 #define DBSN_PROF(step, slot) do { } while (0)
 #define DBSN_PROF_VAL(step, slot, val) do { } while (0)
+#define DBSN_PROF_FLUSH() do { } while (0)
+constexpr int kProfLdsFloats = 0;
 #endif
 #define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 4 + (sub))
 
 constexpr int kPGroups = 256;        // workgroups of the persistent kernel (tile geometry is fixed for it)
 constexpr int kNG = 9;               // register groups of 4 rows per wavefront
 constexpr int kSlots = 4 * kNG;      // rows a wavefront holds: 36 (a tile has at most 8 * 36 = 288 rows)
+constexpr int kMaxTileRows = kSlots * kWaves;   // 288
 constexpr int kStageFloats = 8192;   // LDS staging for polled partials
-constexpr int kTopWMax = 12288;      // floats of W_L kept in LDS
-constexpr int kTopXMax = 4096;
+constexpr int kTopWMax = 10240;      // floats of W_L kept in LDS
+constexpr int kTopXMax = 2048;       // neurons of layer L-1 the output phase can take
 
 struct PLayer {
     float* W; float* b; float* x; float* d;
@@ -86,78 +104,41 @@ struct PNet {
 
 // LDS map (floats)
 struct PLds {
-    static constexpr int WL = 0;                                  // [kTopWMax]
+    static constexpr int WL = 0;                                  // [kTopWMax]  private copy of W_L
     static constexpr int bL = WL + kTopWMax;                      // [kMaxClasses]
-    static constexpr int logit = bL + kMaxClasses;                // [kMaxClasses]
-    static constexpr int dL = logit + kMaxClasses;                // [kMaxClasses]
-    static constexpr int xkeep = dL + kMaxClasses;                // [kMaxLayers + 1][256]
-    static constexpr int stage = xkeep + (kMaxLayers + 1) * 256;  // [kStageFloats]
-    static constexpr int dl = stage + kStageFloats;               // [kSlots * kWaves]
-    static constexpr int ysum = dl + kSlots * kWaves;             // [4][kSlots * kWaves]
-    static constexpr int gred = ysum + 4 * kSlots * kWaves;       // [kWaves][256]
+    static constexpr int xkeep = bL + kMaxClasses;                // [kMaxLayers + 1][256] inputs of each tile
+    static constexpr int bias = xkeep + (kMaxLayers + 1) * 256;   // [kMaxLayers + 1][kMaxTileRows] (column block 0)
+    static constexpr int stage = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kStageFloats]
+    static constexpr int ysum = stage + kStageFloats;             // [4][kMaxTileRows]
+    static constexpr int gred = ysum + 4 * kMaxTileRows;          // [kWaves][256]; [32][16] partial logits
     static constexpr int xtop = gred + kWaves * 256;              // [kTopXMax]
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
-    static constexpr int total = dtop + kTopXMax;
+    static constexpr int fail = dtop + kTopXMax;                  // [1] set when a wait gave up
+    static constexpr int total = fail + 16;
 };
+static_assert(PLds::total * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
 
 __device__ inline u64 pack_tagged(float v, unsigned tag) { return ((u64)tag << 32) | (u64)__float_as_uint(v); }
 
-// Wait for tagged words of step `tag` and put their float payloads into LDS.  The words come from
-// two strided sources that share the row length `len` <= 512: srcA[p * stride + j] (p < PA) lands
-// at stage[p * pitch + j], srcB[p * stride + j] (p < PB) behind them at stage[(PA + p) * pitch + j]
-// (PB may be 0).  Threads are laid out as rows of 2^lg >= len lanes over consecutive j, so that no
-// division is needed and a wavefront reads runs of consecutive words; every thread keeps up to 8
-// loads in flight, and a wavefront re-reads its batch until all of it carries the tag (the loop
-// is wavefront-uniform: no divergent control flow around the loads).  Returns false when the
-// spin limit ran out.
-__device__ inline bool poll_to_lds(const u64* srcA, int PA, const u64* srcB, int PB, int len, size_t stride,
- unsigned tag, float* stage, int pitch, unsigned limit, int backoff,
-                                   unsigned* rounds = nullptr) {
-    int lg = 5;                                   // rows of 32, 64, 128 or 256 lanes
-    while ((1 << lg) < len) ++lg;
-    const int j = (int)threadIdx.x & ((1 << lg) - 1);
-    const int prow = (int)threadIdx.x >> lg;      // first partial this thread reads
-    const int pstep = kThreads >> lg;             // partials covered by one pass of the workgroup
-    const int P = PA + PB;
-    const bool jon = j < len;
-    bool ok = true;
-    for (int p0 = 0; p0 < P; p0 += 8 * pstep) {
-        const u64* a[8];
-        bool valid[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int p = p0 + prow + k * pstep;
-            valid[k] = jon && p < P;
-            const u64* base = (p < PA || !valid[k]) ? srcA : srcB;
-            const int pp = !valid[k] ? 0 : (p < PA ? p : p - PA);
-            a[k] = base + (size_t)pp * stride + (valid[k] ? j : 0);
-        }
-        u64 v[8];
-        unsigned spins = 0;
-        for (;;) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(a[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            bool pending = false;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) pending |= valid[k] && ((unsigned)(v[k] >> 32) != tag);
-            if (!__any(pending)) break;
-            if (++spins > limit) { ok = false; break; }
-            for (int z = 0; z < backoff; ++z) __builtin_amdgcn_s_sleep(1);
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (valid[k]) stage[(p0 + prow + k * pstep) * pitch + j] = __uint_as_float((unsigned)v[k]);
-        if (rounds) *rounds += spins + 1;
-        if (!ok) break;
-    }
-    return ok;
+// Workgroup barrier that orders LDS traffic only.  The workgroup's wavefronts talk to each other
+// through LDS alone, so a barrier need not wait for outstanding global stores (the tagged words
+// published for other workgroups take about a microsecond to be acknowledged); __syncthreads()
+// would.
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// true when every thread of the workgroup succeeded; otherwise raises the error flag
-__device__ inline bool all_ok(bool ok, int* err) {
-    const int r = __syncthreads_and(ok ? 1 : 0);
-    if (!r && threadIdx.x == 0) __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return r != 0;
+// Barrier + agreement: true when every thread of the workgroup succeeded; otherwise raises the
+// error flag.  (The LDS flag is never cleared: a failure ends the kernel.)
+__device__ inline bool all_ok(bool ok, int* err, float* lds) {
+    int* fail = reinterpret_cast<int*>(lds + PLds::fail);
+    if (!ok) *fail = 1;
+    lds_barrier();
+    const bool bad = *fail != 0;
+    if (bad && threadIdx.x == 0) __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return !bad;
 }
 
 // Cross-lane data movement on the vector ALU (DPP), no LDS traffic.
@@ -196,24 +177,114 @@ __device__ inline float quad_sum4(float a0, float a1, float a2, float a3) {
     return v;   // sum over this row of 16 lanes; the caller adds the four rows (xor 16, xor 32)
 }
 
-// sum over p < P of stage[p * len + j], in index order; the LDS reads go out eight at a time
-__device__ inline float sum_partials(const float* stage, int P, int len, int j) {
+__device__ inline u64 ld_tagged(const u64* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One column per thread: wait for the P tagged words src[p * stride] (p < P) of step `tag` and
+// return the sum of their payloads in index order.  Up to 16 loads in flight (one round trip for
+// P <= 16); a wavefront re-reads a batch until all its lanes have it (wavefront-uniform loop, so
+// every lane must pass a readable src; lanes without a column of their own pass any valid one
+// and ignore the result).
+__device__ inline float poll_sum(const u64* src, int P, size_t stride, unsigned tag, unsigned limit, bool& ok) {
     float s = 0.0f;
-    int p = 0;
-    for (; p + 8 <= P; p += 8) {
+    for (int p0 = 0; p0 < P; p0 += 16) {
+        const int nb = min(16, P - p0);
+        u64 v[16];
+        unsigned spins = 0;
+        for (;;) {
+            const u64* a = src + (size_t)p0 * stride;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (k < nb) v[k] = ld_tagged(a);
+                a += stride;
+            }
+            bool pending = false;
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (k < nb) pending |= ((unsigned)(v[k] >> 32) != tag);
+            if (!__any(pending)) break;
+            if (++spins > limit) { ok = false; break; }
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < nb) s += __uint_as_float((unsigned)v[k]);
+        if (!ok) break;
+    }
+    return s;
+}
+
+// Row layout of the staging area used by the backward phase: row j holds its P partials
+// contiguously, P rounded up to a multiple of 4 and padded with zeros, rows PP floats apart with
+// PP odd (bank-conflict-free both for the scattered writes and for the reads).
+__device__ inline int stage_quarter(int P) { return (P + 3) >> 2; }
+__device__ inline int stage_pitch(int P) { return (4 * stage_quarter(P)) | 1; }
+
+// Wait for the tagged words src[p * stride + j] (p < P, j < len <= 256) of step `tag` and put their
+// payloads at stage[j * PP + p].  Called by the lower four wavefronts only (kPollThreads threads,
+// see the note on loads and stores in p_fwd_tile): they form rows of 2^lg >= len lanes over
+// consecutive j, so that a wavefront reads runs of consecutive words; 16 loads in flight per thread.
+constexpr int kPollThreads = 256;
+__device__ inline bool poll_rows_to_lds(const u64* src, int P, int len, size_t stride, unsigned tag, float* stage,
+                                        unsigned limit) {
+    int lg = 5;
+    while ((1 << lg) < len) ++lg;
+    const int j = (int)threadIdx.x & ((1 << lg) - 1);
+    const int prow = (int)threadIdx.x >> lg;
+    const int pstep = kPollThreads >> lg;
+    const int PP = stage_pitch(P), Ppad = 4 * stage_quarter(P);
+    const bool jon = j < len;
+    const u64* col = src + (jon ? j : 0);
+    float* row = stage + j * PP;
+    bool ok = true;
+    for (int p0 = prow; p0 - prow < Ppad; p0 += 16 * pstep) {   // (uniform trip count over the wavefront)
+        u64 v[16];
+        bool valid[16];
+        const u64* a[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int p = p0 + k * pstep;
+            valid[k] = jon && p < P;
+            a[k] = col + (size_t)(valid[k] ? p : 0) * stride;
+        }
+        unsigned spins = 0;
+        for (;;) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) v[k] = ld_tagged(a[k]);
+            bool pending = false;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) pending |= valid[k] && ((unsigned)(v[k] >> 32) != tag);
+            if (!__any(pending)) break;
+            if (++spins > limit) { ok = false; break; }
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int p = p0 + k * pstep;
+            if (jon && p < Ppad) row[p] = valid[k] ? __uint_as_float((unsigned)v[k]) : 0.0f;
+        }
+        if (!ok) break;
+    }
+    return ok;
+}
+
+// Thread (j, q), q = 0..3, adds quarter q of row j of the staging area in index order; the four
+// quarter sums are then combined inside the quad of lanes as (q0 + q1) + (q2 + q3).  All four
+// lanes of a quad (lanes 4a .. 4a+3 hold the same j) return the row sum.
+__device__ inline float sum_row4(const float* stage, int P, int j, int q) {
+    const int P4 = stage_quarter(P);
+    const float* r = stage + j * stage_pitch(P) + q * P4;
+    float s = 0.0f;
+    for (int k0 = 0; k0 < P4; k0 += 8) {
         float v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = stage[(p + k) * len + j];
+        for (int k = 0; k < 8; ++k)
+            if (k0 + k < P4) v[k] = r[k0 + k];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) s += v[k];
+        for (int k = 0; k < 8; ++k)
+            if (k0 + k < P4) s += v[k];
     }
-    if (p < P) {
-        float v[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = (p + k < P) ? stage[(p + k) * len + j] : 0.0f;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) s += v[k];   // adding the zeros of the tail changes nothing
-    }
+    s += dpp_mov<kDppXor1>(s);
+    s += dpp_mov<kDppXor2>(s);
     return s;
 }
 
@@ -294,9 +365,8 @@ __device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const PLa
 
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
 // partial sums of the rows over the tile's columns, the bias riding on column block 0.
-__device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g,
-                                           const float* __restrict__ x0, unsigned tag, float* lds, long long ps,
-                                           int ph) {
+__device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float x0pre,
+                                           unsigned tag, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
     const PLayer& Ly = net.lay[l];
     TileCtx t;
     if (!tile_ctx(Ly, g, t)) return true;
@@ -308,28 +378,22 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
 
     float* xk = lds + PLds::xkeep + l * 256;
     if (l == 1) {
-        if (threadIdx.x < 256) xk[threadIdx.x] = (threadIdx.x < t.Ceff) ? x0[t.c0 + threadIdx.x] : 0.0f;
+        // the caller fetched this thread's input pixel ahead of time
+        if (threadIdx.x < 256) xk[threadIdx.x] = (threadIdx.x < t.Ceff) ? x0pre : 0.0f;
+        lds_barrier();
     } else {
+        // thread j < Ceff gathers the nCB partial sums of its input column j, adds them in index
+        // order and applies the activation: x_{l-1}[c0 + j]
         const PLayer& Lp = net.lay[l - 1];
-        float* stage = lds + PLds::stage;
-        const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0;
-        unsigned rounds = 0;
-        const bool ok = poll_to_lds(src, Lp.nCB, nullptr, 0, t.Ceff, (size_t)Lp.n_out, tag, stage, t.Ceff,
-                                    net.spin_limit, net.backoff, &rounds);
-        DBSN_PROF_VAL(ps, (2 * net.L - 1) * 4 + ph, rounds);
-        DBSN_PROF(ps, (2 * net.L - 1) * 5 + ph * 3 + 0);
-        if (!all_ok(ok, net.err)) return false;
-        DBSN_PROF(ps, (2 * net.L - 1) * 5 + ph * 3 + 1);
+        bool ok = true;
         if (threadIdx.x < 256) {
-            float s = 0.0f;
-            if (threadIdx.x < t.Ceff) {
-                s = act_fast(sum_partials(stage, Lp.nCB, t.Ceff, threadIdx.x));
-                if (t.rb == 0) Lp.x[t.c0 + threadIdx.x] = s;   // state read-out (dbsn_mlp_get_activations)
-            }
-            xk[threadIdx.x] = s;
+            const bool on = (int)threadIdx.x < t.Ceff;
+            const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0 + (on ? threadIdx.x : 0);
+            const float a = poll_sum(src, Lp.nCB, (size_t)Lp.n_out, tag, net.spin_limit, ok);
+            xk[threadIdx.x] = on ? act_fast(a) : 0.0f;
         }
+        if (!all_ok(ok, net.err, lds)) return false;
     }
-    __syncthreads();
     DBSN_PROF_SUB(ps, ph, 1);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     float* ysum = lds + PLds::ysum;
@@ -340,16 +404,24 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
         const float v = quad_sum4(dot4(wr[4 * G_ + 0], x4), dot4(wr[4 * G_ + 1], x4), dot4(wr[4 * G_ + 2], x4),
                                   dot4(wr[4 * G_ + 3], x4));
         const int rl = wave + kWaves * (sbase_ + (lane & 3));
-        if ((lane & 12) == 0) ysum[lrow * (kSlots * kWaves) + rl] = v;
+        if ((lane & 12) == 0) ysum[lrow * kMaxTileRows + rl] = v;
     })
-    __syncthreads();
+    lds_barrier();
     DBSN_PROF_SUB(ps, ph, 2);
-    u64* dst = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + (size_t)t.cb * Ly.n_out + t.r0;
-    for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
-        constexpr int kYS = kSlots * kWaves;
-        float v = (ysum[j] + ysum[kYS + j]) + (ysum[2 * kYS + j] + ysum[3 * kYS + j]);
-        if (t.cb == 0) v += Ly.b[t.r0 + j];
-        __hip_atomic_store(dst + j, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // Only the upper four wavefronts store to global memory, only the lower four load from it: a
+    // wavefront's loads complete behind its earlier stores, and the acknowledgement of a published
+    // word takes about as long as the whole phase.
+    if (threadIdx.x >= 256) {
+        u64* dst = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + (size_t)t.cb * Ly.n_out + t.r0;
+        for (int j = threadIdx.x - 256; j < t.Reff; j += 256) {
+            constexpr int kYS = kMaxTileRows;
+            float v = (ysum[j] + ysum[kYS + j]) + (ysum[2 * kYS + j] + ysum[3 * kYS + j]);
+            if (t.cb == 0) v += lds[PLds::bias + l * kMaxTileRows + j];
+            __hip_atomic_store(dst + j, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // state read-out (dbsn_mlp_get_activations): row block 0 writes the inputs it gathered
+        if (l > 1 && t.rb == 0 && (int)threadIdx.x - 256 < t.Ceff)
+            net.lay[l - 1].x[t.c0 + threadIdx.x - 256] = xk[threadIdx.x - 256];
     }
     DBSN_PROF_SUB(ps, ph, 3);
     return true;
@@ -360,7 +432,7 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
 // its columns from the OLD weights (published first, it is what other workgroups wait for), then
 // the rank-1 update of the tile.
 __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float eta,
-                                           unsigned tag, float* lds, long long ps, int ph) {
+                                           unsigned tag, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
     const PLayer& Ly = net.lay[l];
     TileCtx t;
     if (!tile_ctx(Ly, g, t)) return true;
@@ -370,28 +442,36 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 0);
     if (!net.stationary) load_tile(wr, Ly, t);
 
-    float* dl = lds + PLds::dl;
-    float* sg = lds + PLds::stage;
+    // deltas of the tile's rows: four threads per row add the partials of the layer above (the
+    // producers have multiplied them by f'(x_l) already, see below); then lane s < 36 of a
+    // wavefront picks up the delta of the wavefront's s-th row (tile row wave + 8 s), and the
+    // register slots read it from there by lane index
+    float* dl = lds + PLds::ysum;   // free during the backward sweep
     if (l == net.L - 1) {
         // the output layer was evaluated in this workgroup: its deltas are already in LDS
         for (int j = threadIdx.x; j < t.Reff; j += kThreads) dl[j] = lds[PLds::dtop + t.r0 + j];
+        lds_barrier();
     } else {
+        float* sg = lds + PLds::stage;
         const u64* gsrc = Ly.gp + (size_t)par * Ly.gP * Ly.n_out + t.r0;
-        unsigned rounds = 0;
-        const bool ok = poll_to_lds(gsrc, Ly.gP, nullptr, 0, t.Reff, (size_t)Ly.n_out, tag, sg, t.Reff,
-                                    net.spin_limit, net.backoff, &rounds);
-        DBSN_PROF_VAL(ps, (2 * net.L - 1) * 4 + ph, rounds);
-        if (!all_ok(ok, net.err)) return false;
-        // the producers multiplied their partial sums by f'(x_l) already (they hold x_l, see below)
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) dl[j] = sum_partials(sg, Ly.gP, t.Reff, j);
+        bool ok = true;
+        if (threadIdx.x < kPollThreads)
+            ok = poll_rows_to_lds(gsrc, Ly.gP, t.Reff, (size_t)Ly.n_out, tag, sg, net.spin_limit);
+        if (!all_ok(ok, net.err, lds)) return false;
+        for (int t4 = threadIdx.x; (t4 >> 2) - (lane >> 2) < t.Reff; t4 += kThreads) {
+            // (trip count uniform over the wavefront: sum_row4 exchanges data inside quads)
+            const int j = t4 >> 2;
+            const float d = sum_row4(sg, Ly.gP, min(j, t.Reff - 1), t4 & 3);
+            if ((t4 & 3) == 0 && j < t.Reff) dl[j] = d;
+        }
+        lds_barrier();
     }
-    __syncthreads();
+    const int myrow = wave + kWaves * lane;
+    const bool rowon = lane < kSlots && myrow < t.Reff;
+    const float dlane = rowon ? dl[myrow] : 0.0f;
     DBSN_PROF_SUB(ps, ph, 1);
     const float* xk = lds + PLds::xkeep + l * 256;
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
-    // lane s of a wavefront fetches the delta of the wavefront's s-th row; slots read it by lane index
-    const int myrow = wave + kWaves * lane;
-    const float dlane = (lane < kSlots && myrow < t.Reff) ? dl[myrow] : 0.0f;
     if (l > 1) {
         float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
         DBSN_FOR_LAYER_SLOTS(Ly, {
@@ -406,20 +486,21 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         })
         float* gred = lds + PLds::gred;
         *reinterpret_cast<float4*>(gred + wave * 256 + 4 * lane) = gacc;
-        __syncthreads();
+        lds_barrier();
         const PLayer& Lp = net.lay[l - 1];
         u64* dst = Lp.gp + (size_t)par * Lp.gP * Lp.n_out + (size_t)t.rb * Lp.n_out + t.c0;
-        if (threadIdx.x < t.Ceff) {
+        const int i = (int)threadIdx.x - 256;   // the upper four wavefronts publish
+        if (i >= 0 && i < t.Ceff) {
             float v[kWaves];
 #pragma unroll
-            for (int k = 0; k < kWaves; ++k) v[k] = gred[k * 256 + threadIdx.x];
+            for (int k = 0; k < kWaves; ++k) v[k] = gred[k * 256 + i];
             float s = 0.0f;
 #pragma unroll
             for (int k = 0; k < kWaves; ++k) s += v[k];
             // this tile's columns are neurons of layer l-1 whose outputs it holds: fold f' in here,
             // so that the consumer's sum over row blocks is delta_{l-1} itself
-            s *= dact_from_y(xk[threadIdx.x]);
-            __hip_atomic_store(dst + threadIdx.x, pack_tagged(s, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s *= dact_from_y(xk[i]);
+            __hip_atomic_store(dst + i, pack_tagged(s, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     DBSN_PROF_SUB(ps, ph, 2);
@@ -437,124 +518,129 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     })
     if (!net.stationary) store_tile(wr, Ly, t);
     if (t.cb == 0) {
-        // bias update, and the layer's deltas for dbsn_mlp_get_deltas
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
+        // bias update (the biases of this tile's rows live in LDS for the whole launch), and the
+        // layer's deltas for dbsn_mlp_get_deltas (stored by the upper wavefronts)
+        for (int j = (int)threadIdx.x - 256; j >= 0 && j < t.Reff; j += 256) {
             const float d = dl[j];
-            Ly.b[t.r0 + j] -= eta * d;
+            lds[PLds::bias + l * kMaxTileRows + j] -= eta * d;
             Ly.d[t.r0 + j] = d;
         }
     }
-    __syncthreads();
+    lds_barrier();
     DBSN_PROF_SUB(ps, ph, 3);
     return true;
 }
 
 // Output layer in every workgroup, on its private LDS copy of W_L: x_{L-1} from the partials,
 // logits, softmax, loss, delta_L, the deltas of layer L-1 and the rank-1 update of the copy.
-// Thread i owns column i (input neuron i) of W_L: it forms the products W_L[j][i] x_i, the
-// workgroup adds them per class (quads -> rows of 16 lanes on the vector ALU, then through LDS),
-// and after the softmax the same thread back-propagates and updates its column.
+// Thread i owns column i (input neuron i) of W_L: it gathers x_i and forms the products
+// W_L[j][i] x_i; the workgroup adds them per class (quads -> rows of 16 lanes on the vector ALU,
+// then 32 partial sums per class through LDS); wavefront 0 does the softmax, and each thread
+// back-propagates through and updates its column.
 __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
-                                      float* lds, long long ps, int ph) {
+                                      float* lds, long long ps, int ph DBSN_PROF_ARGS) {
     const int L = net.L;
     const PLayer& Ly = net.lay[L];
     const PLayer& Lp = net.lay[L - 1];
     const int n = Ly.n_in, nc = Ly.n_out;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
-    float* stage = lds + PLds::stage;
     float* xtop = lds + PLds::xtop;
     float* dtop = lds + PLds::dtop;
     float* WL = lds + PLds::WL;
     float* bL = lds + PLds::bL;
-    float* logit = lds + PLds::logit;
-    float* dL = lds + PLds::dL;
-    float* part = lds + PLds::gred;   // [kMaxClasses][32] partial logits: 8 wavefronts x 4 rows of 16 lanes
+    float* part = lds + PLds::gred;    // [class][33]: 8 wavefronts x 4 rows of 16 lanes (pitch 33: no bank conflicts)
+    float* dL = lds + PLds::ysum;      // [kMaxClasses] delta_L
 
     DBSN_PROF_SUB(ps, ph, 0);
-    const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
-    unsigned rounds = 0;
     bool ok = true;
-    for (int j0 = 0; j0 < n && ok; j0 += kThreads)
-        ok = poll_to_lds(src + j0, Lp.nCB, nullptr, 0, min(kThreads, n - j0), (size_t)Lp.n_out, tag, stage + j0, n,
-                         net.spin_limit, net.backoff, &rounds);
-    DBSN_PROF_VAL(ps, (2 * net.L - 1) * 4 + ph, rounds);
-    if (!all_ok(ok, net.err)) return false;
-    DBSN_PROF_SUB(ps, ph, 1);
-
-    // products per class, 16 classes at a time; columns beyond 512 are folded into the same thread
-    for (int j0 = 0; j0 < nc; j0 += 16) {
-        float acc[16];
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.0f;
-        for (int i = threadIdx.x; i < n; i += kThreads) {
-            const float xi = act_fast(sum_partials(stage, Lp.nCB, n, i));
-            if (j0 == 0) {
-                xtop[i] = xi;
-                if (g == 0) Lp.x[i] = xi;   // state read-out (dbsn_mlp_get_activations)
-            }
-            float wv[16];
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) wv[jj] = (j0 + jj < nc) ? WL[(j0 + jj) * n + i] : 0.0f;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) acc[jj] = fmaf(wv[jj], xi, acc[jj]);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float v = quad_sum4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-            const int cls = j0 + 4 * q + (lane & 3);
-            if ((lane & 12) == 0 && cls < nc) part[cls * 32 + wave * 4 + (lane >> 4)] = v;
+    if (threadIdx.x < kPollThreads) {
+        // the lower four wavefronts gather x_{L-1} (they are the ones that load from global memory)
+        const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
+        for (int i0 = 0; i0 < n; i0 += kPollThreads) {
+            const int i = i0 + (int)threadIdx.x;
+            const bool on = i < n;
+            const float a = poll_sum(src + (on ? i : 0), Lp.nCB, (size_t)Lp.n_out, tag, net.spin_limit, ok);
+            if (on) xtop[i] = act_fast(a);
         }
     }
-    __syncthreads();
+    if (!all_ok(ok, net.err, lds)) return false;
+    DBSN_PROF_SUB(ps, ph, 1);
+    // products per class, four classes at a time; a thread folds its columns i, i + 512, ... together
+    for (int j0 = 0; j0 < nc; j0 += 4) {
+        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+        const int j1 = min(j0 + 1, nc - 1), j2 = min(j0 + 2, nc - 1), j3 = min(j0 + 3, nc - 1);
+        for (int i = threadIdx.x; i < n; i += kThreads) {
+            const float xi = xtop[i];
+            a0 = fmaf(WL[j0 * n + i], xi, a0);
+            a1 = fmaf(WL[j1 * n + i], xi, a1);
+            a2 = fmaf(WL[j2 * n + i], xi, a2);
+            a3 = fmaf(WL[j3 * n + i], xi, a3);
+        }
+        const float v = quad_sum4(a0, a1, a2, a3);
+        const int cls = j0 + (lane & 3);
+        if ((lane & 12) == 0 && cls < nc) part[cls * 33 + wave * 4 + (lane >> 4)] = v;
+    }
+    lds_barrier();
     DBSN_PROF_SUB(ps, ph, 2);
     if (wave == 0) {
-        // logits and softmax over nc <= 64 classes, one class per lane
+        // class c = lane: logit, softmax (the sum of the exponentials is taken in index order)
         float a = -3.0e38f;
-        if (lane < nc) a = sum_partials(part + lane * 32, 32, 1, 0) + bL[lane];
+        if (lane < nc) {
+            float v[32];
+#pragma unroll
+            for (int r = 0; r < 32; ++r) v[r] = part[lane * 33 + r];
+            float acc = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 32; ++r) acc += v[r];
+            a = acc + bL[lane];
+        }
         float m = a;
         m = fmaxf(m, dpp_mov<kDppXor1>(m));
         m = fmaxf(m, dpp_mov<kDppXor2>(m));
         m = fmaxf(m, dpp_mov<kDppRor4>(m));
         m = fmaxf(m, dpp_mov<kDppRor8>(m));
-        m = fmaxf(m, __shfl_xor(m, 16, 64));
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
-        const float e = (lane < nc) ? expf(a - m) : 0.0f;
-        if (lane < nc) logit[lane] = e;       // scratch: exponentials
-        // (LDS serves one wavefront's accesses in program order: the reads below see these writes)
-        const float s = sum_partials(logit, nc, 1, 0);   // index order
-        const float p = e / s;
-        const float d = p - (lane == label ? 1.0f : 0.0f);
-        const float pl = __shfl(p, label, 64);
-        if (lane < nc) {
-            dL[lane] = d;
-            if (g == 0) { Ly.x[lane] = p; Ly.d[lane] = d; }
+        if (nc > 16) {
+            m = fmaxf(m, __shfl_xor(m, 16, 64));
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+        } else {
+            m = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(m)));   // row 0 holds all classes
         }
-        if (g == 0 && lane == 0 && loss_out) *loss_out = -logf(pl);
+        const float e = (lane < nc) ? expf(a - m) : 0.0f;
+        float ssum = 0.0f;
+        for (int c = 0; c < nc; ++c) ssum += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e), c));
+        const float p = e / ssum;
+        if (lane < nc) {
+            dL[lane] = p - (lane == label ? 1.0f : 0.0f);
+            dL[kMaxClasses + lane] = p;
+        }
     }
-    __syncthreads();
-    // deltas of layer L-1 and update of the private W_L, 16 classes at a time from registers
+    lds_barrier();
+    if (g == 0 && wave == kWaves - 1) {
+        // results of the step for the host: probabilities, output deltas, loss, x_{L-1} (the last
+        // wavefront stores them: it never waits for a load from global memory)
+        if (lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
+        if (lane == 0 && loss_out) *loss_out = -logf(dL[kMaxClasses + label]);
+        for (int i = lane; i < n; i += 64) Lp.x[i] = xtop[i];
+    }
+    // deltas of layer L-1 and update of the private W_L
     for (int i = threadIdx.x; i < n; i += kThreads) {
         const float xi = xtop[i];
         float gs = 0.0f;
-        for (int j0 = 0; j0 < nc; j0 += 16) {
-            float wv[16], dj[16];
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                const bool on = j0 + jj < nc;
-                wv[jj] = on ? WL[(j0 + jj) * n + i] : 0.0f;
-                dj[jj] = on ? dL[j0 + jj] : 0.0f;
-            }
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                gs = fmaf(wv[jj], dj[jj], gs);
-                if (j0 + jj < nc) WL[(j0 + jj) * n + i] = fmaf(-(eta * dj[jj]), xi, wv[jj]);
-            }
+        for (int j0 = 0; j0 < nc; j0 += 4) {
+            const int j1 = min(j0 + 1, nc - 1), j2 = min(j0 + 2, nc - 1), j3 = min(j0 + 3, nc - 1);
+            const float w0 = WL[j0 * n + i], w1 = WL[j1 * n + i], w2 = WL[j2 * n + i], w3 = WL[j3 * n + i];
+            const float d0 = dL[j0], d1 = dL[j1], d2 = dL[j2], d3 = dL[j3];
+            gs = fmaf(w0, d0, gs);
+            WL[j0 * n + i] = fmaf(-(eta * d0), xi, w0);
+            if (j0 + 1 < nc) { gs = fmaf(w1, d1, gs); WL[j1 * n + i] = fmaf(-(eta * d1), xi, w1); }
+            if (j0 + 2 < nc) { gs = fmaf(w2, d2, gs); WL[j2 * n + i] = fmaf(-(eta * d2), xi, w2); }
+            if (j0 + 3 < nc) { gs = fmaf(w3, d3, gs); WL[j3 * n + i] = fmaf(-(eta * d3), xi, w3); }
         }
         dtop[i] = gs * dact_from_y(xi);
     }
     if (threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
-    __syncthreads();
+    lds_barrier();
     DBSN_PROF_SUB(ps, ph, 3);
     return true;
 }
@@ -563,6 +649,7 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
                                                            int label_val, long long n, float eta, float* loss_out,
                                                            unsigned tag_base) {
     extern __shared__ float lds[];
+    DBSN_PROF_DECL;
     const int g = blockIdx.x, L = net.L;
     const PLayer& LyL = net.lay[L];
     const int n0 = net.lay[1].n_in;
@@ -573,7 +660,14 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     if (threadIdx.x < LyL.n_out) lds[PLds::bL + threadIdx.x] = LyL.b[threadIdx.x];
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
+    if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
 
+    for (int l = 1; l < L; ++l) {
+        TileCtx t;
+        if (tile_ctx(net.lay[l], g, t) && t.cb == 0)
+            for (int j = threadIdx.x; j < t.Reff; j += kThreads)
+                lds[PLds::bias + l * kMaxTileRows + j] = net.lay[l].b[t.r0 + j];
+    }
     float4 wr[kSlots];
 #pragma unroll
     for (int s = 0; s < kSlots; ++s) wr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -585,15 +679,25 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     __syncthreads();
 
+    // this thread's input pixel of the first layer's tile, fetched one sample ahead
+    TileCtx t1;
+    const bool has1 = tile_ctx(net.lay[1], g, t1) && (int)threadIdx.x < t1.Ceff;
+    float x0pre = (has1 && n > 0) ? samples[t1.c0 + threadIdx.x] : 0.0f;
+    int labpre = (labels && n > 0) ? labels[0] : label_val;
+
     bool alive = true;
     for (long long s = 0; s < n && alive; ++s) {
         const unsigned tag = tag_base + (unsigned)s + 1u;
-        const float* x0 = samples + s * n0;
-        int label = labels ? labels[s] : label_val;
+        int label = labpre;
         label = label < 0 ? 0 : (label >= LyL.n_out ? LyL.n_out - 1 : label);
-        for (int l = 1; l < L && alive; ++l) alive = p_fwd_tile(wr, net, l, g, x0, tag, lds, s, l - 1);
-        if (alive) alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, lds, s, L - 1);
-        for (int l = L - 1; l >= 1 && alive; --l) alive = p_bwd_tile(wr, net, l, g, eta, tag, lds, s, L + (L - 1 - l));
+        const float x0cur = x0pre;
+        if (s + 1 < n) {
+            if (has1) x0pre = samples[(s + 1) * n0 + t1.c0 + threadIdx.x];
+            if (labels) labpre = labels[s + 1];
+        }
+        for (int l = 1; l < L && alive; ++l) alive = p_fwd_tile(wr, net, l, g, x0cur, tag, lds, s, l - 1 DBSN_PROF_PASS);
+        if (alive) alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, lds, s, L - 1 DBSN_PROF_PASS);
+        for (int l = L - 1; l >= 1 && alive; --l) alive = p_bwd_tile(wr, net, l, g, eta, tag, lds, s, L + (L - 1 - l) DBSN_PROF_PASS);
     }
     if (net.stationary) {
         for (int l = 1; l < L; ++l) {
@@ -601,6 +705,14 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
             if (tile_ctx(net.lay[l], g, t)) store_tile(wr, net.lay[l], t);
         }
     }
+    __syncthreads();
+    for (int l = 1; l < L; ++l) {
+        TileCtx t;
+        if (tile_ctx(net.lay[l], g, t) && t.cb == 0)
+            for (int j = threadIdx.x; j < t.Reff; j += kThreads)
+                net.lay[l].b[t.r0 + j] = lds[PLds::bias + l * kMaxTileRows + j];
+    }
+    DBSN_PROF_FLUSH();
     if (g == 0) {
         __syncthreads();
         for (int e = threadIdx.x; e < LyL.n_out * LyL.n_in; e += kThreads) {
