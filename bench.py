@@ -148,7 +148,7 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None,
-            "kernel": "k_bp_persistent" if args.mode == 1 else "k_fwd/k_bwd/k_top",
+            "kernel": "k_bp_dataflow" if args.mode == 1 else "k_fwd/k_bwd/k_top",
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "avg_launch_ms": bp_avg_s * 1e3,
             "us_per_sample": bp_avg_s / chunk * 1e6,

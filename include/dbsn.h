@@ -62,7 +62,8 @@ typedef struct {
  * through tagged words in device memory.  Both compute the same step; they add partial sums in
  * different (each fixed) orders, so results agree to rounding, and each mode is bit-reproducible
  * from run to run.  Shapes the persistent kernel does not hold (no hidden layer, an output layer
- * of more than 12288 weights) run in mode 0 whatever is selected. */
+ * of more than 10240 weights or more than 2048 inputs, a layer whose 256 tiles would exceed 224
+ * rows each) run in mode 0 whatever is selected. */
 #define DBSN_MODE_LAUNCHES   0
 #define DBSN_MODE_PERSISTENT 1
 

@@ -99,15 +99,14 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         p.yp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nCB[l] * sizes[l]);
         if (l <= L - 2) {
             p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l + 1] * sizes[l]);
-            // the staging area holds the gp and the yp partials of a tile's rows side by side
             // staging of one tile's partials: R rows of nRB_{l+1} words, padded to an odd pitch
             if (p.R[l] * ((((p.nRB[l + 1] + 3) / 4) * 4) | 1) > kStageFloats) p.persistent_ok = false;
         }
     }
-    // register groups of 4 rows per wavefront: stationary when every layer gets groups of its own
+    // register groups of kGR rows per wavefront: stationary when every layer gets groups of its own
     int groups = 0;
     for (int l = 1; l < L; ++l) {
-        p.ng[l] = ((p.R[l] + kWaves - 1) / kWaves + 3) / 4;
+        p.ng[l] = ((p.R[l] + kWaves - 1) / kWaves + kGR - 1) / kGR;
         if (p.ng[l] > kNG) p.persistent_ok = false;
         groups += p.ng[l];
     }
@@ -209,7 +208,8 @@ int32_t steps_launches(dbsn_mlp* m, const float* samples, const int* labels, int
 int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n, float eta,
                          float* loss) {
     const size_t lds = sizeof(float) * (size_t)(PLds::total + kProfLdsFloats);
-    const void* fn = reinterpret_cast<const void*>(&k_bp_dataflow);
+    const void* fn = m->pnet.stationary ? reinterpret_cast<const void*>(&k_bp_dataflow<true>)
+                                        : reinterpret_cast<const void*>(&k_bp_dataflow<false>);
     if (!m->persistent_ready) {
         if (lds > m->lds_limit) return fail(DBSN_E_SHAPE, "persistent kernel needs %zu B of LDS", lds);
         HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));

@@ -21,13 +21,14 @@
 //    and applies the same update to its private copy (same code, same inputs, same bits), so the
 //    deltas of the last hidden layer are available everywhere without communication.
 //  * Weights live in REGISTERS.  A wavefront owns rows wave, wave+8, ... of a tile, one 128-bit
-//    register quadruple per row and lane, in groups of four rows.  The 256 workgroups x 8
-//    wavefronts x 36 quadruples hold 75 MB: when all tiles of a workgroup fit (they do for every
-//    net of the paper, 48 MB at most) the weights are loaded once per launch, updated in place
-//    for n steps and written back at the end ("stationary"); the memory system then carries
-//    only the small tagged words, and a step costs its chain of hand-overs, not its bytes.
-//    Otherwise each phase loads its tile into the same registers (the loads are issued before
-//    the wait for the inputs, so they overlap it) and the backward phase stores it back.
+//    register quadruple per row and lane (a lane holds four consecutive columns), in groups of
+//    kGR rows.  The 256 workgroups x 8 wavefronts x kSlots quadruples hold 58 MB: when all tiles
+//    of a workgroup fit (they do for every net of the paper, 48 MB at most) the weights are
+//    loaded once per launch, updated in place for n steps and written back at the end
+//    ("stationary"); the memory system then carries only the small tagged words, and a step
+//    costs its chain of hand-overs, not its bytes.  Otherwise each phase loads its tile into the
+//    same registers (the loads are issued before the wait for the inputs, so they overlap it)
+//    and the backward phase stores it back.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -42,7 +43,7 @@ typedef unsigned long long u64;
 // of every workgroup notes the shader clock in LDS for kProfSteps consecutive steps and copies the
 // notes to global memory when the kernel ends, so that taking a stamp costs no memory traffic.
 #ifdef DBSN_PROFILE
-constexpr int kProfSteps = 8, kProfSlots = 64;
+constexpr int kProfSteps = 4, kProfSlots = 128, kProfSubs = 8;
 __device__ unsigned long long* g_prof;     // [kProfSteps][kProfSlots][workgroups]
 __device__ long long g_prof_first;         // first step to record
 #define DBSN_PROF_DECL unsigned long long* prof_lds_ = reinterpret_cast<unsigned long long*>(lds + PLds::total); \
@@ -73,15 +74,23 @@ constexpr int kProfLdsFloats = 2 * kProfSteps * kProfSlots;
 #define DBSN_PROF_FLUSH() do { } while (0)
 constexpr int kProfLdsFloats = 0;
 #endif
-#define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 4 + (sub))
+// (tuning only) a spin limit of all ones makes every wait accept whatever it reads: the results are
+// then meaningless, the time per step is that of the local work plus one round trip per hand-over
+#ifdef DBSN_PROFILE
+#define DBSN_WAITING(limit) ((limit) != 0xFFFFFFFFu)
+#else
+#define DBSN_WAITING(limit) true
+#endif
+#define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 8 + (sub))
 
 constexpr int kPGroups = 256;        // workgroups of the persistent kernel (tile geometry is fixed for it)
-constexpr int kNG = 9;               // register groups of 4 rows per wavefront
-constexpr int kSlots = 4 * kNG;      // rows a wavefront holds: 36 (a tile has at most 8 * 36 = 288 rows)
-constexpr int kMaxTileRows = kSlots * kWaves;   // 288
-constexpr int kStageFloats = 8192;   // LDS staging for polled partials
+constexpr int kGR = 2;               // rows per register group
+constexpr int kNG = 14;              // register groups per wavefront
+constexpr int kSlots = kGR * kNG;    // rows a wavefront holds: 28 (a tile has at most 8 * 28 = 224 rows)
+constexpr int kMaxTileRows = kSlots * kWaves;   // 224
 constexpr int kTopWMax = 10240;      // floats of W_L kept in LDS
 constexpr int kTopXMax = 2048;       // neurons of layer L-1 the output phase can take
+constexpr int kStageFloats = 7168 - kProfLdsFloats;   // LDS staging for the partials a backward tile gathers
 
 struct PLayer {
     float* W; float* b; float* x; float* d;
@@ -106,24 +115,31 @@ struct PNet {
 struct PLds {
     static constexpr int WL = 0;                                  // [kTopWMax]  private copy of W_L
     static constexpr int bL = WL + kTopWMax;                      // [kMaxClasses]
-    static constexpr int xkeep = bL + kMaxClasses;                // [kMaxLayers + 1][256] inputs of each tile
-    static constexpr int bias = xkeep + (kMaxLayers + 1) * 256;   // [kMaxLayers + 1][kMaxTileRows] (column block 0)
-    static constexpr int stage = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kStageFloats]
-    static constexpr int ysum = stage + kStageFloats;             // [4][kMaxTileRows]
-    static constexpr int gred = ysum + 4 * kMaxTileRows;          // [kWaves][256]; [32][16] partial logits
-    static constexpr int xtop = gred + kWaves * 256;              // [kTopXMax]
+    static constexpr int xkeep = bL + kMaxClasses;                // [2][kMaxLayers + 1][256] inputs of each tile, by step parity
+    static constexpr int bias = xkeep + 2 * (kMaxLayers + 1) * 256;       // [kMaxLayers + 1][kMaxTileRows] (column block 0)
+    static constexpr int dkeep = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kMaxLayers + 1][kMaxTileRows] deltas of each tile's rows
+    static constexpr int stage = dkeep + (kMaxLayers + 1) * kMaxTileRows; // [kStageFloats]
+    static constexpr int ysum = stage + kStageFloats;             // [4][kMaxTileRows]; delta_L and probabilities
+    static constexpr int gred = ysum + 4 * kMaxTileRows;          // [kWaves][256]; [class][33] partial logits
+    static constexpr int xtop = gred + kWaves * 264;              // [kTopXMax]
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
     static constexpr int fail = dtop + kTopXMax;                  // [1] set when a wait gave up
     static constexpr int total = fail + 16;
 };
 static_assert(PLds::total * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
+static_assert(kMaxClasses * 33 <= kWaves * 264, "partial logits do not fit");
 
 __device__ inline u64 pack_tagged(float v, unsigned tag) { return ((u64)tag << 32) | (u64)__float_as_uint(v); }
+__device__ inline u64 ld_tagged(const u64* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_tagged(u64* p, float v, unsigned tag) {
+    __hip_atomic_store(p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Workgroup barrier that orders LDS traffic only.  The workgroup's wavefronts talk to each other
-// through LDS alone, so a barrier need not wait for outstanding global stores (the tagged words
-// published for other workgroups take about a microsecond to be acknowledged); __syncthreads()
-// would.
+// through LDS alone, so a barrier need not wait for outstanding global stores (__syncthreads()
+// would, and the tagged words published for other workgroups take long to be acknowledged).
 __device__ inline void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
@@ -177,38 +193,45 @@ __device__ inline float quad_sum4(float a0, float a1, float a2, float a3) {
     return v;   // sum over this row of 16 lanes; the caller adds the four rows (xor 16, xor 32)
 }
 
-__device__ inline u64 ld_tagged(const u64* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Gathering the partial sums a thread needs: P tagged words of step `tag`, word k at
+// base + off(k), with `base` the same for the whole wavefront and off(k) a 32-bit element offset
+// per lane (so that the loads can take a scalar base and one vector offset register).
+// poll_issue sends the first batch of up to 16 loads; the caller may then do unrelated work while
+// they are in flight; poll_finish waits until every word carries the tag (re-reading as long as
+// necessary, batch after batch when P > 16) and returns the sum of the payloads of the first
+// `np` <= P words in index order.  P must be the same for all lanes of a wavefront (the re-read
+// loop is wavefront-uniform), np may differ: a lane that needs fewer words than its neighbours
+// lets off() repeat a word it does need.
+template <class OffF>
+__device__ __forceinline__ void poll_issue(u64 (&v)[16], int P, const u64* base, OffF off) {
+    const int nb = min(16, P);
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+        if (k < nb) v[k] = ld_tagged(base + off(k));
 }
-
-// One column per thread: wait for the P tagged words src[p * stride] (p < P) of step `tag` and
-// return the sum of their payloads in index order.  Up to 16 loads in flight (one round trip for
-// P <= 16); a wavefront re-reads a batch until all its lanes have it (wavefront-uniform loop, so
-// every lane must pass a readable src; lanes without a column of their own pass any valid one
-// and ignore the result).
-__device__ inline float poll_sum(const u64* src, int P, size_t stride, unsigned tag, unsigned limit, bool& ok) {
+template <class OffF>
+__device__ __forceinline__ float poll_finish(u64 (&v)[16], int P, int np, const u64* base, OffF off, unsigned tag,
+                                             unsigned limit, bool& ok) {
     float s = 0.0f;
     for (int p0 = 0; p0 < P; p0 += 16) {
         const int nb = min(16, P - p0);
-        u64 v[16];
         unsigned spins = 0;
         for (;;) {
-            const u64* a = src + (size_t)p0 * stride;
+            if (p0 > 0 || spins > 0) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                if (k < nb) v[k] = ld_tagged(a);
-                a += stride;
+                for (int k = 0; k < 16; ++k)
+                    if (k < nb) v[k] = ld_tagged(base + off(p0 + k));
             }
             bool pending = false;
 #pragma unroll
             for (int k = 0; k < 16; ++k)
                 if (k < nb) pending |= ((unsigned)(v[k] >> 32) != tag);
-            if (!__any(pending)) break;
+            if (!__any(pending && DBSN_WAITING(limit))) break;
             if (++spins > limit) { ok = false; break; }
         }
 #pragma unroll
         for (int k = 0; k < 16; ++k)
-            if (k < nb) s += __uint_as_float((unsigned)v[k]);
+            if (k < nb) s += (p0 + k < np) ? __uint_as_float((unsigned)v[k]) : 0.0f;
         if (!ok) break;
     }
     return s;
@@ -221,46 +244,51 @@ __device__ inline int stage_quarter(int P) { return (P + 3) >> 2; }
 __device__ inline int stage_pitch(int P) { return (4 * stage_quarter(P)) | 1; }
 
 // Wait for the tagged words src[p * stride + j] (p < P, j < len <= 256) of step `tag` and put their
-// payloads at stage[j * PP + p].  Called by the lower four wavefronts only (kPollThreads threads,
-// see the note on loads and stores in p_fwd_tile): they form rows of 2^lg >= len lanes over
-// consecutive j, so that a wavefront reads runs of consecutive words; 16 loads in flight per thread.
-constexpr int kPollThreads = 256;
-__device__ inline bool poll_rows_to_lds(const u64* src, int P, int len, size_t stride, unsigned tag, float* stage,
-                                        unsigned limit) {
+// payloads at stage[j * PP + p].  NT threads (the first NT of the workgroup) form rows of
+// 2^lg >= len lanes over consecutive j, so that a wavefront reads runs of consecutive words;
+// NB loads in flight per thread.  A word that has arrived is not read again.
+template <int NT, int NB>
+__device__ __forceinline__ bool poll_rows_to_lds(const u64* src, int P, int len, unsigned stride, unsigned tag,
+                                                 float* stage, unsigned limit) {
     int lg = 5;
     while ((1 << lg) < len) ++lg;
     const int j = (int)threadIdx.x & ((1 << lg) - 1);
     const int prow = (int)threadIdx.x >> lg;
-    const int pstep = kPollThreads >> lg;
+    const int pstep = NT >> lg;
     const int PP = stage_pitch(P), Ppad = 4 * stage_quarter(P);
     const bool jon = j < len;
     const u64* col = src + (jon ? j : 0);
     float* row = stage + j * PP;
     bool ok = true;
-    for (int p0 = prow; p0 - prow < Ppad; p0 += 16 * pstep) {   // (uniform trip count over the wavefront)
-        u64 v[16];
-        bool valid[16];
-        const u64* a[16];
+    for (int p0 = prow; p0 - prow < Ppad; p0 += NB * pstep) {   // (uniform trip count over the wavefront)
+        u64 v[NB];
+        bool pend[NB];
+        unsigned o[NB];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < NB; ++k) {
             const int p = p0 + k * pstep;
-            valid[k] = jon && p < P;
-            a[k] = col + (size_t)(valid[k] ? p : 0) * stride;
+            pend[k] = jon && p < P;
+            o[k] = (unsigned)(pend[k] ? p : 0) * stride;
+            v[k] = 0;
         }
         unsigned spins = 0;
         for (;;) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) v[k] = ld_tagged(a[k]);
+            for (int k = 0; k < NB; ++k)
+                if (pend[k]) v[k] = ld_tagged(col + o[k]);
             bool pending = false;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) pending |= valid[k] && ((unsigned)(v[k] >> 32) != tag);
-            if (!__any(pending)) break;
+            for (int k = 0; k < NB; ++k) {
+                pend[k] = pend[k] && ((unsigned)(v[k] >> 32) != tag);
+                pending |= pend[k];
+            }
+            if (!__any(pending && DBSN_WAITING(limit))) break;
             if (++spins > limit) { ok = false; break; }
         }
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < NB; ++k) {
             const int p = p0 + k * pstep;
-            if (jon && p < Ppad) row[p] = valid[k] ? __uint_as_float((unsigned)v[k]) : 0.0f;
+            if (jon && p < Ppad) row[p] = (p < P) ? __uint_as_float((unsigned)v[k]) : 0.0f;
         }
         if (!ok) break;
     }
@@ -302,6 +330,17 @@ __device__ inline float act_fast(float a) {
     return kA * copysignf(r, t);
 }
 
+// Same idea for two values: on return lane t holds the sum of a[t & 1] over the 8 lanes of its
+// row of 16 that share its parity.
+__device__ inline float pair_sum2(float a0, float a1) {
+    const bool b0 = (threadIdx.x & 1) != 0;
+    float v = (b0 ? a1 : a0) + dpp_mov<kDppXor1>(b0 ? a0 : a1);
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppRor4>(v);
+    v += dpp_mov<kDppRor8>(v);
+    return v;
+}
+
 __device__ inline float dot4(const float4& w, const float4& x) {
     float acc = w.x * x.x;
     acc = fmaf(w.y, x.y, acc);
@@ -329,11 +368,11 @@ __device__ inline bool tile_ctx(const PLayer& Ly, int g, TileCtx& t) {
     return true;
 }
 
-// Register slot s of group G = g0 + s / 4 holds tile row wave + 8 * s.
+// Register slot s of group G = g0 + s / kGR holds tile row wave + 8 * s.
 #define DBSN_FOR_LAYER_SLOTS(Ly, BODY)                                  \
     _Pragma("unroll") for (int G_ = 0; G_ < kNG; ++G_) {                 \
         if (G_ >= g0_ && G_ < g0_ + ng_) {                               \
-            const int sbase_ = 4 * (G_ - g0_);                           \
+            const int sbase_ = kGR * (G_ - g0_);                         \
             BODY                                                         \
         }                                                                \
     }
@@ -343,9 +382,9 @@ __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const PLayer& Ly
     const int wave = threadIdx.x >> 6;
     DBSN_LAYER_GROUPS(Ly);
     DBSN_FOR_LAYER_SLOTS(Ly, {
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+        _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
             const int rl = wave + kWaves * (sbase_ + q);
-            wr[4 * G_ + q] = (rl < t.Reff && t.lane_on)
+            wr[kGR * G_ + q] = (rl < t.Reff && t.lane_on)
                                  ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * Ly.ld)
                                  : make_float4(0.f, 0.f, 0.f, 0.f);
         }
@@ -356,17 +395,42 @@ __device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const PLa
     const int wave = threadIdx.x >> 6;
     DBSN_LAYER_GROUPS(Ly);
     DBSN_FOR_LAYER_SLOTS(Ly, {
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+        _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
             const int rl = wave + kWaves * (sbase_ + q);
-            if (rl < t.Reff && t.lane_on) *reinterpret_cast<float4*>(t.wbase + (size_t)rl * Ly.ld) = wr[4 * G_ + q];
+            if (rl < t.Reff && t.lane_on) *reinterpret_cast<float4*>(t.wbase + (size_t)rl * Ly.ld) = wr[kGR * G_ + q];
         }
     })
 }
 
+// Rank-1 update of the tile held in registers, w[j][i] -= eta * delta_j * x_i (appendix "Weight
+// updating").  Lane s < kSlots of the wavefront holds in `dlane` the delta of the wavefront's s-th row;
+// rows beyond the tile hold zeros and get a zero delta, so they stay zero.
+__device__ __forceinline__ void update_tile(float4 (&wr)[kSlots], const PLayer& Ly, const float4& x4, float dlane,
+                                            float eta) {
+    DBSN_LAYER_GROUPS(Ly);
+    DBSN_FOR_LAYER_SLOTS(Ly, {
+        _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
+            const float ed = eta * __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
+            float4 v = wr[kGR * G_ + q];
+            v.x = fmaf(-ed, x4.x, v.x);
+            v.y = fmaf(-ed, x4.y, v.y);
+            v.z = fmaf(-ed, x4.z, v.z);
+            v.w = fmaf(-ed, x4.w, v.w);
+            wr[kGR * G_ + q] = v;
+        }
+    })
+}
+
+// deltas of the rows of this workgroup's tile of layer l, as left by the backward phase
+__device__ inline const float* tile_deltas(const PNet& net, int l, const TileCtx& t, const float* lds) {
+    return (l == net.L - 1) ? lds + PLds::dtop + t.r0 : lds + PLds::dkeep + l * kMaxTileRows;
+}
+
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
 // partial sums of the rows over the tile's columns, the bias riding on column block 0.
+template <bool ST>
 __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float x0pre,
-                                           unsigned tag, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
+                                           unsigned tag, bool last, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
     const PLayer& Ly = net.lay[l];
     TileCtx t;
     if (!tile_ctx(Ly, g, t)) return true;
@@ -374,9 +438,9 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     const unsigned par = tag & 1u;
     DBSN_LAYER_GROUPS(Ly);
     DBSN_PROF_SUB(ps, ph, 0);
-    if (!net.stationary) load_tile(wr, Ly, t);  // in flight while the inputs are awaited
+    if (!ST) load_tile(wr, Ly, t);  // in flight while the inputs are awaited
 
-    float* xk = lds + PLds::xkeep + l * 256;
+    float* xk = lds + PLds::xkeep + (par * (kMaxLayers + 1) + l) * 256;
     if (l == 1) {
         // the caller fetched this thread's input pixel ahead of time
         if (threadIdx.x < 256) xk[threadIdx.x] = (threadIdx.x < t.Ceff) ? x0pre : 0.0f;
@@ -385,54 +449,61 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
         // thread j < Ceff gathers the nCB partial sums of its input column j, adds them in index
         // order and applies the activation: x_{l-1}[c0 + j]
         const PLayer& Lp = net.lay[l - 1];
+        const bool poller = threadIdx.x < 256;
+        const bool on = (int)threadIdx.x < t.Ceff;
+        const u64* base = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0;
+        const unsigned stride = (unsigned)Lp.n_out, col = on ? threadIdx.x : 0u;
+        auto off = [=](int k) { return (unsigned)k * stride + col; };
+        u64 v[16];
         bool ok = true;
-        if (threadIdx.x < 256) {
-            const bool on = (int)threadIdx.x < t.Ceff;
-            const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0 + (on ? threadIdx.x : 0);
-            const float a = poll_sum(src, Lp.nCB, (size_t)Lp.n_out, tag, net.spin_limit, ok);
+        if (poller) {
+            poll_issue(v, Lp.nCB, base, off);
+            DBSN_PROF_SUB(ps, ph, 1);
+            const float a = poll_finish(v, Lp.nCB, Lp.nCB, base, off, tag, net.spin_limit, ok);
             xk[threadIdx.x] = on ? act_fast(a) : 0.0f;
+            DBSN_PROF_SUB(ps, ph, 2);
         }
         if (!all_ok(ok, net.err, lds)) return false;
     }
-    DBSN_PROF_SUB(ps, ph, 1);
+    DBSN_PROF_SUB(ps, ph, 3);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     float* ysum = lds + PLds::ysum;
-    // per group: 4 row sums transposed onto the quads, reduced inside each row of 16 lanes on the
-    // vector ALU; the four rows of 16 park their sums in LDS and the publishing thread adds them
+    // per group: 2 row sums transposed onto pairs of lanes, reduced inside each row of 16 lanes on
+    // the vector ALU; the four rows of 16 park their sums in LDS and the publishing thread adds them
     const int lrow = lane >> 4;
     DBSN_FOR_LAYER_SLOTS(Ly, {
-        const float v = quad_sum4(dot4(wr[4 * G_ + 0], x4), dot4(wr[4 * G_ + 1], x4), dot4(wr[4 * G_ + 2], x4),
-                                  dot4(wr[4 * G_ + 3], x4));
-        const int rl = wave + kWaves * (sbase_ + (lane & 3));
-        if ((lane & 12) == 0) ysum[lrow * kMaxTileRows + rl] = v;
+        const float v2 = pair_sum2(dot4(wr[kGR * G_ + 0], x4), dot4(wr[kGR * G_ + 1], x4));
+        const int rl = wave + kWaves * (sbase_ + (lane & 1));
+        if ((lane & 14) == 0) ysum[lrow * kMaxTileRows + rl] = v2;
     })
+    DBSN_PROF_SUB(ps, ph, 4);
     lds_barrier();
-    DBSN_PROF_SUB(ps, ph, 2);
-    // Only the upper four wavefronts store to global memory, only the lower four load from it: a
-    // wavefront's loads complete behind its earlier stores, and the acknowledgement of a published
-    // word takes about as long as the whole phase.
-    if (threadIdx.x >= 256) {
+    DBSN_PROF_SUB(ps, ph, 5);
+    if (threadIdx.x >= 256) {   // the upper four wavefronts publish
         u64* dst = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + (size_t)t.cb * Ly.n_out + t.r0;
         for (int j = threadIdx.x - 256; j < t.Reff; j += 256) {
             constexpr int kYS = kMaxTileRows;
-            float v = (ysum[j] + ysum[kYS + j]) + (ysum[2 * kYS + j] + ysum[3 * kYS + j]);
-            if (t.cb == 0) v += lds[PLds::bias + l * kMaxTileRows + j];
-            __hip_atomic_store(dst + j, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            float y = (ysum[j] + ysum[kYS + j]) + (ysum[2 * kYS + j] + ysum[3 * kYS + j]);
+            if (t.cb == 0) y += lds[PLds::bias + l * kMaxTileRows + j];
+            st_tagged(dst + j, y, tag);
         }
-        // state read-out (dbsn_mlp_get_activations): row block 0 writes the inputs it gathered
-        if (l > 1 && t.rb == 0 && (int)threadIdx.x - 256 < t.Ceff)
+        // state read-out after the last step (dbsn_mlp_get_activations): row block 0 writes the
+        // inputs it gathered
+        if (last && l > 1 && t.rb == 0 && (int)threadIdx.x - 256 < t.Ceff)
             net.lay[l - 1].x[t.c0 + threadIdx.x - 256] = xk[threadIdx.x - 256];
     }
-    DBSN_PROF_SUB(ps, ph, 3);
+    DBSN_PROF_SUB(ps, ph, 7);
     return true;
 }
 
 // Fused backward sweep of this workgroup's tile of layer l (appendix "Backward propagation" and
-// "Weight updating" in one pass over the tile): deltas of the tile's rows, partial W^T delta of
-// its columns from the OLD weights (published first, it is what other workgroups wait for), then
+// "Weight updating" over the same registers): deltas of the tile's rows, partial W^T delta of its
+// columns from the OLD weights, published at once (it is what other workgroups wait for), then
 // the rank-1 update of the tile.
+template <bool ST>
 __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float eta,
-                                           unsigned tag, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
+                                           unsigned tag, bool last, float* lds, long long ps,
+                                           int ph DBSN_PROF_ARGS) {
     const PLayer& Ly = net.lay[l];
     TileCtx t;
     if (!tile_ctx(Ly, g, t)) return true;
@@ -440,94 +511,80 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     const unsigned par = tag & 1u;
     DBSN_LAYER_GROUPS(Ly);
     DBSN_PROF_SUB(ps, ph, 0);
-    if (!net.stationary) load_tile(wr, Ly, t);
+    if (!ST) load_tile(wr, Ly, t);
 
-    // deltas of the tile's rows: four threads per row add the partials of the layer above (the
-    // producers have multiplied them by f'(x_l) already, see below); then lane s < 36 of a
-    // wavefront picks up the delta of the wavefront's s-th row (tile row wave + 8 s), and the
-    // register slots read it from there by lane index
-    float* dl = lds + PLds::ysum;   // free during the backward sweep
-    if (l == net.L - 1) {
-        // the output layer was evaluated in this workgroup: its deltas are already in LDS
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) dl[j] = lds[PLds::dtop + t.r0 + j];
-        lds_barrier();
-    } else {
+    // Deltas of the tile's rows.  For the last hidden layer they are in LDS already (the output
+    // layer was evaluated in this workgroup).  Otherwise the workgroup gathers the gP partials of
+    // each of its rows from the layer above into LDS (the producers have multiplied them by
+    // f'(x_l) already, see below) and four threads per row add a quarter each in index order.
+    const float* dl = tile_deltas(net, l, t, lds);
+    if (l < net.L - 1) {
+        float* dw = lds + PLds::dkeep + l * kMaxTileRows;
         float* sg = lds + PLds::stage;
         const u64* gsrc = Ly.gp + (size_t)par * Ly.gP * Ly.n_out + t.r0;
-        bool ok = true;
-        if (threadIdx.x < kPollThreads)
-            ok = poll_rows_to_lds(gsrc, Ly.gP, t.Reff, (size_t)Ly.n_out, tag, sg, net.spin_limit);
+        const bool ok = poll_rows_to_lds<kThreads, 8>(gsrc, Ly.gP, t.Reff, (unsigned)Ly.n_out, tag, sg,
+                                                      net.spin_limit);
+        DBSN_PROF_SUB(ps, ph, 1);
         if (!all_ok(ok, net.err, lds)) return false;
+        DBSN_PROF_SUB(ps, ph, 2);
         for (int t4 = threadIdx.x; (t4 >> 2) - (lane >> 2) < t.Reff; t4 += kThreads) {
             // (trip count uniform over the wavefront: sum_row4 exchanges data inside quads)
             const int j = t4 >> 2;
             const float d = sum_row4(sg, Ly.gP, min(j, t.Reff - 1), t4 & 3);
-            if ((t4 & 3) == 0 && j < t.Reff) dl[j] = d;
+            if ((t4 & 3) == 0 && j < t.Reff) dw[j] = d;
         }
         lds_barrier();
     }
     const int myrow = wave + kWaves * lane;
-    const bool rowon = lane < kSlots && myrow < t.Reff;
-    const float dlane = rowon ? dl[myrow] : 0.0f;
-    DBSN_PROF_SUB(ps, ph, 1);
-    const float* xk = lds + PLds::xkeep + l * 256;
+    const float dlane = (lane < kSlots && myrow < t.Reff) ? dl[myrow] : 0.0f;
+    DBSN_PROF_SUB(ps, ph, 3);
+    const float* xk = lds + PLds::xkeep + (par * (kMaxLayers + 1) + l) * 256;
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     if (l > 1) {
         float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
         DBSN_FOR_LAYER_SLOTS(Ly, {
-            _Pragma("unroll") for (int q = 0; q < 4; ++q) {
+            _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
                 const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
-                const float4 v = wr[4 * G_ + q];
-                gacc.x = fmaf(v.x, d, gacc.x);
-                gacc.y = fmaf(v.y, d, gacc.y);
-                gacc.z = fmaf(v.z, d, gacc.z);
-                gacc.w = fmaf(v.w, d, gacc.w);
+                const float4 w4 = wr[kGR * G_ + q];
+                gacc.x = fmaf(w4.x, d, gacc.x);
+                gacc.y = fmaf(w4.y, d, gacc.y);
+                gacc.z = fmaf(w4.z, d, gacc.z);
+                gacc.w = fmaf(w4.w, d, gacc.w);
             }
         })
         float* gred = lds + PLds::gred;
-        *reinterpret_cast<float4*>(gred + wave * 256 + 4 * lane) = gacc;
+        *reinterpret_cast<float4*>(gred + wave * 264 + 4 * lane) = gacc;
+        DBSN_PROF_SUB(ps, ph, 4);
         lds_barrier();
+        DBSN_PROF_SUB(ps, ph, 5);
         const PLayer& Lp = net.lay[l - 1];
         u64* dst = Lp.gp + (size_t)par * Lp.gP * Lp.n_out + (size_t)t.rb * Lp.n_out + t.c0;
         const int i = (int)threadIdx.x - 256;   // the upper four wavefronts publish
         if (i >= 0 && i < t.Ceff) {
-            float v[kWaves];
+            float v8[kWaves];
 #pragma unroll
-            for (int k = 0; k < kWaves; ++k) v[k] = gred[k * 256 + i];
-            float s = 0.0f;
+            for (int k = 0; k < kWaves; ++k) v8[k] = gred[k * 264 + i];
+            float s8 = 0.0f;
 #pragma unroll
-            for (int k = 0; k < kWaves; ++k) s += v[k];
+            for (int k = 0; k < kWaves; ++k) s8 += v8[k];
             // this tile's columns are neurons of layer l-1 whose outputs it holds: fold f' in here,
             // so that the consumer's sum over row blocks is delta_{l-1} itself
-            s *= dact_from_y(xk[i]);
-            __hip_atomic_store(dst + i, pack_tagged(s, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            st_tagged(dst + i, s8 * dact_from_y(xk[i]), tag);
         }
     }
-    DBSN_PROF_SUB(ps, ph, 2);
-    // rank-1 update w -= eta * delta_j * x_i (rows beyond the tile hold zeros and stay zero)
-    DBSN_FOR_LAYER_SLOTS(Ly, {
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {
-            const float ed = eta * __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
-            float4 v = wr[4 * G_ + q];
-            v.x = fmaf(-ed, x4.x, v.x);
-            v.y = fmaf(-ed, x4.y, v.y);
-            v.z = fmaf(-ed, x4.z, v.z);
-            v.w = fmaf(-ed, x4.w, v.w);
-            wr[4 * G_ + q] = v;
-        }
-    })
-    if (!net.stationary) store_tile(wr, Ly, t);
+    DBSN_PROF_SUB(ps, ph, 6);
+    update_tile(wr, Ly, x4, dlane, eta);
+    if (!ST) store_tile(wr, Ly, t);
     if (t.cb == 0) {
-        // bias update (the biases of this tile's rows live in LDS for the whole launch), and the
-        // layer's deltas for dbsn_mlp_get_deltas (stored by the upper wavefronts)
-        for (int j = (int)threadIdx.x - 256; j >= 0 && j < t.Reff; j += 256) {
+        // bias update (the biases of this tile's rows live in LDS for the whole launch), and after
+        // the last step the layer's deltas for dbsn_mlp_get_deltas
+        for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
             const float d = dl[j];
             lds[PLds::bias + l * kMaxTileRows + j] -= eta * d;
-            Ly.d[t.r0 + j] = d;
+            if (last) Ly.d[t.r0 + j] = d;
         }
     }
-    lds_barrier();
-    DBSN_PROF_SUB(ps, ph, 3);
+    DBSN_PROF_SUB(ps, ph, 7);
     return true;
 }
 
@@ -538,7 +595,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
 // then 32 partial sums per class through LDS); wavefront 0 does the softmax, and each thread
 // back-propagates through and updates its column.
 __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
-                                      float* lds, long long ps, int ph DBSN_PROF_ARGS) {
+                                      bool last, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
     const int L = net.L;
     const PLayer& Ly = net.lay[L];
     const PLayer& Lp = net.lay[L - 1];
@@ -554,24 +611,28 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
 
     DBSN_PROF_SUB(ps, ph, 0);
     bool ok = true;
-    if (threadIdx.x < kPollThreads) {
-        // the lower four wavefronts gather x_{L-1} (they are the ones that load from global memory)
-        const u64* src = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
-        for (int i0 = 0; i0 < n; i0 += kPollThreads) {
+    {
+        // thread i gathers x_{L-1}[i] (and i + 512, ...): the nCB partial sums in index order
+        const u64* base = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
+        const unsigned stride = (unsigned)Lp.n_out;
+        for (int i0 = 0; i0 < n; i0 += kThreads) {
             const int i = i0 + (int)threadIdx.x;
             const bool on = i < n;
-            const float a = poll_sum(src + (on ? i : 0), Lp.nCB, (size_t)Lp.n_out, tag, net.spin_limit, ok);
+            const unsigned col = on ? (unsigned)i : 0u;
+            auto off = [=](int k) { return (unsigned)k * stride + col; };
+            u64 v[16];
+            poll_issue(v, Lp.nCB, base, off);
+            const float a = poll_finish(v, Lp.nCB, Lp.nCB, base, off, tag, net.spin_limit, ok);
             if (on) xtop[i] = act_fast(a);
         }
     }
-    if (!all_ok(ok, net.err, lds)) return false;
-    DBSN_PROF_SUB(ps, ph, 1);
+    DBSN_PROF_SUB(ps, ph, 2);
     // products per class, four classes at a time; a thread folds its columns i, i + 512, ... together
     for (int j0 = 0; j0 < nc; j0 += 4) {
         float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
         const int j1 = min(j0 + 1, nc - 1), j2 = min(j0 + 2, nc - 1), j3 = min(j0 + 3, nc - 1);
         for (int i = threadIdx.x; i < n; i += kThreads) {
-            const float xi = xtop[i];
+            const float xi = xtop[i];   // this thread's own write
             a0 = fmaf(WL[j0 * n + i], xi, a0);
             a1 = fmaf(WL[j1 * n + i], xi, a1);
             a2 = fmaf(WL[j2 * n + i], xi, a2);
@@ -581,8 +642,9 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         const int cls = j0 + (lane & 3);
         if ((lane & 12) == 0 && cls < nc) part[cls * 33 + wave * 4 + (lane >> 4)] = v;
     }
-    lds_barrier();
-    DBSN_PROF_SUB(ps, ph, 2);
+    DBSN_PROF_SUB(ps, ph, 3);
+    if (!all_ok(ok, net.err, lds)) return false;
+    DBSN_PROF_SUB(ps, ph, 4);
     if (wave == 0) {
         // class c = lane: logit, softmax (the sum of the exponentials is taken in index order)
         float a = -3.0e38f;
@@ -615,13 +677,17 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
             dL[kMaxClasses + lane] = p;
         }
     }
+    DBSN_PROF_SUB(ps, ph, 5);
     lds_barrier();
+    DBSN_PROF_SUB(ps, ph, 6);
     if (g == 0 && wave == kWaves - 1) {
-        // results of the step for the host: probabilities, output deltas, loss, x_{L-1} (the last
-        // wavefront stores them: it never waits for a load from global memory)
-        if (lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
+        // results for the host: the loss of every step; after the last step also the probabilities,
+        // the output deltas and x_{L-1}
         if (lane == 0 && loss_out) *loss_out = -logf(dL[kMaxClasses + label]);
-        for (int i = lane; i < n; i += 64) Lp.x[i] = xtop[i];
+        if (last) {
+            if (lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
+            for (int i = lane; i < n; i += 64) Lp.x[i] = xtop[i];
+        }
     }
     // deltas of layer L-1 and update of the private W_L
     for (int i = threadIdx.x; i < n; i += kThreads) {
@@ -641,10 +707,11 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     }
     if (threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
     lds_barrier();
-    DBSN_PROF_SUB(ps, ph, 3);
+    DBSN_PROF_SUB(ps, ph, 7);
     return true;
 }
 
+template <bool ST>
 __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float* samples, const int* labels,
                                                            int label_val, long long n, float eta, float* loss_out,
                                                            unsigned tag_base) {
@@ -659,7 +726,7 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
         lds[PLds::WL + e] = LyL.W[(size_t)j * LyL.ld + i];
     }
     if (threadIdx.x < LyL.n_out) lds[PLds::bL + threadIdx.x] = LyL.b[threadIdx.x];
-    for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
+    for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
 
     for (int l = 1; l < L; ++l) {
@@ -671,7 +738,7 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     float4 wr[kSlots];
 #pragma unroll
     for (int s = 0; s < kSlots; ++s) wr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (net.stationary) {
+    if (ST) {
         for (int l = 1; l < L; ++l) {
             TileCtx t;
             if (tile_ctx(net.lay[l], g, t)) load_tile(wr, net.lay[l], t);
@@ -695,11 +762,15 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
             if (has1) x0pre = samples[(s + 1) * n0 + t1.c0 + threadIdx.x];
             if (labels) labpre = labels[s + 1];
         }
-        for (int l = 1; l < L && alive; ++l) alive = p_fwd_tile(wr, net, l, g, x0cur, tag, lds, s, l - 1 DBSN_PROF_PASS);
-        if (alive) alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, lds, s, L - 1 DBSN_PROF_PASS);
-        for (int l = L - 1; l >= 1 && alive; --l) alive = p_bwd_tile(wr, net, l, g, eta, tag, lds, s, L + (L - 1 - l) DBSN_PROF_PASS);
+        const bool last = (s + 1 == n);
+        for (int l = 1; l < L && alive; ++l)
+            alive = p_fwd_tile<ST>(wr, net, l, g, x0cur, tag, last, lds, s, l - 1 DBSN_PROF_PASS);
+        if (alive)
+            alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, last, lds, s, L - 1 DBSN_PROF_PASS);
+        for (int l = L - 1; l >= 1 && alive; --l)
+            alive = p_bwd_tile<ST>(wr, net, l, g, eta, tag, last, lds, s, L + (L - 1 - l) DBSN_PROF_PASS);
     }
-    if (net.stationary) {
+    if (ST) {
         for (int l = 1; l < L; ++l) {
             TileCtx t;
             if (tile_ctx(net.lay[l], g, t)) store_tile(wr, net.lay[l], t);
