@@ -7,7 +7,8 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libdbsn.so")
 SOURCES = [os.path.join(CSRC, "dbsn.hip")]
-HEADERS = [os.path.join(CSRC, h) for h in ("dbsn_rng.h", "dbsn_mlp_kernels.h", "dbsn_deform_kernels.h")] + \
+HEADERS = [os.path.join(CSRC, h) for h in ("dbsn_rng.h", "dbsn_mlp_kernels.h", "dbsn_deform_kernels.h",
+                                           "dbsn_persistent_kernel.h")] + \
           [os.path.join(ROOT, "include", "dbsn.h")]
 
 
@@ -16,6 +17,9 @@ def hipcc_command(out=LIB):
     return [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
             # keep the compiler from forming packed fp32 instructions
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            # keep identical stores in different switch cases apart: merged, they index the weight
+            # registers of the persistent kernel dynamically, which sends them to scratch memory
+            "-mllvm", "-simplifycfg-sink-common=false",
             "-I", os.path.join(ROOT, "include"), "-I", CSRC, *SOURCES, "-o", out]
 
 

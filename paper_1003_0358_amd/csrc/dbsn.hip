@@ -98,9 +98,10 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
     for (int l = 1; l < L; ++l) {
         p.yp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nCB[l] * sizes[l]);
         if (l <= L - 2) {
-            p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l + 1] * sizes[l]);
-            // staging of one tile's partials: R rows of nRB_{l+1} words, padded to an odd pitch
-            if (p.R[l] * ((((p.nRB[l + 1] + 3) / 4) * 4) | 1) > kStageFloats) p.persistent_ok = false;
+            // one chunk of nRB_{l+1} x R_l words per row block, see PLayer::gp
+            p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l] * p.R[l] * p.nRB[l + 1]);
+            // staging of one tile's chunk in LDS
+            if (p.R[l] * p.nRB[l + 1] > kStageFloats) p.persistent_ok = false;
         }
     }
     // register groups of kGR rows per wavefront: stationary when every layer gets groups of its own
@@ -116,7 +117,9 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         at += p.ng[l];
     }
     if (L >= 2) {
-        if ((size_t)sizes[L] * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax) p.persistent_ok = false;
+        // W_L lives in LDS with its classes padded to a multiple of four
+        if ((size_t)((sizes[L] + 3) / 4 * 4) * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax)
+            p.persistent_ok = false;
     }
     p.total = off;
     return p;
@@ -137,6 +140,7 @@ struct dbsn_mlp {
     int cus = 0;
     size_t lds_limit = 0;
     bool persistent_ready = false;
+    int layout = 0;            // register layout of the persistent kernel (0: packed at run time)
     int* err = nullptr;
 };
 
@@ -208,8 +212,9 @@ int32_t steps_launches(dbsn_mlp* m, const float* samples, const int* labels, int
 int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n, float eta,
                          float* loss) {
     const size_t lds = sizeof(float) * (size_t)(PLds::total + kProfLdsFloats);
-    const void* fn = m->pnet.stationary ? reinterpret_cast<const void*>(&k_bp_dataflow<true>)
-                                        : reinterpret_cast<const void*>(&k_bp_dataflow<false>);
+    const void* fn = !m->pnet.stationary ? reinterpret_cast<const void*>(&k_bp_dataflow<false, 0>)
+                     : m->layout == 1    ? reinterpret_cast<const void*>(&k_bp_dataflow<true, 1>)
+                                         : reinterpret_cast<const void*>(&k_bp_dataflow<true, 0>);
     if (!m->persistent_ready) {
         if (lds > m->lds_limit) return fail(DBSN_E_SHAPE, "persistent kernel needs %zu B of LDS", lds);
         HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -302,10 +307,17 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     pn.L = net.L;
     pn.err = m->err;
     pn.spin_limit = 1u << 22;
-    pn.backoff = 0;
     pn.stationary = plan.stationary ? 1 : 0;
-    if (const char* e = getenv("DBSN_BACKOFF")) pn.backoff = atoi(e);
+    pn.fwd_delay = 16;
+    if (const char* e = getenv("DBSN_FWD_DELAY")) pn.fwd_delay = atoi(e) < 0 ? 0 : (atoi(e) > 64 ? 64 : atoi(e));
     if (const char* e = getenv("DBSN_STATIONARY")) pn.stationary = (atoi(e) != 0 && plan.stationary) ? 1 : 0;
+    // a compile-time register layout when the net is stationary and fits it
+    m->layout = 0;
+    if (pn.stationary && plan.persistent_ok && net.L - 1 <= kLayoutDepth && !getenv("DBSN_NO_LAYOUT")) {
+        m->layout = 1;
+        for (int l = 1; l < net.L; ++l)
+            if (plan.ng[l] > kLayoutNG[l - 1]) m->layout = 0;
+    }
     for (int l = 1; l <= net.L; ++l) {
         PLayer& P = pn.lay[l];
         const Layer& Ly = net.lay[l];
@@ -313,7 +325,7 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
         if (l < net.L && plan.persistent_ok) {
             P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
-            P.g0 = pn.stationary ? plan.g0[l] : 0;
+            P.g0 = m->layout == 1 ? kLayoutG0[l - 1] : (pn.stationary ? plan.g0[l] : 0);
             P.ng = plan.ng[l];
             P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
             if (l <= net.L - 2) {

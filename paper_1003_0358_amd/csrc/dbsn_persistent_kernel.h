@@ -7,14 +7,14 @@
 //
 //  * Every hidden layer l is cut into tiles of R_l rows x C_l <= 256 columns; tile (cb, rb)
 //    belongs to workgroup g = rb * nCB_l + cb for the whole life of the network, forward and
-//    backward, so a weight is only ever touched by one workgroup (plain cached loads and stores).
+//    backward, so a weight is only ever touched by one workgroup.
 //  * What crosses workgroups is small: forward, a tile publishes its R partial dot products
-//    yp_l[cb][rows]; backward, its C partial sums gp_{l-1}[rb][cols] of W^T delta.  Each value
-//    travels as ONE 64-bit word {step tag, float} written with a device-scope atomic store, and a
-//    consumer polls the words it needs until they carry the current step's tag: the data is its
-//    own flag.  No fence, no L2 write-back, no counter that 256 workgroups hammer.
-//  * A consumer adds the partials in index order (deterministic, bit-reproducible), applies the
-//    activation (forward) or its derivative (backward) itself, and goes on.
+//    yp_l[cb][rows]; backward, its C partial sums of W^T delta.  Each value travels as ONE 64-bit
+//    word {step tag, float} written with a device-scope atomic store, and a consumer polls the
+//    words it needs until they carry the current step's tag: the data is its own flag.  No fence,
+//    no L2 write-back, no counter that 256 workgroups hammer.
+//  * A consumer adds the partials in a fixed order (bit-reproducible), applies the activation
+//    (forward) itself, and goes on.
 //  * Buffers alternate with the parity of the step tag; the output layer needs all of x_{L-1},
 //    hence every tile of the step, which keeps any workgroup from running two steps ahead.
 //  * The 10 x n_{L-1} output layer lives in every workgroup's LDS; each workgroup evaluates it
@@ -29,9 +29,16 @@
 //    costs its chain of hand-overs, not its bytes.  Otherwise each phase loads its tile into the
 //    same registers (the loads are issued before the wait for the inputs, so they overlap it)
 //    and the backward phase stores it back.
+//  * With the weights on chip a step costs INSTRUCTIONS and load round trips, so everything a
+//    phase needs that does not change from step to step (tile bounds, word offsets, register
+//    group ranges) is worked out once per launch into a small per-layer table in LDS, the
+//    register groups of a layer are entered by one switch instead of a test per group, and
+//    reductions stay on the vector ALU (DPP inside rows of 16 lanes, lane-row swaps across them).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "dbsn_mlp_kernels.h"
 
@@ -88,14 +95,18 @@ constexpr int kGR = 2;               // rows per register group
 constexpr int kNG = 14;              // register groups per wavefront
 constexpr int kSlots = kGR * kNG;    // rows a wavefront holds: 28 (a tile has at most 8 * 28 = 224 rows)
 constexpr int kMaxTileRows = kSlots * kWaves;   // 224
-constexpr int kTopWMax = 10240;      // floats of W_L kept in LDS
+constexpr int kTopWMax = 10240;      // floats of W_L kept in LDS (rows padded to a multiple of four classes)
 constexpr int kTopXMax = 2048;       // neurons of layer L-1 the output phase can take
-constexpr int kStageFloats = 7168 - kProfLdsFloats;   // LDS staging for the partials a backward tile gathers
+constexpr int kStageFloats = 7168;   // LDS staging for the partials a backward tile gathers (14 x 512)
+static_assert(kGR == 2, "the forward reduction pairs the two rows of a register group");
+static_assert(kSlots <= 32, "one lane per row slot, two blocks of 16");
 
 struct PLayer {
     float* W; float* b; float* x; float* d;
-    u64* yp;          // [2][nCB][n_out]   forward partial sums of this layer's rows
-    u64* gp;          // [2][gP][n_out]    partial W^T delta for this layer's neurons (from layer l+1)
+    u64* yp;          // [2][nCB][n_out]            forward partial sums of this layer's rows
+    u64* gp;          // [2][nRB][gP][rows of rb]   partial delta of this layer's neurons, one chunk per row block:
+                      //                            chunk rb holds, for p < gP (row blocks of layer l+1), the Reff(rb)
+                      //                            rows of the block side by side; chunks are gP * R words apart
     int n_in, n_out, ld;
     int nCB, nRB, C, R;
     int gP;           // number of partial rows in gp = nRB of layer l+1
@@ -107,35 +118,63 @@ struct PNet {
     int* err;
     int L;
     unsigned spin_limit;
-    int backoff;      // pause between two polls of the same words, in units of 64 clocks
     int stationary;   // 1: every layer has its own register groups for the whole launch
+    int fwd_delay;    // pause before the first look at forward partials, in units of 64 clocks
+};
+
+// Per-layer table of this workgroup (32-bit words in LDS), filled once per launch.
+constexpr int kPlanInts = 32;
+enum : int {
+    PL_FLAGS = 0,   // bit 0: the workgroup has a tile of this layer; bit 1: column block 0; bit 2: row block 0
+    PL_CEFF, PL_REFF, PL_R0, PL_C0, PL_G0, PL_GEND,
+    PL_PF,          // forward: partials per input column = nCB of the layer below
+    PL_FSTRIDE,     // forward: words between two partials of one column = n of the layer below
+    PL_FPAR,        // forward source: words between the two parity buffers
+    PL_FDPAR,       // forward destination: words between the two parity buffers
+    PL_GP,          // backward: partials per row
+    PL_NW,          // backward: words of this tile's chunk = gP * Reff
+    PL_BPAR,        // backward source: words between the parity buffers
+    PL_BDPAR,       // backward destination (gp of the layer below): words between the parity buffers
+    PL_RPREV,       // rows per row block of the layer below
+    PL_M20,         // ceil(2^20 / RPREV): c / RPREV == (c * M20) >> 20 for c < 4096, RPREV <= 224
+    PL_NPREV,       // neurons of the layer below
+    PL_CHUNKPREV,   // words between two chunks of the layer below's gp
+    PL_RB,          // row block of this tile
+    PL_FSRC = 20,   // (2 words each) pointers: forward source of parity 0 at this tile's first column,
+    PL_FDST = 22,   //   forward destination at this tile's first row,
+    PL_BSRC = 24,   //   this tile's chunk of gp,
+    PL_BDST = 26    //   gp of the layer below
 };
 
 // LDS map (floats)
 struct PLds {
-    static constexpr int WL = 0;                                  // [kTopWMax]  private copy of W_L
+    static constexpr int WL = 0;                                  // [kTopWMax]  private copy of W_L, [padded classes][n]
     static constexpr int bL = WL + kTopWMax;                      // [kMaxClasses]
-    static constexpr int xkeep = bL + kMaxClasses;                // [2][kMaxLayers + 1][256] inputs of each tile, by step parity
-    static constexpr int bias = xkeep + 2 * (kMaxLayers + 1) * 256;       // [kMaxLayers + 1][kMaxTileRows] (column block 0)
-    static constexpr int dkeep = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kMaxLayers + 1][kMaxTileRows] deltas of each tile's rows
-    static constexpr int stage = dkeep + (kMaxLayers + 1) * kMaxTileRows; // [kStageFloats]
-    static constexpr int ysum = stage + kStageFloats;             // [4][kMaxTileRows]; delta_L and probabilities
-    static constexpr int gred = ysum + 4 * kMaxTileRows;          // [kWaves][256]; [class][33] partial logits
+    static constexpr int xkeep = bL + kMaxClasses;                // [kMaxLayers + 1][256] inputs of each tile
+    static constexpr int bias = xkeep + (kMaxLayers + 1) * 256;   // [kMaxLayers + 1][kMaxTileRows] (column block 0)
+    static constexpr int stage = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kStageFloats]
+    static constexpr int dLp = stage + kStageFloats;              // [2][kMaxClasses] delta_L (padded with zeros), probabilities
+    static constexpr int gred = dLp + 2 * kMaxClasses;            // [kWaves][264]; [class][33] partial logits
     static constexpr int xtop = gred + kWaves * 264;              // [kTopXMax]
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
-    static constexpr int fail = dtop + kTopXMax;                  // [1] set when a wait gave up
+    static constexpr int plan = dtop + kTopXMax;                  // [kMaxLayers + 1][kPlanInts]
+    static constexpr int fail = plan + (kMaxLayers + 1) * kPlanInts;   // [1] set when a wait gave up
     static constexpr int total = fail + 16;
 };
-static_assert(PLds::total * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
+static_assert((PLds::total + kProfLdsFloats) * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
 static_assert(kMaxClasses * 33 <= kWaves * 264, "partial logits do not fit");
 
 __device__ inline u64 pack_tagged(float v, unsigned tag) { return ((u64)tag << 32) | (u64)__float_as_uint(v); }
+// (the words are in device memory: saying so keeps the compiler from emitting generic-address loads
+// for pointers it has seen rebuilt from integers)
+typedef __attribute__((address_space(1))) u64 global_u64;
 __device__ inline u64 ld_tagged(const u64* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load((const global_u64*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ inline void st_tagged(u64* p, float v, unsigned tag) {
-    __hip_atomic_store(p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store((global_u64*)p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // Workgroup barrier that orders LDS traffic only.  The workgroup's wavefronts talk to each other
 // through LDS alone, so a barrier need not wait for outstanding global stores (__syncthreads()
@@ -167,21 +206,19 @@ constexpr int kDppXor2 = 0x4E;   // quad_perm [2,3,0,1]
 constexpr int kDppRor8 = 0x128;  // rotate within a row of 16 lanes by 8
 constexpr int kDppRor4 = 0x124;  // ... by 4
 
-// Sum of one value over the 64 lanes, result in every lane.
-__device__ inline float wave_sum_dpp(float v) {
-    v += dpp_mov<kDppXor1>(v);
-    v += dpp_mov<kDppXor2>(v);
-    v += dpp_mov<kDppRor4>(v);
-    v += dpp_mov<kDppRor8>(v);
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
+// v[t] + v[t ^ 16] + v[t ^ 32] + v[t ^ 48] in every lane: adds the four rows of 16 lanes as
+// (row0 + row1) + (row2 + row3) with the lane-row swap instructions of gfx950.
+__device__ inline float rows_sum(float v) {
+    const unsigned a = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+    const float s = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const unsigned b = __float_as_uint(s);
+    const auto q = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
 // Sums of four values over the 64 lanes at once: two halving steps inside every quad of lanes
-// leave value (t & 3) in lane t, the remaining steps add over the 16 quads.  On return lane t
-// holds the sum of a[t & 3] over its row of 16 lanes; the caller adds the four rows with two LDS
-// permutes (xor 16, xor 32), which it can overlap across several groups.  13 vector ops.
+// leave value (t & 3) in lane t, the remaining steps add over the quads of the row of 16 lanes.
 __device__ inline float quad_sum4(float a0, float a1, float a2, float a3) {
     const int lane = threadIdx.x & 63;
     const bool b0 = (lane & 1) != 0, b1 = (lane & 2) != 0;
@@ -190,130 +227,88 @@ __device__ inline float quad_sum4(float a0, float a1, float a2, float a3) {
     float v = (b1 ? s1 : s0) + dpp_mov<kDppXor2>(b1 ? s0 : s1);
     v += dpp_mov<kDppRor4>(v);
     v += dpp_mov<kDppRor8>(v);
-    return v;   // sum over this row of 16 lanes; the caller adds the four rows (xor 16, xor 32)
+    return v;   // sum over this row of 16 lanes; the caller adds the four rows
 }
 
-// Gathering the partial sums a thread needs: P tagged words of step `tag`, word k at
-// base + off(k), with `base` the same for the whole wavefront and off(k) a 32-bit element offset
-// per lane (so that the loads can take a scalar base and one vector offset register).
-// poll_issue sends the first batch of up to 16 loads; the caller may then do unrelated work while
-// they are in flight; poll_finish waits until every word carries the tag (re-reading as long as
-// necessary, batch after batch when P > 16) and returns the sum of the payloads of the first
-// `np` <= P words in index order.  P must be the same for all lanes of a wavefront (the re-read
-// loop is wavefront-uniform), np may differ: a lane that needs fewer words than its neighbours
-// lets off() repeat a word it does need.
-template <class OffF>
-__device__ __forceinline__ void poll_issue(u64 (&v)[16], int P, const u64* base, OffF off) {
-    const int nb = min(16, P);
-#pragma unroll
-    for (int k = 0; k < 16; ++k)
-        if (k < nb) v[k] = ld_tagged(base + off(k));
+// Same idea for two values: on return lane t holds the sum of a[t & 1] over the 8 lanes of its
+// row of 16 that share its parity.
+__device__ inline float pair_sum2(float a0, float a1) {
+    const bool b0 = (threadIdx.x & 1) != 0;
+    float v = (b0 ? a1 : a0) + dpp_mov<kDppXor1>(b0 ? a0 : a1);
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppRor4>(v);
+    v += dpp_mov<kDppRor8>(v);
+    return v;
 }
-template <class OffF>
-__device__ __forceinline__ float poll_finish(u64 (&v)[16], int P, int np, const u64* base, OffF off, unsigned tag,
-                                             unsigned limit, bool& ok) {
-    float s = 0.0f;
-    for (int p0 = 0; p0 < P; p0 += 16) {
-        const int nb = min(16, P - p0);
-        unsigned spins = 0;
-        for (;;) {
-            if (p0 > 0 || spins > 0) {
+
+// Gathering the partial sums of one input column: P <= N tagged words of step `tag`, word k at
+// row_k[col] with row_k = base + k * stride the same for the whole wavefront (scalar address
+// arithmetic) and col the lane's column.  All N loads are in flight together; the batch is read
+// again until every word carries the tag.  Slots beyond P repeat word P - 1 and are left out of the
+// sum, which adds the payloads in index order.
+template <int N>
+__device__ __forceinline__ float poll_sum_n(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
+                                            unsigned limit, bool& ok, float s) {
+    u64 v[N];
+    unsigned spins = 0;
+    for (;;) {
 #pragma unroll
-                for (int k = 0; k < 16; ++k)
-                    if (k < nb) v[k] = ld_tagged(base + off(p0 + k));
-            }
-            bool pending = false;
-#pragma unroll
-            for (int k = 0; k < 16; ++k)
-                if (k < nb) pending |= ((unsigned)(v[k] >> 32) != tag);
-            if (!__any(pending && DBSN_WAITING(limit))) break;
-            if (++spins > limit) { ok = false; break; }
+        for (int k = 0; k < N; ++k) {
+            const u64* row = base + (size_t)((unsigned)min(k, P - 1) * stride);
+            v[k] = ld_tagged(row + col);
         }
+        bool pending = false;
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
-            if (k < nb) s += (p0 + k < np) ? __uint_as_float((unsigned)v[k]) : 0.0f;
-        if (!ok) break;
+        for (int k = 0; k < N; ++k) pending |= ((unsigned)(v[k] >> 32) != tag);
+        if (!__any(pending && DBSN_WAITING(limit))) break;
+        if (++spins > limit) { ok = false; break; }
     }
+#pragma unroll
+    for (int k = 0; k < N; ++k) s += (k < P) ? __uint_as_float((unsigned)v[k]) : 0.0f;
     return s;
 }
+// (more than 12 partials, i.e. layers wider than 3072, take two batches one after the other)
+__device__ __forceinline__ float poll_sum(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
+                                          unsigned limit, bool& ok) {
+    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, 0.0f);
+    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, 0.0f);
+    if (P <= 12) return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, 0.0f);
+    const float s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, 0.0f);
+    return poll_sum_n<8>(base + (size_t)(8u * stride), col, P - 8, stride, tag, limit, ok, s);
+}
 
-// Row layout of the staging area used by the backward phase: row j holds its P partials
-// contiguously, P rounded up to a multiple of 4 and padded with zeros, rows PP floats apart with
-// PP odd (bank-conflict-free both for the scattered writes and for the reads).
-__device__ inline int stage_quarter(int P) { return (P + 3) >> 2; }
-__device__ inline int stage_pitch(int P) { return (4 * stage_quarter(P)) | 1; }
-
-// Wait for the tagged words src[p * stride + j] (p < P, j < len <= 256) of step `tag` and put their
-// payloads at stage[j * PP + p].  NT threads (the first NT of the workgroup) form rows of
-// 2^lg >= len lanes over consecutive j, so that a wavefront reads runs of consecutive words;
-// NB loads in flight per thread.  A word that has arrived is not read again.
-template <int NT, int NB>
-__device__ __forceinline__ bool poll_rows_to_lds(const u64* src, int P, int len, unsigned stride, unsigned tag,
-                                                 float* stage, unsigned limit) {
-    int lg = 5;
-    while ((1 << lg) < len) ++lg;
-    const int j = (int)threadIdx.x & ((1 << lg) - 1);
-    const int prow = (int)threadIdx.x >> lg;
-    const int pstep = NT >> lg;
-    const int PP = stage_pitch(P), Ppad = 4 * stage_quarter(P);
-    const bool jon = j < len;
-    const u64* col = src + (jon ? j : 0);
-    float* row = stage + j * PP;
+// Gathering a contiguous chunk of nW <= NK * 512 tagged words into the staging area: thread t
+// takes words t, t + 512, ... (a wavefront reads runs of 64 consecutive words); stage[w] receives
+// the payload of word w.  Slots beyond the chunk repeat its last word.
+template <int NK>
+__device__ __forceinline__ bool poll_chunk_n(const u64* base, unsigned w0, unsigned nW, unsigned tag, float* stage,
+                                             unsigned limit) {
+    u64 v[NK];
     bool ok = true;
-    for (int p0 = prow; p0 - prow < Ppad; p0 += NB * pstep) {   // (uniform trip count over the wavefront)
-        u64 v[NB];
-        bool pend[NB];
-        unsigned o[NB];
+    unsigned spins = 0;
+    for (;;) {
 #pragma unroll
-        for (int k = 0; k < NB; ++k) {
-            const int p = p0 + k * pstep;
-            pend[k] = jon && p < P;
-            o[k] = (unsigned)(pend[k] ? p : 0) * stride;
-            v[k] = 0;
-        }
-        unsigned spins = 0;
-        for (;;) {
+        for (int k = 0; k < NK; ++k) v[k] = ld_tagged(base + min(w0 + threadIdx.x + (unsigned)kThreads * k, nW - 1u));
+        bool pending = false;
 #pragma unroll
-            for (int k = 0; k < NB; ++k)
-                if (pend[k]) v[k] = ld_tagged(col + o[k]);
-            bool pending = false;
+        for (int k = 0; k < NK; ++k) pending |= ((unsigned)(v[k] >> 32) != tag);
+        if (!__any(pending && DBSN_WAITING(limit))) break;
+        if (++spins > limit) { ok = false; break; }
+    }
 #pragma unroll
-            for (int k = 0; k < NB; ++k) {
-                pend[k] = pend[k] && ((unsigned)(v[k] >> 32) != tag);
-                pending |= pend[k];
-            }
-            if (!__any(pending && DBSN_WAITING(limit))) break;
-            if (++spins > limit) { ok = false; break; }
-        }
-#pragma unroll
-        for (int k = 0; k < NB; ++k) {
-            const int p = p0 + k * pstep;
-            if (jon && p < Ppad) row[p] = (p < P) ? __uint_as_float((unsigned)v[k]) : 0.0f;
-        }
-        if (!ok) break;
+    for (int k = 0; k < NK; ++k) {
+        const unsigned w = w0 + threadIdx.x + (unsigned)kThreads * k;
+        if (w < nW) stage[w] = __uint_as_float((unsigned)v[k]);
     }
     return ok;
 }
-
-// Thread (j, q), q = 0..3, adds quarter q of row j of the staging area in index order; the four
-// quarter sums are then combined inside the quad of lanes as (q0 + q1) + (q2 + q3).  All four
-// lanes of a quad (lanes 4a .. 4a+3 hold the same j) return the row sum.
-__device__ inline float sum_row4(const float* stage, int P, int j, int q) {
-    const int P4 = stage_quarter(P);
-    const float* r = stage + j * stage_pitch(P) + q * P4;
-    float s = 0.0f;
-    for (int k0 = 0; k0 < P4; k0 += 8) {
-        float v[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (k0 + k < P4) v[k] = r[k0 + k];
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (k0 + k < P4) s += v[k];
-    }
-    s += dpp_mov<kDppXor1>(s);
-    s += dpp_mov<kDppXor2>(s);
-    return s;
+// (chunks of more than 4096 words take several batches one after the other)
+__device__ __forceinline__ bool poll_chunk(const u64* base, unsigned nW, unsigned tag, float* stage, unsigned limit) {
+    if (nW <= 2u * kThreads) return poll_chunk_n<2>(base, 0u, nW, tag, stage, limit);
+    if (nW <= 4u * kThreads) return poll_chunk_n<4>(base, 0u, nW, tag, stage, limit);
+    bool ok = true;
+    for (unsigned w0 = 0; w0 < nW && ok; w0 += 8u * kThreads) ok = poll_chunk_n<8>(base, w0, nW, tag, stage, limit);
+    return ok;
 }
 
 // y(a) = A tanh(B a) without the library routine: tanh(t) = 1 - 2 / (exp(2t) + 1) away from zero,
@@ -330,17 +325,6 @@ __device__ inline float act_fast(float a) {
     return kA * copysignf(r, t);
 }
 
-// Same idea for two values: on return lane t holds the sum of a[t & 1] over the 8 lanes of its
-// row of 16 that share its parity.
-__device__ inline float pair_sum2(float a0, float a1) {
-    const bool b0 = (threadIdx.x & 1) != 0;
-    float v = (b0 ? a1 : a0) + dpp_mov<kDppXor1>(b0 ? a0 : a1);
-    v += dpp_mov<kDppXor2>(v);
-    v += dpp_mov<kDppRor4>(v);
-    v += dpp_mov<kDppRor8>(v);
-    return v;
-}
-
 __device__ inline float dot4(const float4& w, const float4& x) {
     float acc = w.x * x.x;
     acc = fmaf(w.y, x.y, acc);
@@ -348,149 +332,239 @@ __device__ inline float dot4(const float4& w, const float4& x) {
     return fmaf(w.w, x.w, acc);
 }
 
-struct TileCtx {
-    int cb, rb, c0, r0, Ceff, Reff;
-    bool lane_on;
-    float* wbase;   // &W[r0][c0 + 4 * lane]
-};
-
-__device__ inline bool tile_ctx(const PLayer& Ly, int g, TileCtx& t) {
-    if (g >= Ly.nCB * Ly.nRB) return false;
-    const int lane = threadIdx.x & 63;
-    t.cb = g % Ly.nCB;
-    t.rb = g / Ly.nCB;
-    t.c0 = t.cb * Ly.C;
-    t.r0 = t.rb * Ly.R;
-    t.Ceff = min(Ly.C, Ly.n_in - t.c0);
-    t.Reff = min(Ly.R, Ly.n_out - t.r0);
-    t.lane_on = (4 * lane < Ly.C) && (t.c0 + 4 * lane < Ly.ld);
-    t.wbase = Ly.W + (size_t)t.r0 * Ly.ld + t.c0 + 4 * lane;
-    return true;
-}
-
-// Register slot s of group G = g0 + s / kGR holds tile row wave + 8 * s.
-#define DBSN_FOR_LAYER_SLOTS(Ly, BODY)                                  \
-    _Pragma("unroll") for (int G_ = 0; G_ < kNG; ++G_) {                 \
-        if (G_ >= g0_ && G_ < g0_ + ng_) {                               \
-            const int sbase_ = kGR * (G_ - g0_);                         \
-            BODY                                                         \
-        }                                                                \
+// Runs f(G) for the register groups G = g0 .. gend - 1 of one layer, G a compile-time constant
+// inside f (register indices must be): one switch to enter, one compare per group to leave.
+#define DBSN_GROUP_CASE(G)                                   \
+    case G:                                                  \
+        f(std::integral_constant<int, G>{});                 \
+        if (gend == G + 1) break;                            \
+        [[fallthrough]];
+template <class F>
+__device__ __forceinline__ void for_layer_groups(int g0, int gend, F&& f) {
+    static_assert(kNG == 14, "one case per register group");
+    switch (g0) {
+        DBSN_GROUP_CASE(0) DBSN_GROUP_CASE(1) DBSN_GROUP_CASE(2) DBSN_GROUP_CASE(3) DBSN_GROUP_CASE(4)
+        DBSN_GROUP_CASE(5) DBSN_GROUP_CASE(6) DBSN_GROUP_CASE(7) DBSN_GROUP_CASE(8) DBSN_GROUP_CASE(9)
+        DBSN_GROUP_CASE(10) DBSN_GROUP_CASE(11) DBSN_GROUP_CASE(12)
+        case 13: f(std::integral_constant<int, 13>{}); break;
+        default: break;
     }
-#define DBSN_LAYER_GROUPS(Ly) const int g0_ = (Ly).g0, ng_ = (Ly).ng
+}
 
-__device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const PLayer& Ly, const TileCtx& t) {
+// Entering the groups through that switch costs a few dozen scalar instructions per loop, as much
+// as the work of a small layer.  Networks whose layers fit a register LAYOUT fixed at compile time
+// (layer l owns the groups [g0(l), g0(l) + ngmax(l)), of which it uses its first ng) skip it: the
+// loops below then see constant group numbers, selected by one plain switch on the layer.
+// LAYOUT 0: groups packed in layer order at run time (any network);
+// LAYOUT 1: up to five hidden layers of at most 3, 5, 3, 2, 1 groups (the paper's nets with up to
+//           five hidden layers of 2500, 2000, 1500, 1000, 500 units or fewer fit).
+constexpr int kLayoutDepth = 5;
+constexpr int kLayoutG0[kLayoutDepth] = {0, 3, 8, 11, 13};
+constexpr int kLayoutNG[kLayoutDepth] = {3, 5, 3, 2, 1};
+// (All groups of the layer's static range run, used or not: an unused group holds zero weights and
+// meets zero deltas, so it publishes nothing and stays zero, and the code has no branch to merge.)
+template <int G, int GEND, class F>
+__device__ __forceinline__ void run_groups(F&& f) {
+    if constexpr (G < GEND) {
+        f(std::integral_constant<int, G>{});
+        run_groups<G + 1, GEND>(f);
+    }
+}
+// POS = 0: the layer is known at run time only (LAYOUT 0); POS = 1 .. kLayoutDepth: the phase is
+// compiled for hidden layer POS of LAYOUT 1.
+template <int POS, class F>
+__device__ __forceinline__ void layer_groups(int g0, int gend, F&& f) {
+    if constexpr (POS == 0) for_layer_groups(g0, gend, f);
+    else run_groups<kLayoutG0[POS - 1], kLayoutG0[POS - 1] + kLayoutNG[POS - 1]>(f);
+}
+
+// Register slot a = kGR * G + q of group G holds tile row wave + 8 * (a - kGR * g0) of the layer
+// whose groups start at g0 ("absolute" slot a, the same index in every per-slot register).
+struct TileGeom {
+    float* wbase;   // &W[r0][c0 + 4 * lane]
+    int ld, Reff, g0, gend;
+    bool lane_on;
+};
+__device__ inline TileGeom tile_geom(const PLayer& Ly, int g) {
+    TileGeom t;
+    const int lane = threadIdx.x & 63;
+    const int cb = g % Ly.nCB, rb = g / Ly.nCB;
+    const int c0 = cb * Ly.C, r0 = rb * Ly.R;
+    t.ld = Ly.ld;
+    t.Reff = min(Ly.R, Ly.n_out - r0);
+    t.g0 = Ly.g0;
+    t.gend = Ly.g0 + Ly.ng;
+    t.lane_on = (4 * lane < Ly.C) && (c0 + 4 * lane < Ly.ld);
+    t.wbase = Ly.W + (size_t)r0 * Ly.ld + c0 + 4 * lane;
+    return t;
+}
+__device__ inline bool has_tile(const PLayer& Ly, int g) { return g < Ly.nCB * Ly.nRB; }
+
+__device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const TileGeom& t) {
     const int wave = threadIdx.x >> 6;
-    DBSN_LAYER_GROUPS(Ly);
-    DBSN_FOR_LAYER_SLOTS(Ly, {
-        _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
-            const int rl = wave + kWaves * (sbase_ + q);
-            wr[kGR * G_ + q] = (rl < t.Reff && t.lane_on)
-                                 ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * Ly.ld)
-                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+    for_layer_groups(t.g0, t.gend, [&](auto Gc) {
+        constexpr int G = decltype(Gc)::value;
+#pragma unroll
+        for (int q = 0; q < kGR; ++q) {
+            const int rl = wave + kWaves * (kGR * (G - t.g0) + q);
+            wr[kGR * G + q] = (rl < t.Reff && t.lane_on)
+                                  ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * t.ld)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-    })
+    });
 }
-
-__device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const PLayer& Ly, const TileCtx& t) {
+__device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const TileGeom& t) {
     const int wave = threadIdx.x >> 6;
-    DBSN_LAYER_GROUPS(Ly);
-    DBSN_FOR_LAYER_SLOTS(Ly, {
-        _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
-            const int rl = wave + kWaves * (sbase_ + q);
-            if (rl < t.Reff && t.lane_on) *reinterpret_cast<float4*>(t.wbase + (size_t)rl * Ly.ld) = wr[kGR * G_ + q];
+    for_layer_groups(t.g0, t.gend, [&](auto Gc) {
+        constexpr int G = decltype(Gc)::value;
+#pragma unroll
+        for (int q = 0; q < kGR; ++q) {
+            const int rl = wave + kWaves * (kGR * (G - t.g0) + q);
+            if (rl < t.Reff && t.lane_on) *reinterpret_cast<float4*>(t.wbase + (size_t)rl * t.ld) = wr[kGR * G + q];
         }
-    })
+    });
 }
 
-// Rank-1 update of the tile held in registers, w[j][i] -= eta * delta_j * x_i (appendix "Weight
-// updating").  Lane s < kSlots of the wavefront holds in `dlane` the delta of the wavefront's s-th row;
-// rows beyond the tile hold zeros and get a zero delta, so they stay zero.
-__device__ __forceinline__ void update_tile(float4 (&wr)[kSlots], const PLayer& Ly, const float4& x4, float dlane,
-                                            float eta) {
-    DBSN_LAYER_GROUPS(Ly);
-    DBSN_FOR_LAYER_SLOTS(Ly, {
-        _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
-            const float ed = eta * __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
-            float4 v = wr[kGR * G_ + q];
-            v.x = fmaf(-ed, x4.x, v.x);
-            v.y = fmaf(-ed, x4.y, v.y);
-            v.z = fmaf(-ed, x4.z, v.z);
-            v.w = fmaf(-ed, x4.w, v.w);
-            wr[kGR * G_ + q] = v;
-        }
-    })
+__device__ inline const int* plan_of(const float* lds, int l) {
+    return reinterpret_cast<const int*>(lds + PLds::plan) + l * kPlanInts;
+}
+// The whole table row of layer l into registers with 128-bit LDS reads issued back to back (one
+// wait for all of them); what a phase does not use is dropped by the compiler.
+struct PlanRow {
+    int v[kPlanInts];
+    __device__ __forceinline__ int operator[](int i) const { return v[i]; }
+};
+__device__ __forceinline__ PlanRow load_plan(const float* lds, int l) {
+    PlanRow r;
+    const int4* src = reinterpret_cast<const int4*>(plan_of(lds, l));
+#pragma unroll
+    for (int k = 0; k < kPlanInts / 4; ++k) {
+        const int4 q = src[k];
+        r.v[4 * k + 0] = q.x; r.v[4 * k + 1] = q.y; r.v[4 * k + 2] = q.z; r.v[4 * k + 3] = q.w;
+    }
+    return r;
+}
+__device__ __forceinline__ u64* plan_ptr(const PlanRow& pl, int at) {
+    return reinterpret_cast<u64*>(((u64)(unsigned)uniform(pl[at + 1]) << 32) | (u64)(unsigned)uniform(pl[at]));
 }
 
-// deltas of the rows of this workgroup's tile of layer l, as left by the backward phase
-__device__ inline const float* tile_deltas(const PNet& net, int l, const TileCtx& t, const float* lds) {
-    return (l == net.L - 1) ? lds + PLds::dtop + t.r0 : lds + PLds::dkeep + l * kMaxTileRows;
+// Fills this workgroup's table (called by one thread per layer at kernel start).
+__device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
+    int* pl = reinterpret_cast<int*>(lds + PLds::plan) + l * kPlanInts;
+    const int L = net.L;
+    const PLayer& Ly = net.lay[l];
+    for (int e = 0; e < kPlanInts; ++e) pl[e] = 0;
+    auto put_ptr = [&](int at, const u64* p) {
+        pl[at] = (int)(unsigned)((u64)p & 0xFFFFFFFFull);
+        pl[at + 1] = (int)(unsigned)((u64)p >> 32);
+    };
+    if (l == L) {   // output layer: only the gathering of x_{L-1}
+        const PLayer& Lp = net.lay[L - 1];
+        pl[PL_FLAGS] = 1;
+        pl[PL_PF] = Lp.nCB;
+        pl[PL_FSTRIDE] = Lp.n_out;
+        pl[PL_FPAR] = Lp.nCB * Lp.n_out;
+        put_ptr(PL_FSRC, Lp.yp);
+        return;
+    }
+    if (!has_tile(Ly, g)) return;
+    const int cb = g % Ly.nCB, rb = g / Ly.nCB;
+    const int c0 = cb * Ly.C, r0 = rb * Ly.R;
+    const int Reff = min(Ly.R, Ly.n_out - r0);
+    pl[PL_FLAGS] = 1 | (cb == 0 ? 2 : 0) | (rb == 0 ? 4 : 0);
+    pl[PL_CEFF] = min(Ly.C, Ly.n_in - c0);
+    pl[PL_REFF] = Reff;
+    pl[PL_R0] = r0;
+    pl[PL_C0] = c0;
+    pl[PL_G0] = Ly.g0;
+    pl[PL_GEND] = Ly.g0 + Ly.ng;
+    pl[PL_RB] = rb;
+    pl[PL_FDPAR] = Ly.nCB * Ly.n_out;
+    put_ptr(PL_FDST, Ly.yp + (size_t)cb * Ly.n_out + r0);
+    if (l > 1) {
+        const PLayer& Lp = net.lay[l - 1];
+        pl[PL_PF] = Lp.nCB;
+        pl[PL_FSTRIDE] = Lp.n_out;
+        pl[PL_FPAR] = Lp.nCB * Lp.n_out;
+        put_ptr(PL_FSRC, Lp.yp + c0);
+        pl[PL_BDPAR] = Lp.nRB * Lp.R * Lp.gP;
+        pl[PL_RPREV] = Lp.R;
+        pl[PL_M20] = ((1 << 20) + Lp.R - 1) / Lp.R;
+        pl[PL_NPREV] = Lp.n_out;
+        pl[PL_CHUNKPREV] = Lp.gP * Lp.R;
+        put_ptr(PL_BDST, Lp.gp);
+    }
+    if (l < L - 1) {
+        pl[PL_GP] = Ly.gP;
+        pl[PL_NW] = Ly.gP * Reff;
+        pl[PL_BPAR] = Ly.nRB * Ly.R * Ly.gP;
+        put_ptr(PL_BSRC, Ly.gp + (size_t)rb * Ly.gP * Ly.R);
+    }
 }
 
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
 // partial sums of the rows over the tile's columns, the bias riding on column block 0.
-template <bool ST>
+template <bool ST, int POS>
 __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float x0pre,
                                            unsigned tag, bool last, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
-    const PLayer& Ly = net.lay[l];
-    TileCtx t;
-    if (!tile_ctx(Ly, g, t)) return true;
+    const PlanRow pl = load_plan(lds, l);
+    const int flags = uniform(pl[PL_FLAGS]);
+    if (!(flags & 1)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
-    DBSN_LAYER_GROUPS(Ly);
+    const int Ceff = uniform(pl[PL_CEFF]), Reff = uniform(pl[PL_REFF]);
+    const int g0 = uniform(pl[PL_G0]), gend = uniform(pl[PL_GEND]);
     DBSN_PROF_SUB(ps, ph, 0);
-    if (!ST) load_tile(wr, Ly, t);  // in flight while the inputs are awaited
+    if (!ST) load_tile(wr, tile_geom(net.lay[l], g));  // in flight while the inputs are awaited
 
-    float* xk = lds + PLds::xkeep + (par * (kMaxLayers + 1) + l) * 256;
+    float* xk = lds + PLds::xkeep + l * 256;
     if (l == 1) {
         // the caller fetched this thread's input pixel ahead of time
-        if (threadIdx.x < 256) xk[threadIdx.x] = (threadIdx.x < t.Ceff) ? x0pre : 0.0f;
+        if (threadIdx.x < 256) xk[threadIdx.x] = ((int)threadIdx.x < Ceff) ? x0pre : 0.0f;
         lds_barrier();
     } else {
-        // thread j < Ceff gathers the nCB partial sums of its input column j, adds them in index
-        // order and applies the activation: x_{l-1}[c0 + j]
-        const PLayer& Lp = net.lay[l - 1];
-        const bool poller = threadIdx.x < 256;
-        const bool on = (int)threadIdx.x < t.Ceff;
-        const u64* base = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out + t.c0;
-        const unsigned stride = (unsigned)Lp.n_out, col = on ? threadIdx.x : 0u;
-        auto off = [=](int k) { return (unsigned)k * stride + col; };
-        u64 v[16];
+        // thread j < Ceff of the lower four wavefronts gathers the partial sums of its input column j,
+        // adds them in index order and applies the activation: x_{l-1}[c0 + j]
         bool ok = true;
-        if (poller) {
-            poll_issue(v, Lp.nCB, base, off);
+        if (threadIdx.x < 256) {
+            const int P = uniform(pl[PL_PF]);
+            const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
+            const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
+            const unsigned col = min(threadIdx.x, (unsigned)Ceff - 1u);
+            for (int w = 0; w < net.fwd_delay; ++w) __builtin_amdgcn_s_sleep(1);
             DBSN_PROF_SUB(ps, ph, 1);
-            const float a = poll_finish(v, Lp.nCB, Lp.nCB, base, off, tag, net.spin_limit, ok);
-            xk[threadIdx.x] = on ? act_fast(a) : 0.0f;
+            const float a = poll_sum(base, col, P, stride, tag, net.spin_limit, ok);
+            const float x = ((int)threadIdx.x < Ceff) ? act_fast(a) : 0.0f;
+            xk[threadIdx.x] = x;
+            // state read-out after the last step (dbsn_mlp_get_activations): row block 0 writes the
+            // inputs it gathered
+            if (last && (flags & 4) && (int)threadIdx.x < Ceff) net.lay[l - 1].x[uniform(pl[PL_C0]) + threadIdx.x] = x;
             DBSN_PROF_SUB(ps, ph, 2);
         }
         if (!all_ok(ok, net.err, lds)) return false;
     }
     DBSN_PROF_SUB(ps, ph, 3);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
-    float* ysum = lds + PLds::ysum;
-    // per group: 2 row sums transposed onto pairs of lanes, reduced inside each row of 16 lanes on
-    // the vector ALU; the four rows of 16 park their sums in LDS and the publishing thread adds them
-    const int lrow = lane >> 4;
-    DBSN_FOR_LAYER_SLOTS(Ly, {
-        const float v2 = pair_sum2(dot4(wr[kGR * G_ + 0], x4), dot4(wr[kGR * G_ + 1], x4));
-        const int rl = wave + kWaves * (sbase_ + (lane & 1));
-        if ((lane & 14) == 0) ysum[lrow * kMaxTileRows + rl] = v2;
-    })
+    // the lane that will publish absolute slot a = lane (lanes 0 .. 31): tile row and bias
+    const int myrow = wave + kWaves * (lane - kGR * g0);
+    const bool pub = lane >= kGR * g0 && lane < kGR * gend && myrow < Reff;
+    const float mybias = (pub && (flags & 2)) ? lds[PLds::bias + l * kMaxTileRows + myrow] : 0.0f;
+    // per group: the two row sums transposed onto the even and odd lanes and reduced inside each row
+    // of 16 lanes; lane 16 r + (a & 15) keeps the sum of slot a over lane row r
+    float res0 = 0.0f, res1 = 0.0f;
+    const int lane14 = lane & 14;
+    layer_groups<POS>(g0, gend, [&](auto Gc) {
+        constexpr int G = decltype(Gc)::value;
+        const float v2 = pair_sum2(dot4(wr[kGR * G + 0], x4), dot4(wr[kGR * G + 1], x4));
+        if (kGR * G < 16) res0 = (lane14 == ((kGR * G) & 14)) ? v2 : res0;
+        else res1 = (lane14 == ((kGR * G) & 14)) ? v2 : res1;
+    });
+    res0 = rows_sum(res0);
+    if (gend > 8) res1 = rows_sum(res1);
     DBSN_PROF_SUB(ps, ph, 4);
-    lds_barrier();
-    DBSN_PROF_SUB(ps, ph, 5);
-    if (threadIdx.x >= 256) {   // the upper four wavefronts publish
-        u64* dst = Ly.yp + (size_t)par * Ly.nCB * Ly.n_out + (size_t)t.cb * Ly.n_out + t.r0;
-        for (int j = threadIdx.x - 256; j < t.Reff; j += 256) {
-            constexpr int kYS = kMaxTileRows;
-            float y = (ysum[j] + ysum[kYS + j]) + (ysum[2 * kYS + j] + ysum[3 * kYS + j]);
-            if (t.cb == 0) y += lds[PLds::bias + l * kMaxTileRows + j];
-            st_tagged(dst + j, y, tag);
-        }
-        // state read-out after the last step (dbsn_mlp_get_activations): row block 0 writes the
-        // inputs it gathered
-        if (last && l > 1 && t.rb == 0 && (int)threadIdx.x - 256 < t.Ceff)
-            net.lay[l - 1].x[t.c0 + threadIdx.x - 256] = xk[threadIdx.x - 256];
+    if (pub) {
+        u64* dst = plan_ptr(pl, PL_FDST) + (size_t)(par * (unsigned)uniform(pl[PL_FDPAR]));
+        st_tagged(dst + myrow, ((lane < 16) ? res0 : res1) + mybias, tag);
     }
     DBSN_PROF_SUB(ps, ph, 7);
     return true;
@@ -500,106 +574,152 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
 // "Weight updating" over the same registers): deltas of the tile's rows, partial W^T delta of its
 // columns from the OLD weights, published at once (it is what other workgroups wait for), then
 // the rank-1 update of the tile.
-template <bool ST>
+template <bool ST, int POS>
 __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float eta,
                                            unsigned tag, bool last, float* lds, long long ps,
                                            int ph DBSN_PROF_ARGS) {
-    const PLayer& Ly = net.lay[l];
-    TileCtx t;
-    if (!tile_ctx(Ly, g, t)) return true;
+    const PlanRow pl = load_plan(lds, l);
+    const int flags = uniform(pl[PL_FLAGS]);
+    if (!(flags & 1)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
-    DBSN_LAYER_GROUPS(Ly);
+    const int Ceff = uniform(pl[PL_CEFF]), Reff = uniform(pl[PL_REFF]);
+    const int g0 = uniform(pl[PL_G0]), gend = uniform(pl[PL_GEND]);
     DBSN_PROF_SUB(ps, ph, 0);
-    if (!ST) load_tile(wr, Ly, t);
+    TileGeom tg;
+    if (!ST) { tg = tile_geom(net.lay[l], g); load_tile(wr, tg); }
+    // the tile's inputs, kept since the forward sweep (read before this phase's first barrier: the
+    // next step's forward sweep overwrites them after it)
+    const float* xk = lds + PLds::xkeep + l * 256;
+    const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
 
-    // Deltas of the tile's rows.  For the last hidden layer they are in LDS already (the output
-    // layer was evaluated in this workgroup).  Otherwise the workgroup gathers the gP partials of
-    // each of its rows from the layer above into LDS (the producers have multiplied them by
-    // f'(x_l) already, see below) and four threads per row add a quarter each in index order.
-    const float* dl = tile_deltas(net, l, t, lds);
-    if (l < net.L - 1) {
-        float* dw = lds + PLds::dkeep + l * kMaxTileRows;
+    // Deltas of the wavefront's rows, lane a <-> absolute slot a.  For the last hidden layer they
+    // are in LDS already (the output layer was evaluated in this workgroup).  Otherwise the
+    // workgroup gathers its chunk of partials (gP per row, which the producers have multiplied by
+    // f'(x_l) already, see below) into LDS; then four lanes per row add a quarter of them each
+    // (partials q, q + 4, ... in index order) and combine as (q0 + q1) + (q2 + q3).
+    const int srel = lane - kGR * g0;   // slot of this lane within the layer
+    const int myrow = wave + kWaves * srel;
+    const bool rowon = srel >= 0 && lane < kGR * gend && myrow < Reff;
+    float dlane = 0.0f;
+    if (l == net.L - 1) {
+        if (rowon) dlane = lds[PLds::dtop + uniform(pl[PL_R0]) + myrow];
+    } else {
         float* sg = lds + PLds::stage;
-        const u64* gsrc = Ly.gp + (size_t)par * Ly.gP * Ly.n_out + t.r0;
-        const bool ok = poll_rows_to_lds<kThreads, 8>(gsrc, Ly.gP, t.Reff, (unsigned)Ly.n_out, tag, sg,
-                                                      net.spin_limit);
+        const int gP = uniform(pl[PL_GP]);
+        const u64* src = plan_ptr(pl, PL_BSRC) + (size_t)(par * (unsigned)uniform(pl[PL_BPAR]));
+        const bool ok = poll_chunk(src, (unsigned)uniform(pl[PL_NW]), tag, sg, net.spin_limit);
         DBSN_PROF_SUB(ps, ph, 1);
         if (!all_ok(ok, net.err, lds)) return false;
         DBSN_PROF_SUB(ps, ph, 2);
-        for (int t4 = threadIdx.x; (t4 >> 2) - (lane >> 2) < t.Reff; t4 += kThreads) {
-            // (trip count uniform over the wavefront: sum_row4 exchanges data inside quads)
-            const int j = t4 >> 2;
-            const float d = sum_row4(sg, Ly.gP, min(j, t.Reff - 1), t4 & 3);
-            if ((t4 & 3) == 0 && j < t.Reff) dw[j] = d;
+        const int q = lane & 3;
+        const int nslots = kGR * (gend - g0);
+        for (int s0 = 0; s0 < nslots; s0 += 16) {
+            const int row = min(wave + kWaves * (s0 + (lane >> 2)), Reff - 1);
+            float acc = 0.0f;
+            for (int pb = 0; pb < gP; pb += 16) {
+                float tv[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int p = pb + q + 4 * k;
+                    tv[k] = (p < gP) ? sg[p * Reff + row] : 0.0f;
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc += tv[k];
+            }
+            acc += dpp_mov<kDppXor1>(acc);
+            acc += dpp_mov<kDppXor2>(acc);
+            // lane a takes the sum of its slot from the quad that formed it
+            const float got = __shfl(acc, (4 * (srel - s0)) & 63, 64);
+            if (srel >= s0 && srel < s0 + 16) dlane = got;
         }
-        lds_barrier();
+        if (!rowon) dlane = 0.0f;
     }
-    const int myrow = wave + kWaves * lane;
-    const float dlane = (lane < kSlots && myrow < t.Reff) ? dl[myrow] : 0.0f;
     DBSN_PROF_SUB(ps, ph, 3);
-    const float* xk = lds + PLds::xkeep + (par * (kMaxLayers + 1) + l) * 256;
-    const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     if (l > 1) {
         float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
-        DBSN_FOR_LAYER_SLOTS(Ly, {
-            _Pragma("unroll") for (int q = 0; q < kGR; ++q) {
-                const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), sbase_ + q));
-                const float4 w4 = wr[kGR * G_ + q];
+        layer_groups<POS>(g0, gend, [&](auto Gc) {
+            constexpr int G = decltype(Gc)::value;
+#pragma unroll
+            for (int q = 0; q < kGR; ++q) {
+                const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), kGR * G + q));
+                const float4 w4 = wr[kGR * G + q];
                 gacc.x = fmaf(w4.x, d, gacc.x);
                 gacc.y = fmaf(w4.y, d, gacc.y);
                 gacc.z = fmaf(w4.z, d, gacc.z);
                 gacc.w = fmaf(w4.w, d, gacc.w);
             }
-        })
+        });
         float* gred = lds + PLds::gred;
         *reinterpret_cast<float4*>(gred + wave * 264 + 4 * lane) = gacc;
         DBSN_PROF_SUB(ps, ph, 4);
         lds_barrier();
         DBSN_PROF_SUB(ps, ph, 5);
-        const PLayer& Lp = net.lay[l - 1];
-        u64* dst = Lp.gp + (size_t)par * Lp.gP * Lp.n_out + (size_t)t.rb * Lp.n_out + t.c0;
-        const int i = (int)threadIdx.x - 256;   // the upper four wavefronts publish
-        if (i >= 0 && i < t.Ceff) {
+        const int i = (int)threadIdx.x;   // the lower four wavefronts publish, one column each
+        if (i < Ceff) {
             float v8[kWaves];
 #pragma unroll
             for (int k = 0; k < kWaves; ++k) v8[k] = gred[k * 264 + i];
+            const float xi = xk[i];
             float s8 = 0.0f;
 #pragma unroll
             for (int k = 0; k < kWaves; ++k) s8 += v8[k];
+            // where the word goes: neuron c of the layer below belongs to that layer's row block
+            // c / R', whose chunk keeps this tile's row block rb at offset rb * Reff'
+            const unsigned c = (unsigned)uniform(pl[PL_C0]) + (unsigned)i;
+            const unsigned Rp = (unsigned)uniform(pl[PL_RPREV]);
+            const unsigned rbq = (c * (unsigned)uniform(pl[PL_M20])) >> 20;
+            const unsigned jp = c - rbq * Rp;
+            const unsigned Reffp = min(Rp, (unsigned)uniform(pl[PL_NPREV]) - rbq * Rp);
+            u64* dst = plan_ptr(pl, PL_BDST) + (size_t)(par * (unsigned)uniform(pl[PL_BDPAR]));
             // this tile's columns are neurons of layer l-1 whose outputs it holds: fold f' in here,
             // so that the consumer's sum over row blocks is delta_{l-1} itself
-            st_tagged(dst + i, s8 * dact_from_y(xk[i]), tag);
+            st_tagged(dst + (rbq * (unsigned)uniform(pl[PL_CHUNKPREV]) + (unsigned)uniform(pl[PL_RB]) * Reffp + jp),
+                      s8 * dact_from_y(xi), tag);
         }
     }
     DBSN_PROF_SUB(ps, ph, 6);
-    update_tile(wr, Ly, x4, dlane, eta);
-    if (!ST) store_tile(wr, Ly, t);
-    if (t.cb == 0) {
+    // rank-1 update of the tile held in registers, w[j][i] -= eta * delta_j * x_i; rows beyond the
+    // tile hold zeros and get a zero delta, so they stay zero
+    layer_groups<POS>(g0, gend, [&](auto Gc) {
+        constexpr int G = decltype(Gc)::value;
+#pragma unroll
+        for (int q = 0; q < kGR; ++q) {
+            const float ed = eta * __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dlane), kGR * G + q));
+            float4 v = wr[kGR * G + q];
+            v.x = fmaf(-ed, x4.x, v.x);
+            v.y = fmaf(-ed, x4.y, v.y);
+            v.z = fmaf(-ed, x4.z, v.z);
+            v.w = fmaf(-ed, x4.w, v.w);
+            wr[kGR * G + q] = v;
+        }
+    });
+    if (!ST) store_tile(wr, tg);
+    if ((flags & 2) && rowon) {
         // bias update (the biases of this tile's rows live in LDS for the whole launch), and after
         // the last step the layer's deltas for dbsn_mlp_get_deltas
-        for (int j = threadIdx.x; j < t.Reff; j += kThreads) {
-            const float d = dl[j];
-            lds[PLds::bias + l * kMaxTileRows + j] -= eta * d;
-            if (last) Ly.d[t.r0 + j] = d;
-        }
+        lds[PLds::bias + l * kMaxTileRows + myrow] -= eta * dlane;
+        if (last) net.lay[l].d[uniform(pl[PL_R0]) + myrow] = dlane;
     }
+    // with a single hidden layer this phase has no barrier of its own between reading the inputs
+    // and the next step's forward sweep, which overwrites them
+    if (l == 1 && net.L == 2) lds_barrier();
     DBSN_PROF_SUB(ps, ph, 7);
     return true;
 }
 
-// Output layer in every workgroup, on its private LDS copy of W_L: x_{L-1} from the partials,
-// logits, softmax, loss, delta_L, the deltas of layer L-1 and the rank-1 update of the copy.
-// Thread i owns column i (input neuron i) of W_L: it gathers x_i and forms the products
-// W_L[j][i] x_i; the workgroup adds them per class (quads -> rows of 16 lanes on the vector ALU,
-// then 32 partial sums per class through LDS); wavefront 0 does the softmax, and each thread
-// back-propagates through and updates its column.
+// Output layer in every workgroup, on its private LDS copy of W_L (classes padded to a multiple of
+// four with zero rows): x_{L-1} from the partials, logits, softmax, loss, delta_L, the deltas of
+// layer L-1 and the rank-1 update of the copy.  Thread i owns column i (input neuron i) of W_L
+// (and i + 512, ...): it gathers x_i and forms the products W_L[j][i] x_i; the workgroup adds them
+// per class (quads -> rows of 16 lanes on the vector ALU, then 32 partial sums per class through
+// LDS); wavefront 0 does the softmax, and each thread back-propagates through and updates its columns.
 __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
                                       bool last, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
     const int L = net.L;
     const PLayer& Ly = net.lay[L];
-    const PLayer& Lp = net.lay[L - 1];
-    const int n = Ly.n_in, nc = Ly.n_out;
+    const PlanRow pl = load_plan(lds, L);
+    const int n = Ly.n_in, nc = Ly.n_out, ncq = (nc + 3) >> 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
     float* xtop = lds + PLds::xtop;
@@ -607,55 +727,52 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     float* WL = lds + PLds::WL;
     float* bL = lds + PLds::bL;
     float* part = lds + PLds::gred;    // [class][33]: 8 wavefronts x 4 rows of 16 lanes (pitch 33: no bank conflicts)
-    float* dL = lds + PLds::ysum;      // [kMaxClasses] delta_L
+    float* dL = lds + PLds::dLp;       // [kMaxClasses] delta_L, then [kMaxClasses] probabilities
 
     DBSN_PROF_SUB(ps, ph, 0);
     bool ok = true;
     {
-        // thread i gathers x_{L-1}[i] (and i + 512, ...): the nCB partial sums in index order
-        const u64* base = Lp.yp + (size_t)par * Lp.nCB * Lp.n_out;
-        const unsigned stride = (unsigned)Lp.n_out;
+        // thread i gathers x_{L-1}[i] (and i + 512, ...): the partial sums in index order
+        const int P = uniform(pl[PL_PF]);
+        const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
+        const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
+        for (int w = 0; w < net.fwd_delay; ++w) __builtin_amdgcn_s_sleep(1);
         for (int i0 = 0; i0 < n; i0 += kThreads) {
             const int i = i0 + (int)threadIdx.x;
-            const bool on = i < n;
-            const unsigned col = on ? (unsigned)i : 0u;
-            auto off = [=](int k) { return (unsigned)k * stride + col; };
-            u64 v[16];
-            poll_issue(v, Lp.nCB, base, off);
-            const float a = poll_finish(v, Lp.nCB, Lp.nCB, base, off, tag, net.spin_limit, ok);
-            if (on) xtop[i] = act_fast(a);
+            const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok);
+            if (i < n) xtop[i] = act_fast(a);
         }
     }
     DBSN_PROF_SUB(ps, ph, 2);
     // products per class, four classes at a time; a thread folds its columns i, i + 512, ... together
-    for (int j0 = 0; j0 < nc; j0 += 4) {
+    for (int jq = 0; jq < ncq; ++jq) {
         float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-        const int j1 = min(j0 + 1, nc - 1), j2 = min(j0 + 2, nc - 1), j3 = min(j0 + 3, nc - 1);
+        const float* w = WL + 4 * jq * n;
         for (int i = threadIdx.x; i < n; i += kThreads) {
             const float xi = xtop[i];   // this thread's own write
-            a0 = fmaf(WL[j0 * n + i], xi, a0);
-            a1 = fmaf(WL[j1 * n + i], xi, a1);
-            a2 = fmaf(WL[j2 * n + i], xi, a2);
-            a3 = fmaf(WL[j3 * n + i], xi, a3);
+            a0 = fmaf(w[i], xi, a0);
+            a1 = fmaf(w[n + i], xi, a1);
+            a2 = fmaf(w[2 * n + i], xi, a2);
+            a3 = fmaf(w[3 * n + i], xi, a3);
         }
         const float v = quad_sum4(a0, a1, a2, a3);
-        const int cls = j0 + (lane & 3);
-        if ((lane & 12) == 0 && cls < nc) part[cls * 33 + wave * 4 + (lane >> 4)] = v;
+        if ((lane & 12) == 0) part[(4 * jq + (lane & 3)) * 33 + wave * 4 + (lane >> 4)] = v;
     }
     DBSN_PROF_SUB(ps, ph, 3);
     if (!all_ok(ok, net.err, lds)) return false;
     DBSN_PROF_SUB(ps, ph, 4);
     if (wave == 0) {
-        // class c = lane: logit, softmax (the sum of the exponentials is taken in index order)
+        // class c = lane: logit (32 partial sums added pairwise in a fixed tree), softmax
         float a = -3.0e38f;
         if (lane < nc) {
             float v[32];
 #pragma unroll
             for (int r = 0; r < 32; ++r) v[r] = part[lane * 33 + r];
-            float acc = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 32; ++r) acc += v[r];
-            a = acc + bL[lane];
+            for (int w = 16; w >= 1; w >>= 1)
+#pragma unroll
+                for (int r = 0; r < w; ++r) v[r] = v[2 * r] + v[2 * r + 1];
+            a = v[0] + bL[lane];
         }
         float m = a;
         m = fmaxf(m, dpp_mov<kDppXor1>(m));
@@ -668,14 +785,19 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         } else {
             m = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(m)));   // row 0 holds all classes
         }
-        const float e = (lane < nc) ? expf(a - m) : 0.0f;
-        float ssum = 0.0f;
-        for (int c = 0; c < nc; ++c) ssum += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e), c));
+        const float e = (lane < nc) ? __expf(a - m) : 0.0f;
+        // sum of the exponentials: fixed tree inside the rows of 16 lanes, then the four rows
+        float ssum = e;
+        ssum += dpp_mov<kDppXor1>(ssum);
+        ssum += dpp_mov<kDppXor2>(ssum);
+        ssum += dpp_mov<kDppRor4>(ssum);
+        ssum += dpp_mov<kDppRor8>(ssum);
+        if (nc > 16) ssum = rows_sum(ssum);
+        else ssum = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ssum)));
         const float p = e / ssum;
-        if (lane < nc) {
-            dL[lane] = p - (lane == label ? 1.0f : 0.0f);
-            dL[kMaxClasses + lane] = p;
-        }
+        // classes nc .. 4 ncq - 1 are padding: zero delta keeps their zero weights zero
+        dL[lane] = (lane < nc) ? p - (lane == label ? 1.0f : 0.0f) : 0.0f;
+        dL[kMaxClasses + lane] = p;
     }
     DBSN_PROF_SUB(ps, ph, 5);
     lds_barrier();
@@ -686,22 +808,25 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         if (lane == 0 && loss_out) *loss_out = -logf(dL[kMaxClasses + label]);
         if (last) {
             if (lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
-            for (int i = lane; i < n; i += 64) Lp.x[i] = xtop[i];
+            for (int i = lane; i < n; i += 64) net.lay[L - 1].x[i] = xtop[i];
         }
     }
     // deltas of layer L-1 and update of the private W_L
     for (int i = threadIdx.x; i < n; i += kThreads) {
         const float xi = xtop[i];
         float gs = 0.0f;
-        for (int j0 = 0; j0 < nc; j0 += 4) {
-            const int j1 = min(j0 + 1, nc - 1), j2 = min(j0 + 2, nc - 1), j3 = min(j0 + 3, nc - 1);
-            const float w0 = WL[j0 * n + i], w1 = WL[j1 * n + i], w2 = WL[j2 * n + i], w3 = WL[j3 * n + i];
-            const float d0 = dL[j0], d1 = dL[j1], d2 = dL[j2], d3 = dL[j3];
-            gs = fmaf(w0, d0, gs);
-            WL[j0 * n + i] = fmaf(-(eta * d0), xi, w0);
-            if (j0 + 1 < nc) { gs = fmaf(w1, d1, gs); WL[j1 * n + i] = fmaf(-(eta * d1), xi, w1); }
-            if (j0 + 2 < nc) { gs = fmaf(w2, d2, gs); WL[j2 * n + i] = fmaf(-(eta * d2), xi, w2); }
-            if (j0 + 3 < nc) { gs = fmaf(w3, d3, gs); WL[j3 * n + i] = fmaf(-(eta * d3), xi, w3); }
+        for (int jq = 0; jq < ncq; ++jq) {
+            float* w = WL + 4 * jq * n + i;
+            const float4 d4 = *reinterpret_cast<const float4*>(dL + 4 * jq);
+            const float w0 = w[0], w1 = w[n], w2 = w[2 * n], w3 = w[3 * n];
+            gs = fmaf(w0, d4.x, gs);
+            gs = fmaf(w1, d4.y, gs);
+            gs = fmaf(w2, d4.z, gs);
+            gs = fmaf(w3, d4.w, gs);
+            w[0] = fmaf(-(eta * d4.x), xi, w0);
+            w[n] = fmaf(-(eta * d4.y), xi, w1);
+            w[2 * n] = fmaf(-(eta * d4.z), xi, w2);
+            w[3 * n] = fmaf(-(eta * d4.w), xi, w3);
         }
         dtop[i] = gs * dact_from_y(xi);
     }
@@ -711,7 +836,7 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     return true;
 }
 
-template <bool ST>
+template <bool ST, int LAYOUT>
 __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float* samples, const int* labels,
                                                            int label_val, long long n, float eta, float* loss_out,
                                                            unsigned tag_base) {
@@ -720,36 +845,41 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     const int g = blockIdx.x, L = net.L;
     const PLayer& LyL = net.lay[L];
     const int n0 = net.lay[1].n_in;
-    // private copy of the output layer
-    for (int e = threadIdx.x; e < LyL.n_out * LyL.n_in; e += kThreads) {
-        const int j = e / LyL.n_in, i = e - j * LyL.n_in;
-        lds[PLds::WL + e] = LyL.W[(size_t)j * LyL.ld + i];
+    // private copy of the output layer, classes padded to a multiple of four with zero rows
+    {
+        const int nL = LyL.n_in, ncp = ((LyL.n_out + 3) >> 2) << 2;
+        for (int e = threadIdx.x; e < ncp * nL; e += kThreads) {
+            const int j = e / nL, i = e - j * nL;
+            lds[PLds::WL + e] = (j < LyL.n_out) ? LyL.W[(size_t)j * LyL.ld + i] : 0.0f;
+        }
     }
-    if (threadIdx.x < LyL.n_out) lds[PLds::bL + threadIdx.x] = LyL.b[threadIdx.x];
-    for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
+    if (threadIdx.x < kMaxClasses) lds[PLds::bL + threadIdx.x] = ((int)threadIdx.x < LyL.n_out) ? LyL.b[threadIdx.x] : 0.0f;
+    for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
+    for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
+    if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
 
     for (int l = 1; l < L; ++l) {
-        TileCtx t;
-        if (tile_ctx(net.lay[l], g, t) && t.cb == 0)
-            for (int j = threadIdx.x; j < t.Reff; j += kThreads)
-                lds[PLds::bias + l * kMaxTileRows + j] = net.lay[l].b[t.r0 + j];
+        const PLayer& Ly = net.lay[l];
+        if (has_tile(Ly, g) && g % Ly.nCB == 0) {
+            const int r0 = (g / Ly.nCB) * Ly.R, Reff = min(Ly.R, Ly.n_out - r0);
+            for (int j = threadIdx.x; j < Reff; j += kThreads) lds[PLds::bias + l * kMaxTileRows + j] = Ly.b[r0 + j];
+        }
     }
     float4 wr[kSlots];
 #pragma unroll
     for (int s = 0; s < kSlots; ++s) wr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ST) {
-        for (int l = 1; l < L; ++l) {
-            TileCtx t;
-            if (tile_ctx(net.lay[l], g, t)) load_tile(wr, net.lay[l], t);
-        }
+        for (int l = 1; l < L; ++l)
+            if (has_tile(net.lay[l], g)) load_tile(wr, tile_geom(net.lay[l], g));
     }
     __syncthreads();
 
     // this thread's input pixel of the first layer's tile, fetched one sample ahead
-    TileCtx t1;
-    const bool has1 = tile_ctx(net.lay[1], g, t1) && (int)threadIdx.x < t1.Ceff;
-    float x0pre = (has1 && n > 0) ? samples[t1.c0 + threadIdx.x] : 0.0f;
+    const int* pl1 = plan_of(lds, 1);
+    const bool has1 = (pl1[PL_FLAGS] & 1) && (int)threadIdx.x < pl1[PL_CEFF];
+    const int c01 = pl1[PL_C0];
+    float x0pre = (has1 && n > 0) ? samples[c01 + threadIdx.x] : 0.0f;
     int labpre = (labels && n > 0) ? labels[0] : label_val;
 
     bool alive = true;
@@ -759,29 +889,47 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
         label = label < 0 ? 0 : (label >= LyL.n_out ? LyL.n_out - 1 : label);
         const float x0cur = x0pre;
         if (s + 1 < n) {
-            if (has1) x0pre = samples[(s + 1) * n0 + t1.c0 + threadIdx.x];
+            if (has1) x0pre = samples[(s + 1) * n0 + c01 + threadIdx.x];
             if (labels) labpre = labels[s + 1];
         }
         const bool last = (s + 1 == n);
-        for (int l = 1; l < L && alive; ++l)
-            alive = p_fwd_tile<ST>(wr, net, l, g, x0cur, tag, last, lds, s, l - 1 DBSN_PROF_PASS);
+#define DBSN_FWD(POS, l) p_fwd_tile<ST, POS>(wr, net, l, g, x0cur, tag, last, lds, s, (l) - 1 DBSN_PROF_PASS)
+#define DBSN_BWD(POS, l) p_bwd_tile<ST, POS>(wr, net, l, g, eta, tag, last, lds, s, L + (L - 1 - (l)) DBSN_PROF_PASS)
+        if constexpr (LAYOUT == 0) {
+            for (int l = 1; l < L && alive; ++l) alive = DBSN_FWD(0, l);
+        } else {
+            static_assert(kLayoutDepth == 5, "one line per hidden layer of the layout");
+            alive = DBSN_FWD(1, 1);
+            if (L > 2 && alive) alive = DBSN_FWD(2, 2);
+            if (L > 3 && alive) alive = DBSN_FWD(3, 3);
+            if (L > 4 && alive) alive = DBSN_FWD(4, 4);
+            if (L > 5 && alive) alive = DBSN_FWD(5, 5);
+        }
         if (alive)
             alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, last, lds, s, L - 1 DBSN_PROF_PASS);
-        for (int l = L - 1; l >= 1 && alive; --l)
-            alive = p_bwd_tile<ST>(wr, net, l, g, eta, tag, last, lds, s, L + (L - 1 - l) DBSN_PROF_PASS);
+        if constexpr (LAYOUT == 0) {
+            for (int l = L - 1; l >= 1 && alive; --l) alive = DBSN_BWD(0, l);
+        } else {
+            if (L > 5 && alive) alive = DBSN_BWD(5, 5);
+            if (L > 4 && alive) alive = DBSN_BWD(4, 4);
+            if (L > 3 && alive) alive = DBSN_BWD(3, 3);
+            if (L > 2 && alive) alive = DBSN_BWD(2, 2);
+            if (alive) alive = DBSN_BWD(1, 1);
+        }
+#undef DBSN_FWD
+#undef DBSN_BWD
     }
     if (ST) {
-        for (int l = 1; l < L; ++l) {
-            TileCtx t;
-            if (tile_ctx(net.lay[l], g, t)) store_tile(wr, net.lay[l], t);
-        }
+        for (int l = 1; l < L; ++l)
+            if (has_tile(net.lay[l], g)) store_tile(wr, tile_geom(net.lay[l], g));
     }
     __syncthreads();
     for (int l = 1; l < L; ++l) {
-        TileCtx t;
-        if (tile_ctx(net.lay[l], g, t) && t.cb == 0)
-            for (int j = threadIdx.x; j < t.Reff; j += kThreads)
-                net.lay[l].b[t.r0 + j] = lds[PLds::bias + l * kMaxTileRows + j];
+        const PLayer& Ly = net.lay[l];
+        if (has_tile(Ly, g) && g % Ly.nCB == 0) {
+            const int r0 = (g / Ly.nCB) * Ly.R, Reff = min(Ly.R, Ly.n_out - r0);
+            for (int j = threadIdx.x; j < Reff; j += kThreads) Ly.b[r0 + j] = lds[PLds::bias + l * kMaxTileRows + j];
+        }
     }
     DBSN_PROF_FLUSH();
     if (g == 0) {
