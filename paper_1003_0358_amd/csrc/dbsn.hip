@@ -100,8 +100,6 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         if (l <= L - 2) {
             // one chunk of nRB_{l+1} x R_l words per row block, see PLayer::gp
             p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l] * p.R[l] * p.nRB[l + 1]);
-            // staging of one tile's chunk in LDS
-            if (p.R[l] * p.nRB[l + 1] > kStageFloats) p.persistent_ok = false;
         }
     }
     // register groups of kGR rows per wavefront: stationary when every layer gets groups of its own

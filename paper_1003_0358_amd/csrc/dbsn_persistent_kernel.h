@@ -97,7 +97,7 @@ constexpr int kSlots = kGR * kNG;    // rows a wavefront holds: 28 (a tile has a
 constexpr int kMaxTileRows = kSlots * kWaves;   // 224
 constexpr int kTopWMax = 10240;      // floats of W_L kept in LDS (rows padded to a multiple of four classes)
 constexpr int kTopXMax = 2048;       // neurons of layer L-1 the output phase can take
-constexpr int kStageFloats = 7168;   // LDS staging for the partials a backward tile gathers (14 x 512)
+constexpr int kStageFloats = kWaves * kMaxTileRows;   // per-wavefront partial deltas of a tile's rows
 static_assert(kGR == 2, "the forward reduction pairs the two rows of a register group");
 static_assert(kSlots <= 32, "one lane per row slot, two blocks of 16");
 
@@ -152,7 +152,7 @@ struct PLds {
     static constexpr int bL = WL + kTopWMax;                      // [kMaxClasses]
     static constexpr int xkeep = bL + kMaxClasses;                // [kMaxLayers + 1][256] inputs of each tile
     static constexpr int bias = xkeep + (kMaxLayers + 1) * 256;   // [kMaxLayers + 1][kMaxTileRows] (column block 0)
-    static constexpr int stage = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kStageFloats]
+    static constexpr int stage = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kWaves][kMaxTileRows]
     static constexpr int dLp = stage + kStageFloats;              // [2][kMaxClasses] delta_L (padded with zeros), probabilities
     static constexpr int gred = dLp + 2 * kMaxClasses;            // [kWaves][264]; [class][33] partial logits
     static constexpr int xtop = gred + kWaves * 264;              // [kTopXMax]
@@ -162,7 +162,7 @@ struct PLds {
     static constexpr int total = fail + 16;
 };
 static_assert((PLds::total + kProfLdsFloats) * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
-static_assert(kMaxClasses * 33 <= kWaves * 264, "partial logits do not fit");
+static_assert(kMaxClasses * kWaves <= kWaves * 264, "partial logits do not fit");
 
 __device__ inline u64 pack_tagged(float v, unsigned tag) { return ((u64)tag << 32) | (u64)__float_as_uint(v); }
 // (the words are in device memory: saying so keeps the compiler from emitting generic-address loads
@@ -267,48 +267,18 @@ __device__ __forceinline__ float poll_sum_n(const u64* base, unsigned col, int P
     for (int k = 0; k < N; ++k) s += (k < P) ? __uint_as_float((unsigned)v[k]) : 0.0f;
     return s;
 }
-// (more than 12 partials, i.e. layers wider than 3072, take two batches one after the other)
+// (more than 12 partials take batches of 8 one after the other)
 __device__ __forceinline__ float poll_sum(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
                                           unsigned limit, bool& ok) {
-    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, 0.0f);
-    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, 0.0f);
-    if (P <= 12) return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, 0.0f);
-    const float s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, 0.0f);
-    return poll_sum_n<8>(base + (size_t)(8u * stride), col, P - 8, stride, tag, limit, ok, s);
-}
-
-// Gathering a contiguous chunk of nW <= NK * 512 tagged words into the staging area: thread t
-// takes words t, t + 512, ... (a wavefront reads runs of 64 consecutive words); stage[w] receives
-// the payload of word w.  Slots beyond the chunk repeat its last word.
-template <int NK>
-__device__ __forceinline__ bool poll_chunk_n(const u64* base, unsigned w0, unsigned nW, unsigned tag, float* stage,
-                                             unsigned limit) {
-    u64 v[NK];
-    bool ok = true;
-    unsigned spins = 0;
-    for (;;) {
-#pragma unroll
-        for (int k = 0; k < NK; ++k) v[k] = ld_tagged(base + min(w0 + threadIdx.x + (unsigned)kThreads * k, nW - 1u));
-        bool pending = false;
-#pragma unroll
-        for (int k = 0; k < NK; ++k) pending |= ((unsigned)(v[k] >> 32) != tag);
-        if (!__any(pending && DBSN_WAITING(limit))) break;
-        if (++spins > limit) { ok = false; break; }
+    float s = 0.0f;
+    while (P > 12 && ok) {
+        s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, s);
+        base += (size_t)(8u * stride);
+        P -= 8;
     }
-#pragma unroll
-    for (int k = 0; k < NK; ++k) {
-        const unsigned w = w0 + threadIdx.x + (unsigned)kThreads * k;
-        if (w < nW) stage[w] = __uint_as_float((unsigned)v[k]);
-    }
-    return ok;
-}
-// (chunks of more than 4096 words take several batches one after the other)
-__device__ __forceinline__ bool poll_chunk(const u64* base, unsigned nW, unsigned tag, float* stage, unsigned limit) {
-    if (nW <= 2u * kThreads) return poll_chunk_n<2>(base, 0u, nW, tag, stage, limit);
-    if (nW <= 4u * kThreads) return poll_chunk_n<4>(base, 0u, nW, tag, stage, limit);
-    bool ok = true;
-    for (unsigned w0 = 0; w0 < nW && ok; w0 += 8u * kThreads) ok = poll_chunk_n<8>(base, w0, nW, tag, stage, limit);
-    return ok;
+    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, s);
+    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, s);
+    return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, s);
 }
 
 // y(a) = A tanh(B a) without the library routine: tanh(t) = 1 - 2 / (exp(2t) + 1) away from zero,
@@ -595,9 +565,11 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
 
     // Deltas of the wavefront's rows, lane a <-> absolute slot a.  For the last hidden layer they
     // are in LDS already (the output layer was evaluated in this workgroup).  Otherwise the
-    // workgroup gathers its chunk of partials (gP per row, which the producers have multiplied by
-    // f'(x_l) already, see below) into LDS; then four lanes per row add a quarter of them each
-    // (partials q, q + 4, ... in index order) and combine as (q0 + q1) + (q2 + q3).
+    // workgroup gathers its chunk of partials: gP per row, which the producers have multiplied by
+    // f'(x_l) already (see below).  The rows are dealt to the lanes (64 at a time) and the
+    // partials to classes p mod NPC; wavefront w takes rows 64 (w mod NR) ... and class w / NR,
+    // adds its partials in index order and leaves the sum in LDS; then lane a adds the NPC sums of
+    // its row in class order.
     const int srel = lane - kGR * g0;   // slot of this lane within the layer
     const int myrow = wave + kWaves * srel;
     const bool rowon = srel >= 0 && lane < kGR * gend && myrow < Reff;
@@ -608,32 +580,27 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         float* sg = lds + PLds::stage;
         const int gP = uniform(pl[PL_GP]);
         const u64* src = plan_ptr(pl, PL_BSRC) + (size_t)(par * (unsigned)uniform(pl[PL_BPAR]));
-        const bool ok = poll_chunk(src, (unsigned)uniform(pl[PL_NW]), tag, sg, net.spin_limit);
+        const int lgNR = Reff > 128 ? 2 : (Reff > 64 ? 1 : 0);   // rounds of 64 rows: 1, 2 or 4
+        const int NPC = kWaves >> lgNR;
+        const int pc = wave >> lgNR;
+        const int j = 64 * (wave & ((1 << lgNR) - 1)) + lane;
+        const int Pw = (gP - pc + NPC - 1) / NPC;               // partials of this wavefront's class
+        bool ok = true;
+        float part = 0.0f;
+        if (Pw > 0 && 64 * (wave & ((1 << lgNR) - 1)) < Reff)
+            part = poll_sum(src + (size_t)((unsigned)pc * (unsigned)Reff), (unsigned)min(j, Reff - 1), Pw,
+                            (unsigned)(NPC * Reff), tag, net.spin_limit, ok);
+        if (j < Reff) sg[pc * kMaxTileRows + j] = part;
         DBSN_PROF_SUB(ps, ph, 1);
         if (!all_ok(ok, net.err, lds)) return false;
         DBSN_PROF_SUB(ps, ph, 2);
-        const int q = lane & 3;
-        const int nslots = kGR * (gend - g0);
-        for (int s0 = 0; s0 < nslots; s0 += 16) {
-            const int row = min(wave + kWaves * (s0 + (lane >> 2)), Reff - 1);
-            float acc = 0.0f;
-            for (int pb = 0; pb < gP; pb += 16) {
-                float tv[4];
+        if (rowon) {
+            float pv[kWaves];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int p = pb + q + 4 * k;
-                    tv[k] = (p < gP) ? sg[p * Reff + row] : 0.0f;
-                }
+            for (int k = 0; k < kWaves; ++k) pv[k] = (k < NPC) ? sg[k * kMaxTileRows + myrow] : 0.0f;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) acc += tv[k];
-            }
-            acc += dpp_mov<kDppXor1>(acc);
-            acc += dpp_mov<kDppXor2>(acc);
-            // lane a takes the sum of its slot from the quad that formed it
-            const float got = __shfl(acc, (4 * (srel - s0)) & 63, 64);
-            if (srel >= s0 && srel < s0 + 16) dlane = got;
+            for (int k = 0; k < kWaves; ++k) dlane += pv[k];
         }
-        if (!rowon) dlane = 0.0f;
     }
     DBSN_PROF_SUB(ps, ph, 3);
     if (l > 1) {
@@ -726,53 +693,71 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     float* dtop = lds + PLds::dtop;
     float* WL = lds + PLds::WL;
     float* bL = lds + PLds::bL;
-    float* part = lds + PLds::gred;    // [class][33]: 8 wavefronts x 4 rows of 16 lanes (pitch 33: no bank conflicts)
+    float* part = lds + PLds::gred;    // [class][8 wavefronts] partial logits
     float* dL = lds + PLds::dLp;       // [kMaxClasses] delta_L, then [kMaxClasses] probabilities
 
     DBSN_PROF_SUB(ps, ph, 0);
     bool ok = true;
-    {
+    const int P = uniform(pl[PL_PF]);
+    const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
+    const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
+    for (int w = 0; w < net.fwd_delay; ++w) __builtin_amdgcn_s_sleep(1);
+    // One column per thread and at most 16 classes (the paper's nets): the column of W_L stays in
+    // registers from the products to the update.  Otherwise the same steps with loops over the
+    // thread's columns and the classes.
+    const bool small = n <= kThreads && ncq <= 4;
+    float xi = 0.0f, wcol[16];
+    if (small) {
+        const int i = (int)threadIdx.x, ic = min(i, n - 1);
+        const float a = poll_sum(base, (unsigned)ic, P, stride, tag, net.spin_limit, ok);
+        xi = (i < n) ? act_fast(a) : 0.0f;
+        DBSN_PROF_SUB(ps, ph, 2);
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) wcol[4 * jq + c] = (jq < ncq) ? WL[(4 * jq + c) * n + ic] : 0.0f;
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq) {
+            if (jq < ncq) {
+                float v = quad_sum4(wcol[4 * jq] * xi, wcol[4 * jq + 1] * xi, wcol[4 * jq + 2] * xi, wcol[4 * jq + 3] * xi);
+                v = rows_sum(v);   // lanes 0 .. 3 hold the wavefront's sums of classes 4 jq .. 4 jq + 3
+                if (lane < 4) part[(4 * jq + lane) * kWaves + wave] = v;
+            }
+        }
+    } else {
         // thread i gathers x_{L-1}[i] (and i + 512, ...): the partial sums in index order
-        const int P = uniform(pl[PL_PF]);
-        const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
-        const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
-        for (int w = 0; w < net.fwd_delay; ++w) __builtin_amdgcn_s_sleep(1);
         for (int i0 = 0; i0 < n; i0 += kThreads) {
             const int i = i0 + (int)threadIdx.x;
             const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok);
             if (i < n) xtop[i] = act_fast(a);
         }
-    }
-    DBSN_PROF_SUB(ps, ph, 2);
-    // products per class, four classes at a time; a thread folds its columns i, i + 512, ... together
-    for (int jq = 0; jq < ncq; ++jq) {
-        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-        const float* w = WL + 4 * jq * n;
-        for (int i = threadIdx.x; i < n; i += kThreads) {
-            const float xi = xtop[i];   // this thread's own write
-            a0 = fmaf(w[i], xi, a0);
-            a1 = fmaf(w[n + i], xi, a1);
-            a2 = fmaf(w[2 * n + i], xi, a2);
-            a3 = fmaf(w[3 * n + i], xi, a3);
+        DBSN_PROF_SUB(ps, ph, 2);
+        // products per class, four classes at a time; a thread folds its columns i, i + 512, ... together
+        for (int jq = 0; jq < ncq; ++jq) {
+            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+            const float* w = WL + 4 * jq * n;
+            for (int i = threadIdx.x; i < n; i += kThreads) {
+                const float xv = xtop[i];   // this thread's own write
+                a0 = fmaf(w[i], xv, a0);
+                a1 = fmaf(w[n + i], xv, a1);
+                a2 = fmaf(w[2 * n + i], xv, a2);
+                a3 = fmaf(w[3 * n + i], xv, a3);
+            }
+            float v = quad_sum4(a0, a1, a2, a3);
+            v = rows_sum(v);
+            if (lane < 4) part[(4 * jq + lane) * kWaves + wave] = v;
         }
-        const float v = quad_sum4(a0, a1, a2, a3);
-        if ((lane & 12) == 0) part[(4 * jq + (lane & 3)) * 33 + wave * 4 + (lane >> 4)] = v;
     }
     DBSN_PROF_SUB(ps, ph, 3);
     if (!all_ok(ok, net.err, lds)) return false;
     DBSN_PROF_SUB(ps, ph, 4);
     if (wave == 0) {
-        // class c = lane: logit (32 partial sums added pairwise in a fixed tree), softmax
+        // class c = lane: logit (the eight wavefronts' sums added pairwise in a fixed tree), softmax
         float a = -3.0e38f;
         if (lane < nc) {
-            float v[32];
-#pragma unroll
-            for (int r = 0; r < 32; ++r) v[r] = part[lane * 33 + r];
-#pragma unroll
-            for (int w = 16; w >= 1; w >>= 1)
-#pragma unroll
-                for (int r = 0; r < w; ++r) v[r] = v[2 * r] + v[2 * r + 1];
-            a = v[0] + bL[lane];
+            const float4 p0 = *reinterpret_cast<const float4*>(part + lane * kWaves);
+            const float4 p1 = *reinterpret_cast<const float4*>(part + lane * kWaves + 4);
+            a = ((p0.x + p0.y) + (p0.z + p0.w)) + ((p1.x + p1.y) + (p1.z + p1.w)) + bL[lane];
         }
         float m = a;
         m = fmaxf(m, dpp_mov<kDppXor1>(m));
@@ -794,7 +779,7 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         ssum += dpp_mov<kDppRor8>(ssum);
         if (nc > 16) ssum = rows_sum(ssum);
         else ssum = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ssum)));
-        const float p = e / ssum;
+        const float p = __fdividef(e, ssum);
         // classes nc .. 4 ncq - 1 are padding: zero delta keeps their zero weights zero
         dL[lane] = (lane < nc) ? p - (lane == label ? 1.0f : 0.0f) : 0.0f;
         dL[kMaxClasses + lane] = p;
@@ -803,32 +788,55 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     lds_barrier();
     DBSN_PROF_SUB(ps, ph, 6);
     if (g == 0 && wave == kWaves - 1) {
-        // results for the host: the loss of every step; after the last step also the probabilities,
-        // the output deltas and x_{L-1}
+        // results for the host: the loss of every step; after the last step also the probabilities
+        // and the output deltas
         if (lane == 0 && loss_out) *loss_out = -logf(dL[kMaxClasses + label]);
-        if (last) {
-            if (lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
-            for (int i = lane; i < n; i += 64) net.lay[L - 1].x[i] = xtop[i];
-        }
+        if (last && lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
     }
     // deltas of layer L-1 and update of the private W_L
-    for (int i = threadIdx.x; i < n; i += kThreads) {
-        const float xi = xtop[i];
+    if (small) {
+        const int i = (int)threadIdx.x, ic = min(i, n - 1);
+        float4 d4[4];
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq)
+            d4[jq] = (jq < ncq) ? *reinterpret_cast<const float4*>(dL + 4 * jq) : make_float4(0.f, 0.f, 0.f, 0.f);
         float gs = 0.0f;
-        for (int jq = 0; jq < ncq; ++jq) {
-            float* w = WL + 4 * jq * n + i;
-            const float4 d4 = *reinterpret_cast<const float4*>(dL + 4 * jq);
-            const float w0 = w[0], w1 = w[n], w2 = w[2 * n], w3 = w[3 * n];
-            gs = fmaf(w0, d4.x, gs);
-            gs = fmaf(w1, d4.y, gs);
-            gs = fmaf(w2, d4.z, gs);
-            gs = fmaf(w3, d4.w, gs);
-            w[0] = fmaf(-(eta * d4.x), xi, w0);
-            w[n] = fmaf(-(eta * d4.y), xi, w1);
-            w[2 * n] = fmaf(-(eta * d4.z), xi, w2);
-            w[3 * n] = fmaf(-(eta * d4.w), xi, w3);
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq) {
+            if (jq < ncq) {
+                const float dd[4] = {d4[jq].x, d4[jq].y, d4[jq].z, d4[jq].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float w0 = wcol[4 * jq + c];
+                    gs = fmaf(w0, dd[c], gs);
+                    if (i < n) WL[(4 * jq + c) * n + ic] = fmaf(-(eta * dd[c]), xi, w0);
+                }
+            }
         }
-        dtop[i] = gs * dact_from_y(xi);
+        if (i < n) {
+            dtop[i] = gs * dact_from_y(xi);
+            if (last && g == 0) net.lay[L - 1].x[i] = xi;   // x_{L-1} for the host
+        }
+    } else {
+        for (int i = threadIdx.x; i < n; i += kThreads) {
+            const float xv = xtop[i];
+            float gs = 0.0f;
+            for (int jq = 0; jq < ncq; ++jq) {
+                float* w = WL + 4 * jq * n + i;
+                const float4 d4 = *reinterpret_cast<const float4*>(dL + 4 * jq);
+                const float w0 = w[0], w1 = w[n], w2 = w[2 * n], w3 = w[3 * n];
+                gs = fmaf(w0, d4.x, gs);
+                gs = fmaf(w1, d4.y, gs);
+                gs = fmaf(w2, d4.z, gs);
+                gs = fmaf(w3, d4.w, gs);
+                w[0] = fmaf(-(eta * d4.x), xv, w0);
+                w[n] = fmaf(-(eta * d4.y), xv, w1);
+                w[2 * n] = fmaf(-(eta * d4.z), xv, w2);
+                w[3 * n] = fmaf(-(eta * d4.w), xv, w3);
+            }
+            dtop[i] = gs * dact_from_y(xv);
+            if (last && g == 0) net.lay[L - 1].x[i] = xv;
+        }
     }
     if (threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
     lds_barrier();
