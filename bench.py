@@ -4,7 +4,8 @@
 Workload (benchmark configs[3], the configuration the target is quoted on): the
 784-2500-2000-1500-1000-500-10 net (11,972,510 fp32 weights), a 60,000-sample synthetic
 stroke-image epoch, every image elastically + affinely deformed on the GPU right before it is
-trained on, eta = 1e-3, plus a forward-only classify pass over 10,000 undeformed images.
+trained on, eta = 1e-3, plus a forward-only classify pass over 10,000 undeformed images (reported
+separately under "classify"; `value` is the training rate).
 
 A "step" is one pass of the whole hot path over one chunk of `--chunk` samples:
 dbsn_deform_batch(chunk) followed by dbsn_bp_steps(chunk) (strictly sequential batch-size-1
@@ -166,7 +167,12 @@ def main():
         t1 = time.perf_counter()
         pred = m.classify(tx)
         torch.cuda.synchronize()
-        out["classify"] = {"samples": 10000, "samples_per_s": 10000 / (time.perf_counter() - t1),
+        ct = time.perf_counter() - t1
+        # the batched forward pass is a dense contraction on the fp32 matrix cores: 2 flop per weight per sample
+        tflops = 2.0 * nw * 10000 / ct / 1e12
+        out["classify"] = {"samples": 10000, "samples_per_s": 10000 / ct,
+                           "roofline": {"bound": "mfma", "achieved": tflops, "peak": 157.3, "unit": "TFLOP/s",
+                                        "frac": tflops / 157.3, "kernel": "k_layer_batch (fp32 MFMA)"},
                            "label_histogram": torch.bincount(pred.long(), minlength=10).tolist()}
 
     # deformation alone

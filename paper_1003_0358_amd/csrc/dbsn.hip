@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -15,6 +16,7 @@
 
 #include "dbsn_deform_kernels.h"
 #include "dbsn_mlp_kernels.h"
+#include "dbsn_batch_kernels.h"
 #include "dbsn_persistent_kernel.h"
 
 using namespace dbsn;
@@ -53,8 +55,8 @@ bool shape_ok(const int32_t* sizes, int32_t n_sizes) {
 struct ArenaPlan {
     size_t W[kMaxLayers + 1], b[kMaxLayers + 1], x[kMaxLayers + 1], d[kMaxLayers + 1];
     size_t yp[kMaxLayers + 1], gp[kMaxLayers + 1];
-    size_t gpart[2], flags, total;
-    int ld[kMaxLayers + 1], gld;
+    size_t gpart[2], flags, act[2], total;
+    int ld[kMaxLayers + 1], gld, ldact;
     // tile geometry of the persistent kernel (hidden layers 1 .. L-1), fixed for kPGroups workgroups
     int nCB[kMaxLayers + 1], nRB[kMaxLayers + 1], C[kMaxLayers + 1], R[kMaxLayers + 1];
     int g0[kMaxLayers + 1], ng[kMaxLayers + 1];   // register groups of each layer's tile
@@ -80,6 +82,15 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         off = align_up(off + sizeof(float) * (size_t)kArenaGroups * p.gld);
     }
     p.flags = off; off = align_up(off + 256);
+    // activations of a batch of samples for the forward-only classification passes, two buffers
+    // that the layers use in turn
+    int maxo = 0;
+    for (int l = 1; l < n_sizes; ++l) maxo = sizes[l] > maxo ? sizes[l] : maxo;
+    p.ldact = (maxo + 3) / 4 * 4;
+    for (int k = 0; k < 2; ++k) {
+        p.act[k] = off;
+        off = align_up(off + sizeof(float) * (size_t)kBatchSamples * p.ldact);
+    }
 
     // Persistent kernel: layer l is cut into nRB x nCB tiles of R rows x C <= 256 columns, one per
     // workgroup; yp_l holds the forward partial sums [2][nCB][n_l], gp_l the backward ones
@@ -472,9 +483,29 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     if (n == 0) return DBSN_OK;
     if (!samples_dev || !labels_out_dev) return fail(DBSN_E_ARG, "null pointer");
     if (!aligned(samples_dev, 4) || !aligned(labels_out_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
-    for (int64_t s = 0; s < n; ++s) {
-        int32_t rc = forward_launches(m, samples_dev + s * m->sizes[0], labels_out_dev + s);
-        if (rc) return rc;
+    // batches of kBatchSamples samples go through the layers together, one launch per layer
+    const int L = m->net.L, n0 = m->sizes[0], ldact = m->plan.ldact;
+    float* act[2] = {reinterpret_cast<float*>(m->arena + m->plan.act[0]),
+                     reinterpret_cast<float*>(m->arena + m->plan.act[1])};
+    for (int64_t at = 0; at < n; at += kBatchSamples) {
+        const int S = (int)std::min<int64_t>(kBatchSamples, n - at);
+        const float* X = samples_dev + at * n0;
+        int ldx = n0;
+        for (int l = 1; l <= L; ++l) {
+            const Layer& Ly = m->net.lay[l];
+            float* Y = act[l & 1];
+            const dim3 grid((Ly.n_out + kBatchTile - 1) / kBatchTile, (S + kBatchTile - 1) / kBatchTile);
+            if (l < L)
+                hipLaunchKernelGGL(k_layer_batch<true>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W, Ly.ld,
+                                   Ly.b, Ly.n_in, Ly.n_out, Y, ldact);
+            else
+                hipLaunchKernelGGL(k_layer_batch<false>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W, Ly.ld,
+                                   Ly.b, Ly.n_in, Ly.n_out, Y, ldact);
+            X = Y;
+            ldx = ldact;
+        }
+        hipLaunchKernelGGL(k_argmax_batch, dim3((S + 255) / 256), dim3(256), 0, m->stream, X, ldact, S,
+                           m->net.lay[L].n_out, labels_out_dev + at);
     }
     HIP_TRY(hipGetLastError());
     return DBSN_OK;

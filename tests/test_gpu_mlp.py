@@ -190,6 +190,65 @@ def test_forward_and_classify(oracle):
     m.close()
 
 
+def _margins(oracle, sizes, p, X):
+    nc = sizes[-1]
+    out = []
+    for s in range(len(X)):
+        acts, _ = oracle.forward(sizes, p, X[s], "f64")
+        top2 = np.sort(acts[-nc:])[-2:]
+        out.append(top2[1] - top2[0])
+    return np.array(out)
+
+
+def test_classify_batches_ragged_shapes(oracle):
+    """The batched forward pass: widths that are no multiple of the 64 x 64 tiles or of the k-chunk,
+    more samples than one pass takes (2048) plus a ragged tail, against the oracle and against the
+    one-sample forward call."""
+    torch = _torch()
+    sizes = [37, 70, 33, 7]
+    n = 2100
+    rng = np.random.default_rng(5)
+    X = rng.uniform(-1, 1, (n, sizes[0])).astype(np.float32)
+    m = _mk(sizes, 1, seed=2)
+    # weights large enough for the classes to differ clearly
+    for l in range(1, 4):
+        W = rng.normal(0, 0.5, (sizes[l], sizes[l - 1])).astype(np.float32)
+        b = rng.normal(0, 0.5, sizes[l]).astype(np.float32)
+        m.set_weights(l, W, b)
+    p = m.get_params()
+    xs = torch.from_numpy(X).cuda()
+    got = m.classify(xs).cpu().numpy()
+    ref = oracle.classify(sizes, p, X, "f64")
+    clear = _margins(oracle, sizes, p, X[:400]) > 1e-4
+    assert clear.sum() >= 390
+    assert np.array_equal(got[:400][clear], ref[:400][clear])
+    assert (got != ref).sum() <= 2            # the rest: only decisions within rounding may differ
+    assert len(np.unique(got)) >= 5
+    for s in (0, 63, 64, 2047, 2048, 2099):   # tile and pass boundaries
+        probs = m.forward(xs[s]).cpu().numpy()
+        assert int(np.argmax(probs)) == int(got[s]) or np.sort(probs)[-1] - np.sort(probs)[-2] < 1e-5
+    assert m.classify(xs[:1]).cpu().tolist() == [int(got[0])]
+    m.close()
+
+
+def test_classify_full_size_net(oracle):
+    torch = _torch()
+    img, _ = datagen.stroke_images(200, seed=21)
+    X = datagen.to_inputs(img)
+    m = _mk(NET4, 1, seed=4)
+    Xt, yt = _data(30, seed=22)
+    m.bp_steps(torch.from_numpy(Xt).cuda(), torch.from_numpy(yt).cuda(), 1e-2)
+    p = m.get_params()
+    got = m.classify(torch.from_numpy(X).cuda()).cpu().numpy()
+    oracle.set_threads(8)
+    ref = oracle.classify(NET4, p, X, "f64")
+    clear = _margins(oracle, NET4, p, X) > 1e-4
+    oracle.set_threads(1)
+    assert clear.sum() >= 190
+    assert np.array_equal(got[clear], ref[clear])
+    m.close()
+
+
 def test_set_get_weights_roundtrip_and_errors():
     from paper_1003_0358_amd import binding
     torch = _torch()
