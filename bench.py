@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--mode", type=int, default=1, help="0: one launch per phase, 1: persistent kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-classify", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one plain elementwise kernel that reads 256 MiB and writes 256 MiB, as the "
+                         "known-size reference for scaling FETCH_SIZE / WRITE_SIZE counter readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (on-line back-propagation is strictly sequential over "
@@ -185,6 +188,15 @@ def main():
     torch.cuda.synchronize()
     out["deform_batch_images_per_s"] = n_train / (time.perf_counter() - t1)
     del big
+
+    if args.traffic_probe:
+        a = torch.ones(64 * 2 ** 20, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.mul(a, 2.0, out=b)   # one elementwise kernel: 256 MiB read, 256 MiB written
+        torch.cuda.synchronize()
+        out["traffic_probe"] = {"kernel": "torch elementwise mul", "read_bytes": a.numel() * 4, "write_bytes": b.numel() * 4}
+        del a, b
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sizes, img, lab, eta)

@@ -21,7 +21,10 @@ SHAPES = [
     NET0,
     [30, 17, 9, 5],                  # widths that are no multiple of 4
     [784, 1000, 1000, 1000, 1000, 10],
-    [1030, 2051, 520, 33],           # ragged, several column chunks with a tail
+    [1030, 2051, 520, 33],           # ragged, several column chunks with a tail; 33 classes
+    [784] + [300] * 9 + [10],        # nine hidden layers: register groups packed at run time
+    [3000, 3000, 3000, 500, 10],     # tiles that do not all fit in registers: the streaming variant
+    [784, 300, 700, 10],             # more than 512 inputs to the output layer: several columns per thread
 ]
 
 
@@ -86,7 +89,8 @@ def test_single_step(oracle, sizes, mode):
     m.close()
 
 
-@pytest.mark.parametrize("sizes", [NET0, [784, 1000, 1000, 1000, 1000, 10], [30, 17, 9, 5]])
+@pytest.mark.parametrize("sizes", [NET0, [784, 1000, 1000, 1000, 1000, 10], [30, 17, 9, 5],
+                                   [784] + [300] * 9 + [10], [784, 300, 700, 10]])
 def test_hundred_steps(oracle, sizes):
     torch = _torch()
     X, y = _data(100, sizes[0], seed=0)
