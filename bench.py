@@ -24,6 +24,12 @@ if ROOT not in sys.path:
 
 NET4 = [784, 2500, 2000, 1500, 1000, 500, 10]
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+# Memory-side traffic of one persistent-kernel launch (1000 samples) on this workload, in bytes:
+# FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs of this script, each scaled by what the same
+# counter reads for a plain kernel of known size (--traffic-probe).  Counters cannot be read from
+# inside the process, so the figure is the one recorded in profiles/k_bp_dataflow_net4_pmc.txt
+# (commands there); it applies to the default chunk of 1000 samples in persistent mode only.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1.824e10
 
 
 def n_weights(sizes):
@@ -151,7 +157,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (args.mode == 1 and chunk == 1000) else None,
             "kernel": "k_bp_dataflow" if args.mode == 1 else "k_fwd/k_bwd/k_top",
             "algorithmic_bytes_per_launch": bytes_per_launch,
             "avg_launch_ms": bp_avg_s * 1e3,
