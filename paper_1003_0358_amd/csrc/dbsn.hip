@@ -317,8 +317,10 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     pn.err = m->err;
     pn.spin_limit = 1u << 22;
     pn.stationary = plan.stationary ? 1 : 0;
-    pn.fwd_delay = 16;
-    if (const char* e = getenv("DBSN_FWD_DELAY")) pn.fwd_delay = atoi(e) < 0 ? 0 : (atoi(e) > 64 ? 64 : atoi(e));
+    pn.fwd_delay = 12;
+    pn.adapt = 0;
+    if (const char* e = getenv("DBSN_ADAPT")) pn.adapt = atoi(e) != 0;
+    if (const char* e = getenv("DBSN_FWD_DELAY")) pn.fwd_delay = atoi(e) < 0 ? 0 : (atoi(e) > 48 ? 48 : atoi(e));
     if (const char* e = getenv("DBSN_STATIONARY")) pn.stationary = (atoi(e) != 0 && plan.stationary) ? 1 : 0;
     // a compile-time register layout when the net is stationary and fits it
     m->layout = 0;

@@ -119,7 +119,8 @@ struct PNet {
     int L;
     unsigned spin_limit;
     int stationary;   // 1: every layer has its own register groups for the whole launch
-    int fwd_delay;    // pause before the first look at forward partials, in units of 64 clocks
+    int fwd_delay;    // first guess of the pause before looking at forward partials, in units of 64 clocks
+    int adapt;        // 1: every wavefront tunes its pauses while it runs (see pace_begin)
 };
 
 // Per-layer table of this workgroup (32-bit words in LDS), filled once per launch.
@@ -159,7 +160,8 @@ struct PLds {
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
     static constexpr int plan = dtop + kTopXMax;                  // [kMaxLayers + 1][kPlanInts]
     static constexpr int fail = plan + (kMaxLayers + 1) * kPlanInts;   // [1] set when a wait gave up
-    static constexpr int total = fail + 16;
+    static constexpr int pace = fail + 16;                        // [kWaves][2][kMaxLayers + 1] pauses before polling
+    static constexpr int total = pace + kWaves * 2 * (kMaxLayers + 1);
 };
 static_assert((PLds::total + kProfLdsFloats) * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
 static_assert(kMaxClasses * kWaves <= kWaves * 264, "partial logits do not fit");
@@ -248,7 +250,7 @@ __device__ inline float pair_sum2(float a0, float a1) {
 // sum, which adds the payloads in index order.
 template <int N>
 __device__ __forceinline__ float poll_sum_n(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
-                                            unsigned limit, bool& ok, float s) {
+                                            unsigned limit, bool& ok, float s, unsigned& rereads) {
     u64 v[N];
     unsigned spins = 0;
     for (;;) {
@@ -263,22 +265,46 @@ __device__ __forceinline__ float poll_sum_n(const u64* base, unsigned col, int P
         if (!__any(pending && DBSN_WAITING(limit))) break;
         if (++spins > limit) { ok = false; break; }
     }
+    rereads += spins;
 #pragma unroll
     for (int k = 0; k < N; ++k) s += (k < P) ? __uint_as_float((unsigned)v[k]) : 0.0f;
     return s;
 }
-// (more than 12 partials take batches of 8 one after the other)
+// (more than 12 partials take batches of 8 one after the other); rereads counts the batches that
+// had to be read again
 __device__ __forceinline__ float poll_sum(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
-                                          unsigned limit, bool& ok) {
+                                          unsigned limit, bool& ok, unsigned& rereads) {
     float s = 0.0f;
     while (P > 12 && ok) {
-        s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, s);
+        s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, s, rereads);
         base += (size_t)(8u * stride);
         P -= 8;
     }
-    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, s);
-    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, s);
-    return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, s);
+    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, s, rereads);
+    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, s, rereads);
+    return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, s, rereads);
+}
+
+// Pacing of the polls.  A batch of loads that comes back without the data costs a full round trip
+// before the next one can be judged, so it pays to look a little later and find the data at the
+// first look.  How much later depends on the layer, the direction and the machine, so every
+// wavefront keeps one pause per (direction, layer) in LDS, in units of 64 clocks, and tunes it as
+// it goes: two units more after a wait that had to read again, one unit less after every eighth
+// step that did not.  Results do not depend on it.
+constexpr int kPaceMax = 48;
+__device__ __forceinline__ int pace_begin(const float* lds, int dir, int l) {
+    const int* tab = reinterpret_cast<const int*>(lds + PLds::pace);
+    const int d = uniform(tab[((threadIdx.x >> 6) * 2 + dir) * (kMaxLayers + 1) + l]);
+    for (int w = 0; w < d; ++w) __builtin_amdgcn_s_sleep(1);
+    return d;
+}
+__device__ __forceinline__ void pace_end(float* lds, int dir, int l, int d, unsigned rereads, unsigned tag, int adapt) {
+    if (!adapt) return;
+    int* tab = reinterpret_cast<int*>(lds + PLds::pace);
+    int nd = d;
+    if (rereads != 0) nd = min(d + 2, kPaceMax);
+    else if ((tag & 7u) == 0u && d > 0) nd = d - 1;
+    if (nd != d && (threadIdx.x & 63) == 0) tab[((threadIdx.x >> 6) * 2 + dir) * (kMaxLayers + 1) + l] = nd;
 }
 
 // y(a) = A tanh(B a) without the library routine: tanh(t) = 1 - 2 / (exp(2t) + 1) away from zero,
@@ -398,8 +424,9 @@ __device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const Til
 __device__ inline const int* plan_of(const float* lds, int l) {
     return reinterpret_cast<const int*>(lds + PLds::plan) + l * kPlanInts;
 }
-// The whole table row of layer l into registers with 128-bit LDS reads issued back to back (one
-// wait for all of them); what a phase does not use is dropped by the compiler.
+// The whole table row of layer l into scalar registers with 128-bit LDS reads issued back to back
+// (one wait for all of them); what a phase does not use is dropped by the compiler.  Kernels with
+// a compile-time layout fetch the rows once, before the step loop.
 struct PlanRow {
     int v[kPlanInts];
     __device__ __forceinline__ int operator[](int i) const { return v[i]; }
@@ -410,7 +437,8 @@ __device__ __forceinline__ PlanRow load_plan(const float* lds, int l) {
 #pragma unroll
     for (int k = 0; k < kPlanInts / 4; ++k) {
         const int4 q = src[k];
-        r.v[4 * k + 0] = q.x; r.v[4 * k + 1] = q.y; r.v[4 * k + 2] = q.z; r.v[4 * k + 3] = q.w;
+        r.v[4 * k + 0] = uniform(q.x); r.v[4 * k + 1] = uniform(q.y);
+        r.v[4 * k + 2] = uniform(q.z); r.v[4 * k + 3] = uniform(q.w);
     }
     return r;
 }
@@ -476,8 +504,7 @@ __device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
 // partial sums of the rows over the tile's columns, the bias riding on column block 0.
 template <bool ST, int POS>
 __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float x0pre,
-                                           unsigned tag, bool last, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
-    const PlanRow pl = load_plan(lds, l);
+                                           unsigned tag, bool last, float* lds, const PlanRow& pl, long long ps, int ph DBSN_PROF_ARGS) {
     const int flags = uniform(pl[PL_FLAGS]);
     if (!(flags & 1)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -501,9 +528,11 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
             const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
             const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
             const unsigned col = min(threadIdx.x, (unsigned)Ceff - 1u);
-            for (int w = 0; w < net.fwd_delay; ++w) __builtin_amdgcn_s_sleep(1);
+            const int pause = pace_begin(lds, 0, l);
             DBSN_PROF_SUB(ps, ph, 1);
-            const float a = poll_sum(base, col, P, stride, tag, net.spin_limit, ok);
+            unsigned rereads = 0;
+            const float a = poll_sum(base, col, P, stride, tag, net.spin_limit, ok, rereads);
+            pace_end(lds, 0, l, pause, rereads, tag, net.adapt);
             const float x = ((int)threadIdx.x < Ceff) ? act_fast(a) : 0.0f;
             xk[threadIdx.x] = x;
             // state read-out after the last step (dbsn_mlp_get_activations): row block 0 writes the
@@ -546,9 +575,8 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
 // the rank-1 update of the tile.
 template <bool ST, int POS>
 __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float eta,
-                                           unsigned tag, bool last, float* lds, long long ps,
+                                           unsigned tag, bool last, float* lds, const PlanRow& pl, long long ps,
                                            int ph DBSN_PROF_ARGS) {
-    const PlanRow pl = load_plan(lds, l);
     const int flags = uniform(pl[PL_FLAGS]);
     if (!(flags & 1)) return true;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -587,9 +615,13 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         const int Pw = (gP - pc + NPC - 1) / NPC;               // partials of this wavefront's class
         bool ok = true;
         float part = 0.0f;
-        if (Pw > 0 && 64 * (wave & ((1 << lgNR) - 1)) < Reff)
+        if (Pw > 0 && 64 * (wave & ((1 << lgNR) - 1)) < Reff) {
+            const int pause = pace_begin(lds, 1, l);
+            unsigned rereads = 0;
             part = poll_sum(src + (size_t)((unsigned)pc * (unsigned)Reff), (unsigned)min(j, Reff - 1), Pw,
-                            (unsigned)(NPC * Reff), tag, net.spin_limit, ok);
+                            (unsigned)(NPC * Reff), tag, net.spin_limit, ok, rereads);
+            pace_end(lds, 1, l, pause, rereads, tag, net.adapt);
+        }
         if (j < Reff) sg[pc * kMaxTileRows + j] = part;
         DBSN_PROF_SUB(ps, ph, 1);
         if (!all_ok(ok, net.err, lds)) return false;
@@ -675,6 +707,26 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     return true;
 }
 
+// Registers of the output phase when a thread owns one column of W_L and there are at most 16
+// classes (the paper's nets): the column itself, for the whole launch, and what its update needs,
+// which is applied after the backward phase that follows has published its partial sums.
+struct TopRegs {
+    float w[16];    // W_L[c][i] of this thread's column i, classes padded with zeros
+    float xi;       // x_{L-1}[i] of the step in flight
+};
+// (delta_L of the step is still in LDS, padded with zeros up to 16 classes)
+__device__ __forceinline__ void top_update(TopRegs& tr, float eta, const float* lds) {
+    const float4* dL = reinterpret_cast<const float4*>(lds + PLds::dLp);
+#pragma unroll
+    for (int jq = 0; jq < 4; ++jq) {
+        const float4 d4 = dL[jq];
+        tr.w[4 * jq + 0] = fmaf(-(eta * d4.x), tr.xi, tr.w[4 * jq + 0]);
+        tr.w[4 * jq + 1] = fmaf(-(eta * d4.y), tr.xi, tr.w[4 * jq + 1]);
+        tr.w[4 * jq + 2] = fmaf(-(eta * d4.z), tr.xi, tr.w[4 * jq + 2]);
+        tr.w[4 * jq + 3] = fmaf(-(eta * d4.w), tr.xi, tr.w[4 * jq + 3]);
+    }
+}
+
 // Output layer in every workgroup, on its private LDS copy of W_L (classes padded to a multiple of
 // four with zero rows): x_{L-1} from the partials, logits, softmax, loss, delta_L, the deltas of
 // layer L-1 and the rank-1 update of the copy.  Thread i owns column i (input neuron i) of W_L
@@ -682,10 +734,10 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
 // per class (quads -> rows of 16 lanes on the vector ALU, then 32 partial sums per class through
 // LDS); wavefront 0 does the softmax, and each thread back-propagates through and updates its columns.
 __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
-                                      bool last, float* lds, long long ps, int ph DBSN_PROF_ARGS) {
+                                      bool last, float* lds, const PlanRow& pl, TopRegs& tr, long long ps,
+                                      int ph DBSN_PROF_ARGS) {
     const int L = net.L;
     const PLayer& Ly = net.lay[L];
-    const PlanRow pl = load_plan(lds, L);
     const int n = Ly.n_in, nc = Ly.n_out, ncq = (nc + 3) >> 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
@@ -701,25 +753,22 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     const int P = uniform(pl[PL_PF]);
     const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
     const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
-    for (int w = 0; w < net.fwd_delay; ++w) __builtin_amdgcn_s_sleep(1);
+    const int pause = pace_begin(lds, 0, L);
+    unsigned rereads = 0;
     // One column per thread and at most 16 classes (the paper's nets): the column of W_L stays in
     // registers from the products to the update.  Otherwise the same steps with loops over the
     // thread's columns and the classes.
     const bool small = n <= kThreads && ncq <= 4;
-    float xi = 0.0f, wcol[16];
     if (small) {
         const int i = (int)threadIdx.x, ic = min(i, n - 1);
-        const float a = poll_sum(base, (unsigned)ic, P, stride, tag, net.spin_limit, ok);
-        xi = (i < n) ? act_fast(a) : 0.0f;
+        const float a = poll_sum(base, (unsigned)ic, P, stride, tag, net.spin_limit, ok, rereads);
+        const float xi = (i < n) ? act_fast(a) : 0.0f;
+        tr.xi = xi;
         DBSN_PROF_SUB(ps, ph, 2);
-#pragma unroll
-        for (int jq = 0; jq < 4; ++jq)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) wcol[4 * jq + c] = (jq < ncq) ? WL[(4 * jq + c) * n + ic] : 0.0f;
 #pragma unroll
         for (int jq = 0; jq < 4; ++jq) {
             if (jq < ncq) {
-                float v = quad_sum4(wcol[4 * jq] * xi, wcol[4 * jq + 1] * xi, wcol[4 * jq + 2] * xi, wcol[4 * jq + 3] * xi);
+                float v = quad_sum4(tr.w[4 * jq] * xi, tr.w[4 * jq + 1] * xi, tr.w[4 * jq + 2] * xi, tr.w[4 * jq + 3] * xi);
                 v = rows_sum(v);   // lanes 0 .. 3 hold the wavefront's sums of classes 4 jq .. 4 jq + 3
                 if (lane < 4) part[(4 * jq + lane) * kWaves + wave] = v;
             }
@@ -728,7 +777,7 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         // thread i gathers x_{L-1}[i] (and i + 512, ...): the partial sums in index order
         for (int i0 = 0; i0 < n; i0 += kThreads) {
             const int i = i0 + (int)threadIdx.x;
-            const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok);
+            const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok, rereads);
             if (i < n) xtop[i] = act_fast(a);
         }
         DBSN_PROF_SUB(ps, ph, 2);
@@ -748,6 +797,7 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
             if (lane < 4) part[(4 * jq + lane) * kWaves + wave] = v;
         }
     }
+    pace_end(lds, 0, L, pause, rereads, tag, net.adapt);
     DBSN_PROF_SUB(ps, ph, 3);
     if (!all_ok(ok, net.err, lds)) return false;
     DBSN_PROF_SUB(ps, ph, 4);
@@ -793,29 +843,23 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         if (lane == 0 && loss_out) *loss_out = -logf(dL[kMaxClasses + label]);
         if (last && lane < nc) { Ly.x[lane] = dL[kMaxClasses + lane]; Ly.d[lane] = dL[lane]; }
     }
-    // deltas of layer L-1 and update of the private W_L
+    // deltas of layer L-1 (and, with many columns per thread, the update of the private W_L)
     if (small) {
-        const int i = (int)threadIdx.x, ic = min(i, n - 1);
-        float4 d4[4];
-#pragma unroll
-        for (int jq = 0; jq < 4; ++jq)
-            d4[jq] = (jq < ncq) ? *reinterpret_cast<const float4*>(dL + 4 * jq) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int i = (int)threadIdx.x;
         float gs = 0.0f;
 #pragma unroll
         for (int jq = 0; jq < 4; ++jq) {
             if (jq < ncq) {
-                const float dd[4] = {d4[jq].x, d4[jq].y, d4[jq].z, d4[jq].w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float w0 = wcol[4 * jq + c];
-                    gs = fmaf(w0, dd[c], gs);
-                    if (i < n) WL[(4 * jq + c) * n + ic] = fmaf(-(eta * dd[c]), xi, w0);
-                }
+                const float4 d4 = *reinterpret_cast<const float4*>(dL + 4 * jq);
+                gs = fmaf(tr.w[4 * jq + 0], d4.x, gs);
+                gs = fmaf(tr.w[4 * jq + 1], d4.y, gs);
+                gs = fmaf(tr.w[4 * jq + 2], d4.z, gs);
+                gs = fmaf(tr.w[4 * jq + 3], d4.w, gs);
             }
         }
         if (i < n) {
-            dtop[i] = gs * dact_from_y(xi);
-            if (last && g == 0) net.lay[L - 1].x[i] = xi;   // x_{L-1} for the host
+            dtop[i] = gs * dact_from_y(tr.xi);
+            if (last && g == 0) net.lay[L - 1].x[i] = tr.xi;   // x_{L-1} for the host
         }
     } else {
         for (int i = threadIdx.x; i < n; i += kThreads) {
@@ -865,6 +909,8 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
+    for (int e = threadIdx.x; e < kWaves * 2 * (kMaxLayers + 1); e += kThreads)
+        reinterpret_cast<int*>(lds + PLds::pace)[e] = ((e / (kMaxLayers + 1)) & 1) ? 0 : net.fwd_delay;
     if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
 
     for (int l = 1; l < L; ++l) {
@@ -890,6 +936,19 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     float x0pre = (has1 && n > 0) ? samples[c01 + threadIdx.x] : 0.0f;
     int labpre = (labels && n > 0) ? labels[0] : label_val;
 
+    // this thread's column of the output layer, when it lives in registers (see TopRegs)
+    TopRegs tr;
+    const bool top_small = LyL.n_in <= kThreads && LyL.n_out <= 16;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        tr.w[c] = (top_small && (int)threadIdx.x < LyL.n_in && c < LyL.n_out) ? lds[PLds::WL + c * LyL.n_in + threadIdx.x] : 0.0f;
+    }
+    tr.xi = 0.0f;
+    // the table rows of the layers: fetched once here when the layout is fixed at compile time
+    const PlanRow rowL = load_plan(lds, L);
+    const PlanRow row1 = load_plan(lds, 1), row2 = load_plan(lds, LAYOUT ? min(2, L) : 1),
+                  row3 = load_plan(lds, LAYOUT ? min(3, L) : 1), row4 = load_plan(lds, LAYOUT ? min(4, L) : 1),
+                  row5 = load_plan(lds, LAYOUT ? min(5, L) : 1);
     bool alive = true;
     for (long long s = 0; s < n && alive; ++s) {
         const unsigned tag = tag_base + (unsigned)s + 1u;
@@ -901,28 +960,38 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
             if (labels) labpre = labels[s + 1];
         }
         const bool last = (s + 1 == n);
-#define DBSN_FWD(POS, l) p_fwd_tile<ST, POS>(wr, net, l, g, x0cur, tag, last, lds, s, (l) - 1 DBSN_PROF_PASS)
-#define DBSN_BWD(POS, l) p_bwd_tile<ST, POS>(wr, net, l, g, eta, tag, last, lds, s, L + (L - 1 - (l)) DBSN_PROF_PASS)
+#define DBSN_FWD(POS, l, row) p_fwd_tile<ST, POS>(wr, net, l, g, x0cur, tag, last, lds, row, s, (l) - 1 DBSN_PROF_PASS)
+#define DBSN_BWD(POS, l, row) p_bwd_tile<ST, POS>(wr, net, l, g, eta, tag, last, lds, row, s, L + (L - 1 - (l)) DBSN_PROF_PASS)
         if constexpr (LAYOUT == 0) {
-            for (int l = 1; l < L && alive; ++l) alive = DBSN_FWD(0, l);
+            for (int l = 1; l < L && alive; ++l) alive = DBSN_FWD(0, l, load_plan(lds, l));
         } else {
             static_assert(kLayoutDepth == 5, "one line per hidden layer of the layout");
-            alive = DBSN_FWD(1, 1);
-            if (L > 2 && alive) alive = DBSN_FWD(2, 2);
-            if (L > 3 && alive) alive = DBSN_FWD(3, 3);
-            if (L > 4 && alive) alive = DBSN_FWD(4, 4);
-            if (L > 5 && alive) alive = DBSN_FWD(5, 5);
+            alive = DBSN_FWD(1, 1, row1);
+            if (L > 2 && alive) alive = DBSN_FWD(2, 2, row2);
+            if (L > 3 && alive) alive = DBSN_FWD(3, 3, row3);
+            if (L > 4 && alive) alive = DBSN_FWD(4, 4, row4);
+            if (L > 5 && alive) alive = DBSN_FWD(5, 5, row5);
         }
         if (alive)
-            alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, last, lds, s, L - 1 DBSN_PROF_PASS);
+            alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, last, lds, rowL, tr, s, L - 1 DBSN_PROF_PASS);
+        // (the update of the register-held column of W_L waits until the first backward phase has
+        // published: it is nobody's input before the next step's output phase)
         if constexpr (LAYOUT == 0) {
-            for (int l = L - 1; l >= 1 && alive; --l) alive = DBSN_BWD(0, l);
+            for (int l = L - 1; l >= 1 && alive; --l) {
+                alive = DBSN_BWD(0, l, load_plan(lds, l));
+                if (l == L - 1) top_update(tr, eta, lds);
+            }
         } else {
-            if (L > 5 && alive) alive = DBSN_BWD(5, 5);
-            if (L > 4 && alive) alive = DBSN_BWD(4, 4);
-            if (L > 3 && alive) alive = DBSN_BWD(3, 3);
-            if (L > 2 && alive) alive = DBSN_BWD(2, 2);
-            if (alive) alive = DBSN_BWD(1, 1);
+            if (L > 5 && alive) alive = DBSN_BWD(5, 5, row5);
+            if (L == 6) top_update(tr, eta, lds);
+            if (L > 4 && alive) alive = DBSN_BWD(4, 4, row4);
+            if (L == 5) top_update(tr, eta, lds);
+            if (L > 3 && alive) alive = DBSN_BWD(3, 3, row3);
+            if (L == 4) top_update(tr, eta, lds);
+            if (L > 2 && alive) alive = DBSN_BWD(2, 2, row2);
+            if (L == 3) top_update(tr, eta, lds);
+            if (alive) alive = DBSN_BWD(1, 1, row1);
+            if (L == 2) top_update(tr, eta, lds);
         }
 #undef DBSN_FWD
 #undef DBSN_BWD
@@ -941,6 +1010,11 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     DBSN_PROF_FLUSH();
     if (g == 0) {
+        if (top_small && (int)threadIdx.x < LyL.n_in) {
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+                if (c < LyL.n_out) lds[PLds::WL + c * LyL.n_in + threadIdx.x] = tr.w[c];
+        }
         __syncthreads();
         for (int e = threadIdx.x; e < LyL.n_out * LyL.n_in; e += kThreads) {
             const int j = e / LyL.n_in, i = e - j * LyL.n_in;
