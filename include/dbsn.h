@@ -61,9 +61,9 @@ typedef struct {
  * 1 (default): one persistent kernel per call, whose workgroups hand partial sums to each other
  * through tagged words in device memory.  Both compute the same step; they add partial sums in
  * different (each fixed) orders, so results agree to rounding, and each mode is bit-reproducible
- * from run to run.  Shapes the persistent kernel does not hold (no hidden layer, an output layer
- * of more than 10240 weights or more than 2048 inputs, a layer whose 256 tiles would exceed 224
- * rows each) run in mode 0 whatever is selected. */
+ * from run to run.  Shapes the persistent kernel does not hold (no hidden layer; an output layer of
+ * more than 16384 weights, counting its classes rounded up to a multiple of 4, or of more than 2048
+ * inputs; a layer whose 256 tiles would exceed 224 rows each) run in mode 0 whatever is selected. */
 #define DBSN_MODE_LAUNCHES   0
 #define DBSN_MODE_PERSISTENT 1
 

@@ -95,7 +95,7 @@ constexpr int kGR = 2;               // rows per register group
 constexpr int kNG = 14;              // register groups per wavefront
 constexpr int kSlots = kGR * kNG;    // rows a wavefront holds: 28 (a tile has at most 8 * 28 = 224 rows)
 constexpr int kMaxTileRows = kSlots * kWaves;   // 224
-constexpr int kTopWMax = 10240;      // floats of W_L kept in LDS (rows padded to a multiple of four classes)
+constexpr int kTopWMax = 16384;      // floats of W_L kept in LDS (rows padded to a multiple of four classes)
 constexpr int kTopXMax = 2048;       // neurons of layer L-1 the output phase can take
 constexpr int kStageFloats = kWaves * kMaxTileRows;   // per-wavefront partial deltas of a tile's rows
 static_assert(kGR == 2, "the forward reduction pairs the two rows of a register group");
