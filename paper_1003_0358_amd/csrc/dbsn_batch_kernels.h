@@ -2,14 +2,15 @@
 // over validation and test sets (sections "Data" and "Results"; appendix "Forward propagation").
 // With many samples at once the layer is a dense contraction Y = X W^T, so unlike the on-line
 // training step it belongs on the matrix cores: fp32 MFMA (products and sums in binary32, as
-// everywhere in this library), each weight tile read from memory once per 64 samples.
+// everywhere in this library), each weight tile read from memory once per 128 samples.
 //
-// One workgroup of 4 wavefronts computes a tile of 64 samples x 64 neurons; wavefront w owns the
-// 32 x 32 block (w & 1, w >> 1) as one v_mfma_f32_32x32x2 accumulator (16 registers).  The k
+// One workgroup of 4 wavefronts computes a tile of 128 samples x 128 neurons; wavefront w owns the
+// 64 x 64 quadrant (w & 1, w >> 1) as 2 x 2 v_mfma_f32_32x32x2 accumulators (64 registers).  The k
 // dimension is walked in chunks of 32 staged in LDS (pitch 33: the operand reads, row = lane % 32,
-// k = lane / 32, fall in distinct banks).  Operand layout of the instruction: lane t supplies
-// A[i = t % 32][k = t / 32] and B[k = t / 32][j = t % 32]; result register r of lane t is
-// D[i = r % 4 + 4 (t / 32) + 8 (r / 4)][j = t % 32].
+// k = lane / 32, fall in distinct banks); the next chunk's global loads are issued before the
+// current chunk's matrix instructions and parked in registers, so memory latency hides behind the
+// arithmetic.  Operand layout of the instruction: lane t supplies A[i = t % 32][k = t / 32] and
+// B[k = t / 32][j = t % 32]; result register r of lane t is D[i = r % 4 + 4 (t / 32) + 8 (r / 4)][j = t % 32].
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -19,11 +20,12 @@
 namespace dbsn {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-constexpr int kBatchTile = 64;          // samples and neurons per workgroup tile
+constexpr int kBatchTile = 128;         // samples and neurons per workgroup tile
 constexpr int kBatchK = 32;             // k-chunk staged in LDS
 constexpr int kBatchPitch = kBatchK + 1;
 constexpr int kBatchThreads = 256;
-constexpr int kBatchSamples = 2048;     // samples per pass through the layers (sizes the activation buffers)
+constexpr int kBatchRows = kBatchTile / 8;   // rows of each operand tile a thread stages per chunk
+constexpr int kBatchSamples = 8192;     // samples per pass through the layers (sizes the activation buffers)
 
 // Y[s][j] = f(b[j] + sum_i W[j][i] X[s][i]) for s < S, j < n_out; f = scaled tanh (ACT) or identity
 // (the output layer's pre-activations, whose largest entry is the class).  X: [S][ldx], W: [n_out][ldw],
@@ -37,38 +39,65 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
     __shared__ float Ws[kBatchTile * kBatchPitch];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s0 = blockIdx.y * kBatchTile, j0 = blockIdx.x * kBatchTile;
-    const int sw = (wave & 1) * 32, jw = (wave >> 1) * 32;
-    floatx16 acc;
+    const int sw = (wave & 1) * 64, jw = (wave >> 1) * 64;
+    floatx16 acc[2][2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
     const int tk = threadIdx.x & 31, tr = threadIdx.x >> 5;   // staging: column tk, rows tr, tr + 8, ...
-    for (int k0 = 0; k0 < n_in; k0 += kBatchK) {
+    float xr[kBatchRows], wrg[kBatchRows];
+    auto fetch = [&](int k0) {
         const int k = k0 + tk;
 #pragma unroll
-        for (int r = 0; r < kBatchTile / 8; ++r) {
+        for (int r = 0; r < kBatchRows; ++r) {
             const int row = tr + 8 * r;
             const int s = s0 + row, j = j0 + row;
-            Xs[row * kBatchPitch + tk] = (s < S && k < n_in) ? X[(size_t)s * ldx + k] : 0.0f;
-            Ws[row * kBatchPitch + tk] = (j < n_out && k < n_in) ? W[(size_t)j * ldw + k] : 0.0f;
+            xr[r] = (s < S && k < n_in) ? X[(size_t)s * ldx + k] : 0.0f;
+            wrg[r] = (j < n_out && k < n_in) ? W[(size_t)j * ldw + k] : 0.0f;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < n_in; k0 += kBatchK) {
+#pragma unroll
+        for (int r = 0; r < kBatchRows; ++r) {
+            const int row = tr + 8 * r;
+            Xs[row * kBatchPitch + tk] = xr[r];
+            Ws[row * kBatchPitch + tk] = wrg[r];
         }
         __syncthreads();
+        if (k0 + kBatchK < n_in) fetch(k0 + kBatchK);   // in flight during the matrix instructions below
 #pragma unroll
         for (int kk = 0; kk < kBatchK; kk += 2) {
-            const float a = Xs[(sw + (lane & 31)) * kBatchPitch + kk + (lane >> 5)];
-            const float w = Ws[(jw + (lane & 31)) * kBatchPitch + kk + (lane >> 5)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, w, acc, 0, 0, 0);
+            const int kc = kk + (lane >> 5);
+            const float a0 = Xs[(sw + (lane & 31)) * kBatchPitch + kc];
+            const float a1 = Xs[(sw + 32 + (lane & 31)) * kBatchPitch + kc];
+            const float w0 = Ws[(jw + (lane & 31)) * kBatchPitch + kc];
+            const float w1 = Ws[(jw + 32 + (lane & 31)) * kBatchPitch + kc];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, w0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, w1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, w0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, w1, acc[1][1], 0, 0, 0);
         }
         __syncthreads();
     }
-    const int j = j0 + jw + (lane & 31);
-    if (j < n_out) {
-        const float bj = b[j];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int s = s0 + sw + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
-            if (s < S) {
-                const float v = acc[r] + bj;
-                Y[(size_t)s * ldy + j] = ACT ? act(v) : v;
+    for (int c = 0; c < 2; ++c) {
+        const int j = j0 + jw + 32 * c + (lane & 31);
+        if (j < n_out) {
+            const float bj = b[j];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int s = s0 + sw + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
+                    if (s < S) {
+                        const float v = acc[a][c][r] + bj;
+                        Y[(size_t)s * ldy + j] = ACT ? act(v) : v;
+                    }
+                }
             }
         }
     }

@@ -205,12 +205,12 @@ def _margins(oracle, sizes, p, X):
 
 
 def test_classify_batches_ragged_shapes(oracle):
-    """The batched forward pass: widths that are no multiple of the 64 x 64 tiles or of the k-chunk,
-    more samples than one pass takes (2048) plus a ragged tail, against the oracle and against the
+    """The batched forward pass: widths that are no multiple of the 128 x 128 tiles or of the k-chunk,
+    more samples than one pass takes (8192) plus a ragged tail, against the oracle and against the
     one-sample forward call."""
     torch = _torch()
     sizes = [37, 70, 33, 7]
-    n = 2100
+    n = 8300
     rng = np.random.default_rng(5)
     X = rng.uniform(-1, 1, (n, sizes[0])).astype(np.float32)
     m = _mk(sizes, 1, seed=2)
@@ -228,7 +228,7 @@ def test_classify_batches_ragged_shapes(oracle):
     assert np.array_equal(got[:400][clear], ref[:400][clear])
     assert (got != ref).sum() <= 2            # the rest: only decisions within rounding may differ
     assert len(np.unique(got)) >= 5
-    for s in (0, 63, 64, 2047, 2048, 2099):   # tile and pass boundaries
+    for s in (0, 127, 128, 8191, 8192, 8299):   # tile and pass boundaries
         probs = m.forward(xs[s]).cpu().numpy()
         assert int(np.argmax(probs)) == int(got[s]) or np.sort(probs)[-1] - np.sort(probs)[-2] < 1e-5
     assert m.classify(xs[:1]).cpu().tolist() == [int(got[0])]
