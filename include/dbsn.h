@@ -46,7 +46,9 @@ typedef struct dbsn_mlp dbsn_mlp;   /* opaque host handle */
 
 /* Deformation parameters (section "Deforming images to get more training instances"):
  * sigma, alpha: Gaussian width (pixels) and scale of the elastic displacement field;
- * beta_deg: rotation angle drawn uniformly from [-beta, +beta] degrees;
+ * beta_deg: an angle is drawn uniformly from [-beta, +beta] degrees per image; it is a rotation,
+ * or, when shear != 0, a horizontal shear whose tangent is the ratio of horizontal displacement
+ * to image height;
  * gamma_pct: x and y scale factors drawn independently from [1-gamma/100, 1+gamma/100];
  * ktaps: odd number of taps of the 1-D Gaussian (the appendix uses a 21 x 21 kernel). */
 typedef struct {
@@ -55,6 +57,7 @@ typedef struct {
     float   beta_deg;
     float   gamma_pct;
     int32_t ktaps;
+    int32_t shear;
 } dbsn_deform_params;
 
 /* Execution mode of dbsn_bp_steps / dbsn_bp_step.  0: one kernel launch per layer phase;
@@ -112,12 +115,19 @@ int32_t dbsn_mlp_status(dbsn_mlp* mlp);
  * does not change the result.  Per image: rotation angle and two scale factors; two displacement
  * fields uniform in [-1,1) per pixel, each smoothed with the separable ktaps-tap Gaussian of
  * width sigma (taps sum to 1, field taken as zero outside the image) and multiplied by alpha;
- * output pixel (r,c) is the bilinear sample of the source at the rotated-and-scaled position of
- * (r,c) about the image centre plus the displacement at (r,c), pixels outside the source counting
+ * output pixel (r,c) is the bilinear sample of the source at the rotated (or sheared) and scaled
+ * position of (r,c) about the image centre plus the displacement at (r,c), pixels outside the source counting
  * as 0; the result is mapped to intensity/127.5 - 1 (section "Data").
  * src_dev: [n][784] uint8 (any alignment); dst_dev: [n][784] float.  n == 0 is a no-op. */
 int32_t dbsn_deform_batch(const dbsn_deform_params* params_host, const uint8_t* src_dev, int64_t n,
                           uint64_t seed, uint64_t first_index, float* dst_dev, void* hip_stream);
+
+/* The same with one bound of the angle per image, beta_deg_dev: [n] float (degrees, finite), which
+ * replaces params->beta_deg: the paper rotates or shears digits 1 and 7 by at most 7.5 degrees
+ * and the others by at most 15 (section "Deforming images ..."), so the bound follows the label. */
+int32_t dbsn_deform_batch_beta(const dbsn_deform_params* params_host, const uint8_t* src_dev,
+                               const float* beta_deg_dev, int64_t n, uint64_t seed, uint64_t first_index,
+                               float* dst_dev, void* hip_stream);
 
 /* n on-line back-propagation steps, strictly in order (sections "Architectures", "Training
  * algorithm"; appendix "Forward propagation", "Backward propagation", "Weight updating"): for

@@ -216,13 +216,42 @@ class Oracle:
                                                           _p(out, ct))
         return out
 
+    def linear_part(self, shear, beta_deg, s3, mode="f64"):
+        """-> (p, q, r, t): X' = p u + q v, Y' = r u + t v (rotation, or horizontal shear when `shear`)."""
+        dt, ct = self._t(mode)
+        s3 = np.ascontiguousarray(s3, dtype=np.float32)
+        out = np.empty(4, dtype=dt)
+        getattr(self.lib, "dbsn_oracle_linear_part_" + mode)(C.c_int32(int(shear)), C.c_float(beta_deg),
+                                                             _p(s3, C.c_float), _p(out, ct))
+        return out
+
+    def resample_lin(self, img, pqrt, sx, sy, dx, dy, mode="f64"):
+        dt, ct = self._t(mode)
+        img = np.ascontiguousarray(img, dtype=np.uint8)
+        H, W = img.shape
+        pqrt = np.ascontiguousarray(pqrt, dtype=dt)
+        dx = np.ascontiguousarray(dx, dtype=dt).reshape(H, W)
+        dy = np.ascontiguousarray(dy, dtype=dt).reshape(H, W)
+        out = np.empty((H, W), dtype=dt)
+        getattr(self.lib, "dbsn_oracle_resample_lin_" + mode)(_p(img, C.c_uint8), C.c_int32(H), C.c_int32(W),
+                                                              _p(pqrt, ct), ct(sx), ct(sy), _p(dx, ct), _p(dy, ct),
+                                                              _p(out, ct))
+        return out
+
     def deform_batch(self, src, seed, first_index, sigma=6.0, alpha=36.0, beta_deg=7.5, gamma_pct=15.0, ktaps=21,
-                     mode="f64"):
+                     mode="f64", shear=False, beta_each=None):
+        """beta_each: one angle bound (degrees) per image instead of beta_deg; shear: horizontal
+        shearing instead of rotation."""
         dt, ct = self._t(mode)
         src = np.ascontiguousarray(src, dtype=np.uint8).reshape(-1, 784)
         n = src.shape[0]
         out = np.empty((n, 784), dtype=dt)
+        be = None
+        if beta_each is not None:
+            be = np.ascontiguousarray(beta_each, dtype=np.float32)
+            assert be.shape == (n,)
         getattr(self.lib, "dbsn_oracle_deform_batch_" + mode)(
             C.c_float(sigma), C.c_float(alpha), C.c_float(beta_deg), C.c_float(gamma_pct), C.c_int32(ktaps),
+            C.c_int32(int(bool(shear))), _p(be, C.c_float) if be is not None else None,
             _p(src, C.c_uint8), C.c_int64(n), C.c_uint64(seed), C.c_uint64(first_index), _p(out, ct))
         return out

@@ -248,20 +248,36 @@ void affine_scalars(float beta_deg, float gamma_pct, const float* s3, T* cs, T* 
     *sy = (T)(1.0 + ((double)gamma_pct / 100.0) * (double)s3[2]);
 }
 
+/* The linear part of the inverse map, applied to (u, v) = output pixel minus centre:
+ *   X' = p u + q v,  Y' = r u + t v   (then scaled by sx, sy).
+ * Rotation by the angle: (p, q, r, t) = (cos, -sin, sin, cos).
+ * Horizontal shear (section "Deforming images ..."): the tangent of the angle is the ratio of
+ * horizontal displacement to height, so a row v above or below the centre moves by tan * v:
+ * (p, q, r, t) = (1, tan, 0, 1).  Formed in double from the same angle, rounded to T. */
+template <class T>
+void linear_part(int shear, float beta_deg, const float* s3, T* pqrt) {
+    const double th = (double)beta_deg * (double)s3[0] * (3.14159265358979323846 / 180.0);
+    if (shear) {
+        pqrt[0] = (T)1; pqrt[1] = (T)std::tan(th); pqrt[2] = (T)0; pqrt[3] = (T)1;
+    } else {
+        pqrt[0] = (T)std::cos(th); pqrt[1] = (T)(-std::sin(th)); pqrt[2] = (T)std::sin(th); pqrt[3] = (T)std::cos(th);
+    }
+}
+
 /* Inverse-map resampling: output pixel (r,c) takes the bilinear sample of the
  * source image at
- *   X = sx (cos u - sin v) + c0x + dx[r][c],   u = c - c0x, c0x = (W-1)/2
- *   Y = sy (sin u + cos v) + c0y + dy[r][c],   v = r - c0y, c0y = (H-1)/2
+ *   X = sx (p u + q v) + c0x + dx[r][c],   u = c - c0x, c0x = (W-1)/2
+ *   Y = sy (r u + t v) + c0y + dy[r][c],   v = r - c0y, c0y = (H-1)/2
  * every one of the four taps being 0 (background) when it lies outside the
  * image.  The result is mapped to intensity/127.5 - 1 (section "Data"). */
 template <class T>
-void resample(const uint8_t* img, int H, int W, T cs, T sn, T sx, T sy, const T* dx, const T* dy, T* out) {
+void resample_lin(const uint8_t* img, int H, int W, const T* pqrt, T sx, T sy, const T* dx, const T* dy, T* out) {
     const T c0x = (T)(W - 1) / 2, c0y = (T)(H - 1) / 2;
     for (int r = 0; r < H; ++r)
         for (int c = 0; c < W; ++c) {
             const T u = (T)c - c0x, v = (T)r - c0y;
-            const T X = sx * (cs * u - sn * v) + c0x + dx[r * W + c];
-            const T Y = sy * (sn * u + cs * v) + c0y + dy[r * W + c];
+            const T X = sx * (pqrt[0] * u + pqrt[1] * v) + c0x + dx[r * W + c];
+            const T Y = sy * (pqrt[2] * u + pqrt[3] * v) + c0y + dy[r * W + c];
             const T xf = std::floor(X), yf = std::floor(Y);
             const T fx = X - xf, fy = Y - yf;
             T p00 = 0, p01 = 0, p10 = 0, p11 = 0;
@@ -278,8 +294,15 @@ void resample(const uint8_t* img, int H, int W, T cs, T sn, T sx, T sy, const T*
         }
 }
 
+/* Rotation given as cosine and sine. */
 template <class T>
-void deform_one(float sigma, float alpha, float beta_deg, float gamma_pct, int ktaps, const uint8_t* img,
+void resample(const uint8_t* img, int H, int W, T cs, T sn, T sx, T sy, const T* dx, const T* dy, T* out) {
+    const T pqrt[4] = {cs, -sn, sn, cs};
+    resample_lin<T>(img, H, W, pqrt, sx, sy, dx, dy, out);
+}
+
+template <class T>
+void deform_one(float sigma, float alpha, float beta_deg, float gamma_pct, int ktaps, int shear, const uint8_t* img,
                 uint64_t seed, uint64_t index, T* out) {
     const int H = 28, W = 28, HW = H * W;
     float s3[3];
@@ -289,9 +312,10 @@ void deform_one(float sigma, float alpha, float beta_deg, float gamma_pct, int k
     for (int i = 0; i < HW; ++i) { fx[i] = (T)Dx[i]; fy[i] = (T)Dy[i]; }
     smooth_field<T>(fx.data(), H, W, (T)sigma, ktaps, (T)alpha, gx.data());
     smooth_field<T>(fy.data(), H, W, (T)sigma, ktaps, (T)alpha, gy.data());
-    T cs, sn, sx, sy;
+    T cs, sn, sx, sy, pqrt[4];
     affine_scalars<T>(beta_deg, gamma_pct, s3, &cs, &sn, &sx, &sy);
-    resample<T>(img, H, W, cs, sn, sx, sy, gx.data(), gy.data(), out);
+    linear_part<T>(shear, beta_deg, s3, pqrt);
+    resample_lin<T>(img, H, W, pqrt, sx, sy, gx.data(), gy.data(), out);
 }
 
 }  // namespace
@@ -383,13 +407,21 @@ void dbsn_oracle_init_params_f32(const int32_t* sizes, int32_t n_sizes, uint64_t
                                     const T* dy, T* out) {                                                          \
         resample<T>(img, H, W, cs, sn, sx, sy, dx, dy, out);                                                        \
     }                                                                                                               \
+    void dbsn_oracle_linear_part_##SUF(int32_t shear, float beta_deg, const float* s3, T* pqrt) {                   \
+        linear_part<T>(shear, beta_deg, s3, pqrt);                                                                  \
+    }                                                                                                               \
+    void dbsn_oracle_resample_lin_##SUF(const uint8_t* img, int32_t H, int32_t W, const T* pqrt, T sx, T sy,        \
+                                        const T* dx, const T* dy, T* out) {                                         \
+        resample_lin<T>(img, H, W, pqrt, sx, sy, dx, dy, out);                                                      \
+    }                                                                                                               \
+    /* beta_each: one angle bound per image (degrees), or NULL for beta_deg everywhere */                          \
     void dbsn_oracle_deform_batch_##SUF(float sigma, float alpha, float beta_deg, float gamma_pct, int32_t ktaps,   \
-                                        const uint8_t* src, int64_t n, uint64_t seed, uint64_t first_index,         \
-                                        T* dst) {                                                                   \
+                                        int32_t shear, const float* beta_each, const uint8_t* src, int64_t n,       \
+                                        uint64_t seed, uint64_t first_index, T* dst) {                              \
         _Pragma("omp parallel for num_threads(g_threads) if (g_threads > 1)")                                       \
         for (int64_t k = 0; k < n; ++k)                                                                             \
-            deform_one<T>(sigma, alpha, beta_deg, gamma_pct, ktaps, src + k * 784, seed, first_index + (uint64_t)k, \
-                          dst + k * 784);                                                                           \
+            deform_one<T>(sigma, alpha, beta_each ? beta_each[k] : beta_deg, gamma_pct, ktaps, shear,               \
+                          src + k * 784, seed, first_index + (uint64_t)k, dst + k * 784);                           \
     }
 
 DBSN_ORACLE_MLP(f32, float)

@@ -18,14 +18,14 @@ MODE_LAUNCHES, MODE_PERSISTENT = 0, 1
 SYMBOLS = [
     "dbsn_mlp_arena_bytes", "dbsn_mlp_init", "dbsn_mlp_free", "dbsn_mlp_set_weights", "dbsn_mlp_get_weights",
     "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
-    "dbsn_mlp_status", "dbsn_deform_batch", "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify",
+    "dbsn_mlp_status", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify",
     "dbsn_last_error",
 ]
 
 
 class DeformParams(C.Structure):
     _fields_ = [("sigma", C.c_float), ("alpha", C.c_float), ("beta_deg", C.c_float), ("gamma_pct", C.c_float),
-                ("ktaps", C.c_int32)]
+                ("ktaps", C.c_int32), ("shear", C.c_int32)]
 
 
 class DbsnError(RuntimeError):
@@ -66,6 +66,7 @@ class Lib:
         c.dbsn_mlp_set_spin_limit.argtypes = [vp, C.c_uint32]
         c.dbsn_mlp_status.argtypes = [vp]
         c.dbsn_deform_batch.argtypes = [C.POINTER(DeformParams), vp, i64, u64, u64, vp, vp]
+        c.dbsn_deform_batch_beta.argtypes = [C.POINTER(DeformParams), vp, vp, i64, u64, u64, vp, vp]
         c.dbsn_bp_steps.argtypes = [vp, vp, vp, i64, f32, vp]
         c.dbsn_bp_step.argtypes = [vp, vp, i32, f32]
         c.dbsn_forward.argtypes = [vp, vp, vp]
@@ -123,6 +124,10 @@ class Lib:
         return self.c.dbsn_deform_batch(C.byref(params) if params is not None else None, _ptr(src), n, seed,
                                         first_index, _ptr(dst), C.c_void_p(stream))
 
+    def deform_batch_beta(self, params, src, beta_deg, n, seed, first_index, dst, stream=0):
+        return self.c.dbsn_deform_batch_beta(C.byref(params) if params is not None else None, _ptr(src),
+                                             _ptr(beta_deg), n, seed, first_index, _ptr(dst), C.c_void_p(stream))
+
     def bp_steps(self, h, samples, labels, n, eta, loss=None):
         return self.c.dbsn_bp_steps(h, _ptr(samples), _ptr(labels), n, eta, _ptr(loss))
 
@@ -149,7 +154,19 @@ def load():
 
 def default_deform_params():
     """sigma 6, alpha 36, rotation +-7.5 degrees, scaling +-15 %, 21 taps (values the paper reports using)."""
-    return DeformParams(6.0, 36.0, 7.5, 15.0, 21)
+    return DeformParams(6.0, 36.0, 7.5, 15.0, 21, 0)
+
+
+def beta_for_labels(labels, similar=(1, 7), beta_similar=7.5, beta_other=15.0):
+    """Per-image bound of the rotation / shear angle from the class labels: the paper deforms the
+    look-alike digits 1 and 7 less (7.5 degrees) than the others (15 degrees).  labels: integer
+    device tensor [n] -> float32 device tensor [n]."""
+    import torch
+    hit = torch.zeros_like(labels, dtype=torch.bool)
+    for k in similar:
+        hit |= labels == k
+    return torch.where(hit, torch.tensor(beta_similar, device=labels.device),
+                       torch.tensor(beta_other, device=labels.device)).to(torch.float32).contiguous()
 
 
 class Mlp:
@@ -243,8 +260,9 @@ class Mlp:
         return out
 
 
-def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None):
-    """src_u8: uint8 device tensor [n, 784] -> float32 device tensor [n, 784]."""
+def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None, beta_deg=None):
+    """src_u8: uint8 device tensor [n, 784] -> float32 device tensor [n, 784].  beta_deg: optional
+    float32 device tensor [n], one bound of the angle per image instead of params.beta_deg."""
     import torch
     lib = load()
     n = src_u8.shape[0]
@@ -252,5 +270,10 @@ def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None):
         out = torch.empty((n, 784), dtype=torch.float32, device=src_u8.device)
     if stream is None:
         stream = torch.cuda.current_stream(src_u8.device).cuda_stream
-    lib.check(lib.deform_batch(params or default_deform_params(), src_u8, n, seed, first_index, out, stream))
+    params = params or default_deform_params()
+    if beta_deg is None:
+        lib.check(lib.deform_batch(params, src_u8, n, seed, first_index, out, stream))
+    else:
+        assert beta_deg.dtype == torch.float32 and beta_deg.numel() == n and beta_deg.is_contiguous()
+        lib.check(lib.deform_batch_beta(params, src_u8, beta_deg, n, seed, first_index, out, stream))
     return out

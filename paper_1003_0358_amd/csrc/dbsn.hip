@@ -513,8 +513,8 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     return DBSN_OK;
 }
 
-int32_t dbsn_deform_batch(const dbsn_deform_params* p, const uint8_t* src_dev, int64_t n, uint64_t seed,
-                          uint64_t first_index, float* dst_dev, void* hip_stream) {
+int32_t dbsn_deform_batch_beta(const dbsn_deform_params* p, const uint8_t* src_dev, const float* beta_deg_dev,
+                               int64_t n, uint64_t seed, uint64_t first_index, float* dst_dev, void* hip_stream) {
     if (!p) return fail(DBSN_E_ARG, "params is null");
     if (n < 0) return fail(DBSN_E_ARG, "n is negative");
     if (p->ktaps < 1 || p->ktaps > DBSN_MAX_KTAPS || (p->ktaps & 1) == 0)
@@ -522,9 +522,10 @@ int32_t dbsn_deform_batch(const dbsn_deform_params* p, const uint8_t* src_dev, i
     if (!(p->sigma >= 0.0f) || !std::isfinite(p->sigma) || !std::isfinite(p->alpha) || !std::isfinite(p->beta_deg) ||
         !std::isfinite(p->gamma_pct))
         return fail(DBSN_E_ARG, "deformation parameters must be finite, sigma >= 0");
+    if (p->shear != 0 && p->shear != 1) return fail(DBSN_E_ARG, "shear must be 0 or 1");
     if (n == 0) return DBSN_OK;
     if (!src_dev || !dst_dev) return fail(DBSN_E_ARG, "null pointer");
-    if (!aligned(dst_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    if (!aligned(dst_dev, 4) || !aligned(beta_deg_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
 
     DeformArgs a{};
     // 1-D Gaussian exp(-t^2 / (2 sigma^2)), t = -R..R, scaled to sum 1 (sigma 0: unit impulse)
@@ -540,6 +541,8 @@ int32_t dbsn_deform_batch(const dbsn_deform_params* p, const uint8_t* src_dev, i
     a.alpha = p->alpha;
     a.beta_deg = p->beta_deg;
     a.gamma_pct = p->gamma_pct;
+    a.shear = p->shear;
+    a.beta_each = beta_deg_dev;
     a.seed = seed;
     a.first_index = first_index;
     a.n = n;
@@ -548,6 +551,11 @@ int32_t dbsn_deform_batch(const dbsn_deform_params* p, const uint8_t* src_dev, i
                        src_dev, dst_dev);
     HIP_TRY(hipGetLastError());
     return DBSN_OK;
+}
+
+int32_t dbsn_deform_batch(const dbsn_deform_params* p, const uint8_t* src_dev, int64_t n, uint64_t seed,
+                          uint64_t first_index, float* dst_dev, void* hip_stream) {
+    return dbsn_deform_batch_beta(p, src_dev, nullptr, n, seed, first_index, dst_dev, hip_stream);
 }
 
 }  // extern "C"

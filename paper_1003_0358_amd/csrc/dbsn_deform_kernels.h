@@ -3,8 +3,8 @@
 //
 // One workgroup of 256 threads deforms one 28x28 image entirely in LDS: it draws the two random
 // displacement fields, smooths them with the separable Gaussian (rows, then columns, the field
-// being zero outside the image), scales them by alpha, adds the rotated-and-scaled pixel grid
-// and takes the bilinear sample of the source image.  The paper ran only the (full 2-D, 441-tap)
+// being zero outside the image), scales them by alpha, adds the rotated (or horizontally sheared)
+// and scaled pixel grid and takes the bilinear sample of the source image.  The paper ran only the (full 2-D, 441-tap)
 // convolution on its GPU and everything else on the CPU; here nothing leaves the chip between the
 // uint8 source (784 B read) and the float result (3136 B written).
 #pragma once
@@ -24,6 +24,8 @@ struct DeformArgs {
     float taps[kMaxTaps + 1];  // 1-D Gaussian, sums to 1, taps[R] is the centre
     int ktaps;
     float alpha, beta_deg, gamma_pct;
+    int shear;                 // 0: rotation by the angle, 1: horizontal shear with tan(angle) = displacement / height
+    const float* beta_each;    // per-image bound of the angle in degrees, or null for beta_deg everywhere
     uint64_t seed, first_index;
     long long n;
 };
@@ -33,7 +35,7 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
     __shared__ float img[kPix];
     __shared__ float fx[kPix], fy[kPix];   // raw fields, later reused for nothing else
     __shared__ float tx[kPix], ty[kPix];   // after the row pass
-    __shared__ float aff[4];               // cos, sin, sx, sy
+    __shared__ float aff[6];               // linear part p, q, r, t (X' = p u + q v, Y' = r u + t v), then sx, sy
     const int R = (a.ktaps - 1) / 2;
 
     for (long long k = blockIdx.x; k < a.n; k += gridDim.x) {
@@ -49,11 +51,15 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
             const double u0 = (double)rng_unit(rng_draw(key, 0));
             const double u1 = (double)rng_unit(rng_draw(key, 1));
             const double u2 = (double)rng_unit(rng_draw(key, 2));
-            const double th = (double)a.beta_deg * u0 * (3.14159265358979323846 / 180.0);
-            aff[0] = (float)cos(th);
-            aff[1] = (float)sin(th);
-            aff[2] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
-            aff[3] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
+            const double beta = a.beta_each ? (double)a.beta_each[k] : (double)a.beta_deg;
+            const double th = beta * u0 * (3.14159265358979323846 / 180.0);
+            if (a.shear) {
+                aff[0] = 1.0f; aff[1] = (float)tan(th); aff[2] = 0.0f; aff[3] = 1.0f;
+            } else {
+                aff[0] = (float)cos(th); aff[1] = (float)(-sin(th)); aff[2] = (float)sin(th); aff[3] = (float)cos(th);
+            }
+            aff[4] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
+            aff[5] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
         }
         __syncthreads();
         // row pass: along c
@@ -72,7 +78,7 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
             ty[i] = sy;
         }
         __syncthreads();
-        const float cs = aff[0], sn = aff[1], scx = aff[2], scy = aff[3];
+        const float lp = aff[0], lq = aff[1], lr = aff[2], lt = aff[3], scx = aff[4], scy = aff[5];
         const float c0 = 0.5f * (float)(kSide - 1);
         float* out = dst + k * kPix;
         for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
@@ -88,9 +94,9 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
                 }
             }
             const float u = (float)c - c0, v = (float)r - c0;
-            // X = sx (cos u - sin v) + c0 + alpha * smoothed dx;  Y = sy (sin u + cos v) + c0 + alpha * ...
-            const float X = fmaf(a.alpha, gx, fmaf(scx, fmaf(cs, u, -(sn * v)), c0));
-            const float Y = fmaf(a.alpha, gy, fmaf(scy, fmaf(sn, u, cs * v), c0));
+            // X = sx (p u + q v) + c0 + alpha * smoothed dx;  Y = sy (r u + t v) + c0 + alpha * smoothed dy
+            const float X = fmaf(a.alpha, gx, fmaf(scx, fmaf(lp, u, lq * v), c0));
+            const float Y = fmaf(a.alpha, gy, fmaf(scy, fmaf(lr, u, lt * v), c0));
             const float xf = floorf(X), yf = floorf(Y);
             const float wx = X - xf, wy = Y - yf;
             float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;

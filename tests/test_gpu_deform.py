@@ -79,3 +79,42 @@ def test_more_images_than_workgroups(oracle):
     assert got.min() >= -1.0 and got.max() <= 1.0
     # same source image, different index: different deformation
     assert np.abs(got[0] - got[1000]).max() > 0.1
+
+
+def test_shear_and_per_image_angle_bounds(oracle):
+    """Horizontal shear instead of rotation, and one bound of the angle per image taken from the
+    label (7.5 degrees for digits 1 and 7, 15 for the others), against the oracle."""
+    import torch
+    from paper_1003_0358_amd import binding
+    imgs, lab = datagen.stroke_images(300, seed=8)
+    src = torch.from_numpy(imgs).cuda()
+    labels = torch.from_numpy(lab).cuda()
+    beta = binding.beta_for_labels(labels)
+    bh = beta.cpu().numpy()
+    assert set(np.unique(bh)) == {7.5, 15.0}
+    assert np.array_equal(bh == 7.5, (lab == 1) | (lab == 7))
+    oracle.set_threads(8)
+    for shear in (1, 0):
+        p = binding.default_deform_params()
+        p.shear = shear
+        got = binding.deform_batch(src, 21, 500, p, beta_deg=beta).cpu().numpy()
+        ref32 = oracle.deform_batch(imgs, 21, 500, mode="f32", shear=bool(shear), beta_each=bh)
+        ref64 = oracle.deform_batch(imgs, 21, 500, mode="f64", shear=bool(shear), beta_each=bh)
+        assert np.abs(got - ref32).max() <= 1e-5
+        assert np.abs(got - ref64).max() <= 1e-5
+        # the scalar bound, sheared
+        p.beta_deg = 15.0
+        got = binding.deform_batch(src[:64], 21, 500, p).cpu().numpy()
+        ref = oracle.deform_batch(imgs[:64], 21, 500, mode="f64", shear=bool(shear), beta_deg=15.0)
+        assert np.abs(got - ref).max() <= 1e-5
+    oracle.set_threads(1)
+    # shear with a zero angle bound and nothing else is the identity, exactly
+    p = binding.default_deform_params()
+    p.shear, p.alpha, p.beta_deg, p.gamma_pct = 1, 0.0, 0.0, 0.0
+    got = binding.deform_batch(src[:20], 3, 0, p).cpu().numpy()
+    assert np.array_equal(got, datagen.to_inputs(imgs[:20]))
+    # a shear flag outside {0, 1} is an argument error
+    p.shear = 2
+    lib = binding.load()
+    out = torch.empty((1, 784), dtype=torch.float32, device="cuda")
+    assert lib.deform_batch(p, src, 1, 0, 0, out) == binding.E_ARG

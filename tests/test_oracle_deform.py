@@ -222,3 +222,101 @@ def test_f32_mode_tracks_f64(oracle):
     b = oracle.deform_batch(imgs, seed=3, first_index=0, mode="f32")
     assert b.dtype == np.float32
     assert np.abs(a - b).max() < 1e-5
+
+
+# ---- horizontal shear (section "Deforming images ...": tan(beta) = horizontal displacement / height) ----
+def test_shear_linear_part(oracle):
+    # rotation: (cos, -sin, sin, cos); shear: (1, tan, 0, 1); same angle = beta * s0 degrees
+    s3 = np.array([0.6, 0.0, 0.0], np.float32)
+    th = np.deg2rad(15.0 * float(s3[0]))
+    assert oracle.linear_part(False, 15.0, s3) == pytest.approx([np.cos(th), -np.sin(th), np.sin(th), np.cos(th)], abs=1e-15)
+    assert oracle.linear_part(True, 15.0, s3) == pytest.approx([1.0, np.tan(th), 0.0, 1.0], abs=1e-15)
+    # zero angle: both are the identity, exactly
+    z = np.zeros(3, np.float32)
+    assert list(oracle.linear_part(True, 15.0, z)) == [1, 0, 0, 1]
+    assert list(oracle.linear_part(False, 15.0, z)) == [1, 0, 0, 1]
+    # rotation given as (cos, sin) and as its linear part are the same resampling, bit for bit
+    img = _img()[0]
+    rng = np.random.default_rng(4)
+    dx = rng.uniform(-2, 2, (28, 28)); dy = rng.uniform(-2, 2, (28, 28))
+    a = oracle.resample(img, np.cos(th), np.sin(th), 1.1, 0.9, dx, dy)
+    b = oracle.resample_lin(img, [np.cos(th), -np.sin(th), np.sin(th), np.cos(th)], 1.1, 0.9, dx, dy)
+    assert np.array_equal(a, b)
+
+
+def test_shear_by_an_integer_slope_moves_rows_by_whole_pixels(oracle):
+    img = _img()[2]
+    z = np.zeros((28, 28))
+    # slope 2: row r reads from column c + 2 (r - 13.5) = c + 2 r - 27 (whole pixels), rows stay rows
+    out = oracle.resample_lin(img, [1.0, 2.0, 0.0, 1.0], 1.0, 1.0, z, z)
+    want = np.zeros((28, 28))
+    for r in range(28):
+        for c in range(28):
+            cc = c + 2 * r - 27
+            want[r, c] = img[r, cc] if 0 <= cc < 28 else 0
+    assert np.allclose(out, want / 127.5 - 1.0, rtol=0, atol=1e-12)
+    # tan(beta) is the ratio of horizontal displacement to height: top and bottom rows are
+    # 27 rows apart and end up 2 * 27 columns apart
+    assert (2 * 27 - 27) - (2 * 0 - 27) == 2 * 27
+    # slope 1 puts source columns half way between pixels: the mean of two neighbours
+    out = oracle.resample_lin(img, [1.0, 1.0, 0.0, 1.0], 1.0, 1.0, z, z)
+    r, c = 10, 15          # X = 15 + 10 - 13.5 = 11.5
+    assert out[r, c] == pytest.approx((0.5 * img[r, 11] + 0.5 * img[r, 12]) / 127.5 - 1.0, abs=1e-12)
+
+
+def test_shear_keeps_images_that_do_not_vary_along_rows(oracle):
+    # I(r, c) = f(r): a horizontal shear reads the same row, so nothing changes where all taps are inside
+    rr = np.arange(28)
+    img = np.repeat(((rr * 9) % 251).astype(np.uint8)[:, None], 28, axis=1)
+    z = np.zeros((28, 28))
+    t = np.tan(np.deg2rad(15.0))
+    out = oracle.resample_lin(img, [1.0, t, 0.0, 1.0], 1.0, 1.0, z, z)
+    r, c = np.meshgrid(np.arange(28.0), np.arange(28.0), indexing="ij")
+    X = (c - 13.5) + t * (r - 13.5) + 13.5
+    inside = (X >= 0) & (X <= 27)
+    assert inside.sum() > 600
+    assert np.allclose(out[inside], (img / 127.5 - 1.0)[inside], rtol=0, atol=1e-12)
+
+
+def test_shear_matches_scipy_map_coordinates_and_plane(oracle):
+    img = _img()[1]
+    rng = np.random.default_rng(6)
+    dx = oracle.smooth_field(rng.uniform(-1, 1, (28, 28)), 6.0, 21, 36.0)
+    dy = oracle.smooth_field(rng.uniform(-1, 1, (28, 28)), 6.0, 21, 36.0)
+    t = np.tan(np.deg2rad(-12.0)); sx, sy = 1.12, 0.9
+    out = oracle.resample_lin(img, [1.0, t, 0.0, 1.0], sx, sy, dx, dy)
+    r, c = np.meshgrid(np.arange(28.0), np.arange(28.0), indexing="ij")
+    u, v = c - 13.5, r - 13.5
+    X = sx * (u + t * v) + 13.5 + dx
+    Y = sy * v + 13.5 + dy
+    ref = ndi.map_coordinates(img.astype(np.float64), [Y, X], order=1, mode="grid-constant", cval=0.0)
+    assert np.allclose(out, ref / 127.5 - 1.0, rtol=0, atol=1e-12)
+    # a plane is interpolated exactly
+    plane = (10 + 3 * r + 5 * c).astype(np.uint8)
+    out = oracle.resample_lin(plane, [1.0, t, 0.0, 1.0], sx, sy, dx, dy)
+    inside = (X >= 0) & (X <= 27) & (Y >= 0) & (Y <= 27)
+    assert inside.sum() > 400
+    assert np.allclose(out[inside], ((10 + 3 * Y + 5 * X) / 127.5 - 1.0)[inside], rtol=0, atol=1e-10)
+
+
+def test_shear_pipeline_and_per_image_angles(oracle):
+    imgs = _img(seed=5)
+    beta = np.array([7.5, 15.0, 15.0, 7.5], np.float32)      # e.g. digits 1 and 7 get the smaller bound
+    out = oracle.deform_batch(imgs.reshape(4, 784), seed=3, first_index=40, shear=True, beta_each=beta)
+    for k in range(4):
+        s3, Dx, Dy = oracle.draw_image_randoms(3, 40 + k)
+        _, _, sx, sy = oracle.affine_scalars(float(beta[k]), 15.0, s3)
+        pqrt = oracle.linear_part(True, float(beta[k]), s3)
+        assert pqrt[1] == pytest.approx(np.tan(np.deg2rad(float(beta[k]) * float(s3[0]))), abs=1e-15)
+        gx = oracle.smooth_field(Dx.reshape(28, 28), 6.0, 21, 36.0)
+        gy = oracle.smooth_field(Dy.reshape(28, 28), 6.0, 21, 36.0)
+        want = oracle.resample_lin(imgs[k], pqrt, sx, sy, gx, gy)
+        assert np.array_equal(out[k], want.ravel())
+        # one angle bound per image == the scalar bound applied to that image alone
+        one = oracle.deform_batch(imgs[k].reshape(1, 784), seed=3, first_index=40 + k, beta_deg=float(beta[k]), shear=True)
+        assert np.array_equal(out[k], one[0])
+    # rotation with per-image bounds likewise
+    rot = oracle.deform_batch(imgs.reshape(4, 784), seed=3, first_index=40, beta_each=beta)
+    one = oracle.deform_batch(imgs[1].reshape(1, 784), seed=3, first_index=41, beta_deg=15.0)
+    assert np.array_equal(rot[1], one[0])
+    assert np.abs(rot - out).max() > 1e-3                      # shear and rotation differ
