@@ -1,0 +1,81 @@
+"""Epoch driver around the library calls, as the paper runs its training (sections "Data",
+"Architectures", "Deforming images ...", "Results"):
+
+* at the beginning of every epoch the whole training set is deformed anew (dbsn_deform_batch with
+  first_index = epoch * n, so every epoch sees different deformations of every image);
+* one on-line back-propagation pass over it (dbsn_bp_steps), with a learning rate that shrinks by
+  a constant factor after each epoch, from eta_start down to eta_end;
+* validation on the UN-deformed training set (or a set the caller gives), forward only
+  (dbsn_classify); the weights with the lowest validation error are the ones kept.
+
+Host logic only: every array operation on the data runs in the library's kernels (the un-deformed
+inputs are produced by the deformation kernel with all amplitudes at zero, which is the exact
+intensity map).
+"""
+import numpy as np
+
+from . import binding
+
+
+def eta_schedule(epochs, eta_start=1e-3, eta_end=1e-6):
+    """Learning rates of the epochs as float32: eta_start * f**e with the constant f that reaches
+    eta_end in the last epoch."""
+    if epochs < 1:
+        return np.zeros(0, np.float32)
+    if epochs == 1:
+        return np.array([eta_start], np.float32)
+    f = (eta_end / eta_start) ** (1.0 / (epochs - 1))
+    return np.array([eta_start * f ** e for e in range(epochs)], dtype=np.float32)
+
+
+def identity_params():
+    """Deformation parameters that leave the image alone: the kernel then only maps intensities to
+    p / 127.5 - 1."""
+    return binding.DeformParams(0.0, 0.0, 0.0, 0.0, 1, 0)
+
+
+def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6, params=None,
+               beta_by_label=True, seed=0, chunk=1000, val_u8=None, val_labels=None, keep_best=True,
+               log=None):
+    """Train `mlp` (binding.Mlp) for `epochs` epochs.
+
+    train_u8: uint8 device tensor [n, 784]; train_labels: int32 device tensor [n];
+    params: binding.DeformParams (default: the paper's values); beta_by_label: the bound of the
+    rotation / shear angle follows the label: the look-alike digits 1 and 7 get params.beta_deg, all
+    others twice that (7.5 and 15 degrees with the default), instead of params.beta_deg for all;
+    val_u8 / val_labels: validation set (default: the un-deformed training set).
+    Returns the history: one dict per epoch with eta, mean training loss, validation errors.
+    With keep_best the network ends with the weights of the epoch of lowest validation error.
+    """
+    import torch
+    n = train_u8.shape[0]
+    assert train_u8.dtype == torch.uint8 and train_u8.shape[1] == 784
+    assert train_labels.dtype == torch.int32 and train_labels.numel() == n
+    params = params or binding.default_deform_params()
+    if val_u8 is None:
+        val_u8, val_labels = train_u8, train_labels
+    beta = binding.beta_for_labels(train_labels, beta_similar=params.beta_deg, beta_other=2.0 * params.beta_deg) \
+        if beta_by_label else None
+    val_x = binding.deform_batch(val_u8, 0, 0, identity_params())
+    xbuf = torch.empty((chunk, 784), dtype=torch.float32, device=train_u8.device)
+    loss = torch.zeros(n, dtype=torch.float32, device=train_u8.device)
+    history, best, best_params = [], None, None
+    for e, eta in enumerate(eta_schedule(epochs, eta_start, eta_end)):
+        for a in range(0, n, chunk):
+            m = min(chunk, n - a)
+            binding.deform_batch(train_u8[a:a + m], seed, e * n + a, params, out=xbuf[:m],
+                                 beta_deg=None if beta is None else beta[a:a + m])
+            mlp.bp_steps(xbuf[:m], train_labels[a:a + m], float(eta), loss[a:a + m])
+        mlp.status()
+        pred = mlp.classify(val_x)
+        errors = int((pred != val_labels).sum().item())
+        rec = {"epoch": e, "eta": float(eta), "train_loss": float(loss.mean().item()), "val_errors": errors,
+               "val_n": int(val_labels.numel())}
+        history.append(rec)
+        if log:
+            log(rec)
+        if keep_best and (best is None or errors < best):
+            best, best_params = errors, mlp.get_params()
+    if keep_best and best_params is not None and history[-1]["val_errors"] != best:
+        mlp.set_params(best_params)
+    return history
