@@ -25,6 +25,9 @@ SHAPES = [
     [784] + [300] * 9 + [10],        # nine hidden layers: register groups packed at run time
     [3000, 3000, 3000, 500, 10],     # tiles that do not all fit in registers: the streaming variant
     [784, 300, 700, 10],             # more than 512 inputs to the output layer: several columns per thread
+    [784, 1500, 1000, 500, 10],      # the other nets of the benchmark configurations
+    [784, 2000, 1500, 1000, 500, 10],
+    [784] + [1000] * 9 + [10],
 ]
 
 
