@@ -485,29 +485,29 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     if (n == 0) return DBSN_OK;
     if (!samples_dev || !labels_out_dev) return fail(DBSN_E_ARG, "null pointer");
     if (!aligned(samples_dev, 4) || !aligned(labels_out_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
-    // batches of kBatchSamples samples go through the layers together, one launch per layer
+    // the samples go through the layers in passes of kBatchSamples (full passes keep every compute
+    // unit at its four resident workgroups, which is where the kernel runs best), one launch per layer
     const int L = m->net.L, n0 = m->sizes[0], ldact = m->plan.ldact;
     float* act[2] = {reinterpret_cast<float*>(m->arena + m->plan.act[0]),
                      reinterpret_cast<float*>(m->arena + m->plan.act[1])};
-    for (int64_t at = 0; at < n; at += kBatchSamples) {
-        const int S = (int)std::min<int64_t>(kBatchSamples, n - at);
+    const int64_t per = kBatchSamples;
+    for (int64_t at = 0; at < n; at += per) {
+        const int S = (int)std::min<int64_t>(per, n - at);
         const float* X = samples_dev + at * n0;
         int ldx = n0;
-        for (int l = 1; l <= L; ++l) {
+        for (int l = 1; l < L; ++l) {
             const Layer& Ly = m->net.lay[l];
             float* Y = act[l & 1];
             const dim3 grid((Ly.n_out + kBatchTile - 1) / kBatchTile, (S + kBatchTile - 1) / kBatchTile);
-            if (l < L)
-                hipLaunchKernelGGL(k_layer_batch<true>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W, Ly.ld,
-                                   Ly.b, Ly.n_in, Ly.n_out, Y, ldact);
-            else
-                hipLaunchKernelGGL(k_layer_batch<false>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W, Ly.ld,
-                                   Ly.b, Ly.n_in, Ly.n_out, Y, ldact);
+            hipLaunchKernelGGL(k_layer_batch<true>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W, Ly.ld,
+                               Ly.b, Ly.n_in, Ly.n_out, Y, ldact);
             X = Y;
             ldx = ldact;
         }
-        hipLaunchKernelGGL(k_argmax_batch, dim3((S + 255) / 256), dim3(256), 0, m->stream, X, ldact, S,
-                           m->net.lay[L].n_out, labels_out_dev + at);
+        const Layer& Lt = m->net.lay[L];
+        const int per_block = kBatchThreads / 64;
+        hipLaunchKernelGGL(k_top_batch, dim3((S + per_block - 1) / per_block), dim3(kBatchThreads), 0, m->stream, X, ldx,
+                           S, Lt.W, Lt.ld, Lt.b, Lt.n_in, Lt.n_out, labels_out_dev + at);
     }
     HIP_TRY(hipGetLastError());
     return DBSN_OK;

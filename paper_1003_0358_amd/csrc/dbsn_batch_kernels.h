@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
                     const int s = s0 + sw + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
                     if (s < S) {
                         const float v = acc[a][c][r] + bj;
-                        Y[(size_t)s * ldy + j] = ACT ? act(v) : v;
+                        Y[(size_t)s * ldy + j] = ACT ? act_fast(v) : v;
                     }
                 }
             }
@@ -103,18 +103,42 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
     }
 }
 
-// labels[s] = index of the largest of the n_out values of row s (the lowest index on ties)
-__global__ void k_argmax_batch(const float* __restrict__ Y, int ldy, int S, int n_out, int* __restrict__ labels) {
-    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+// Output layer of the classification pass: labels[s] = index of the largest pre-activation
+// b[c] + sum_i W[c][i] X[s][i] over the classes (the lowest index on ties).  The layer has only a
+// few rows, so it is no job for 128-wide tiles: one wavefront per sample, lanes over the inputs,
+// classes 16 at a time in registers, sums over the lanes on the vector ALU.
+__global__ __launch_bounds__(kBatchThreads) void k_top_batch(const float* __restrict__ X, int ldx, int S,
+                                                              const float* __restrict__ W, int ldw,
+                                                              const float* __restrict__ b, int n_in, int n_out,
+                                                              int* __restrict__ labels) {
+    const int lane = threadIdx.x & 63;
+    const int s = blockIdx.x * (kBatchThreads / 64) + (threadIdx.x >> 6);
     if (s >= S) return;
-    const float* y = Y + (size_t)s * ldy;
+    const float* x = X + (size_t)s * ldx;
     int best = 0;
-    float bv = y[0];
-    for (int j = 1; j < n_out; ++j) {
-        const float v = y[j];
-        if (v > bv) { bv = v; best = j; }
+    float bv = 0.0f;
+    for (int c0 = 0; c0 < n_out; c0 += 16) {
+        float acc[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) acc[c] = 0.0f;
+        for (int i = lane; i < n_in; i += 64) {
+            const float xi = x[i];
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+                if (c0 + c < n_out) acc[c] = fmaf(W[(size_t)(c0 + c) * ldw + i], xi, acc[c]);
+        }
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            if (c0 + c < n_out) {   // (uniform)
+                float v = acc[c];
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+                v += b[c0 + c];
+                if ((c0 + c == 0) || v > bv) { bv = v; best = c0 + c; }
+            }
+        }
     }
-    labels[s] = best;
+    if (lane == 0) labels[s] = best;
 }
 
 }  // namespace dbsn
