@@ -6,11 +6,13 @@
 //
 // One workgroup of 4 wavefronts computes a tile of 128 samples x 128 neurons; wavefront w owns the
 // 64 x 64 quadrant (w & 1, w >> 1) as 2 x 2 v_mfma_f32_32x32x2 accumulators (64 registers).  The k
-// dimension is walked in chunks of 32 staged in LDS (pitch 33: the operand reads, row = lane % 32,
-// k = lane / 32, fall in distinct banks); the next chunk's global loads are issued before the
-// current chunk's matrix instructions and parked in registers, so memory latency hides behind the
-// arithmetic.  Operand layout of the instruction: lane t supplies A[i = t % 32][k = t / 32] and
-// B[k = t / 32][j = t % 32]; result register r of lane t is D[i = r % 4 + 4 (t / 32) + 8 (r / 4)][j = t % 32].
+// dimension is walked in chunks of 16 staged in LDS (pitch 17: the operand reads, row = lane % 32,
+// k = lane / 32, fall in distinct banks), in two buffers used in turn: while the matrix
+// instructions work on one chunk, the next one is written to the other buffer and the one after
+// that is on its way from memory into registers, so a chunk costs one barrier and memory latency
+// hides behind the arithmetic.  Operand layout of the instruction: lane t supplies
+// A[i = t % 32][k = t / 32] and B[k = t / 32][j = t % 32]; result register r of lane t is
+// D[i = r % 4 + 4 (t / 32) + 8 (r / 4)][j = t % 32].
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,10 +23,10 @@ namespace dbsn {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kBatchTile = 128;         // samples and neurons per workgroup tile
-constexpr int kBatchK = 32;             // k-chunk staged in LDS
+constexpr int kBatchK = 16;             // k-chunk staged in LDS
 constexpr int kBatchPitch = kBatchK + 1;
 constexpr int kBatchThreads = 256;
-constexpr int kBatchRows = kBatchTile / 8;   // rows of each operand tile a thread stages per chunk
+constexpr int kBatchRows = kBatchTile * kBatchK / kBatchThreads;   // elements of each operand tile a thread stages per chunk
 constexpr int kBatchSamples = 8192;     // samples per pass through the layers (sizes the activation buffers)
 
 // Y[s][j] = f(b[j] + sum_i W[j][i] X[s][i]) for s < S, j < n_out; f = scaled tanh (ACT) or identity
@@ -35,8 +37,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
                                                                 const float* __restrict__ W, int ldw,
                                                                 const float* __restrict__ b, int n_in, int n_out,
                                                                 float* __restrict__ Y, int ldy) {
-    __shared__ float Xs[kBatchTile * kBatchPitch];
-    __shared__ float Ws[kBatchTile * kBatchPitch];
+    __shared__ float Xs[2][kBatchTile * kBatchPitch];
+    __shared__ float Ws[2][kBatchTile * kBatchPitch];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s0 = blockIdx.y * kBatchTile, j0 = blockIdx.x * kBatchTile;
     const int sw = (wave & 1) * 64, jw = (wave >> 1) * 64;
@@ -47,35 +49,47 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
         for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-    const int tk = threadIdx.x & 31, tr = threadIdx.x >> 5;   // staging: column tk, rows tr, tr + 8, ...
+    // staging: column tk of rows tr, tr + 16, ...
+    const int tk = threadIdx.x & (kBatchK - 1), tr = threadIdx.x / kBatchK;
+    constexpr int kRowStep = kBatchThreads / kBatchK;
     float xr[kBatchRows], wrg[kBatchRows];
     auto fetch = [&](int k0) {
         const int k = k0 + tk;
 #pragma unroll
         for (int r = 0; r < kBatchRows; ++r) {
-            const int row = tr + 8 * r;
+            const int row = tr + kRowStep * r;
             const int s = s0 + row, j = j0 + row;
             xr[r] = (s < S && k < n_in) ? X[(size_t)s * ldx + k] : 0.0f;
             wrg[r] = (j < n_out && k < n_in) ? W[(size_t)j * ldw + k] : 0.0f;
         }
     };
-    fetch(0);
-    for (int k0 = 0; k0 < n_in; k0 += kBatchK) {
+    auto stage = [&](int buf) {
 #pragma unroll
         for (int r = 0; r < kBatchRows; ++r) {
-            const int row = tr + 8 * r;
-            Xs[row * kBatchPitch + tk] = xr[r];
-            Ws[row * kBatchPitch + tk] = wrg[r];
+            const int row = tr + kRowStep * r;
+            Xs[buf][row * kBatchPitch + tk] = xr[r];
+            Ws[buf][row * kBatchPitch + tk] = wrg[r];
         }
-        __syncthreads();
-        if (k0 + kBatchK < n_in) fetch(k0 + kBatchK);   // in flight during the matrix instructions below
+    };
+    const int nchunks = (n_in + kBatchK - 1) / kBatchK;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    if (nchunks > 1) fetch(kBatchK);
+    for (int c = 0; c < nchunks; ++c) {
+        const int cur = c & 1;
+        // the other buffer was last read one chunk ago, before the barrier every wavefront has passed
+        if (c + 1 < nchunks) stage(cur ^ 1);
+        if (c + 2 < nchunks) fetch((c + 2) * kBatchK);   // in flight during the matrix instructions below
+        const float* xs = Xs[cur];
+        const float* ws = Ws[cur];
 #pragma unroll
         for (int kk = 0; kk < kBatchK; kk += 2) {
             const int kc = kk + (lane >> 5);
-            const float a0 = Xs[(sw + (lane & 31)) * kBatchPitch + kc];
-            const float a1 = Xs[(sw + 32 + (lane & 31)) * kBatchPitch + kc];
-            const float w0 = Ws[(jw + (lane & 31)) * kBatchPitch + kc];
-            const float w1 = Ws[(jw + 32 + (lane & 31)) * kBatchPitch + kc];
+            const float a0 = xs[(sw + (lane & 31)) * kBatchPitch + kc];
+            const float a1 = xs[(sw + 32 + (lane & 31)) * kBatchPitch + kc];
+            const float w0 = ws[(jw + (lane & 31)) * kBatchPitch + kc];
+            const float w1 = ws[(jw + 32 + (lane & 31)) * kBatchPitch + kc];
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, w0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, w1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, w0, acc[1][0], 0, 0, 0);
