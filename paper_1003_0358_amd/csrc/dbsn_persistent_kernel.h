@@ -64,7 +64,11 @@ __device__ long long g_prof_first;         // first step to record
         if (threadIdx.x == 0 && ps_ >= 0 && ps_ < kProfSteps && (slot) < kProfSlots)                    \
             prof_lds_[ps_ * kProfSlots + (slot)] = (val);                                               \
     } while (0)
+#ifdef DBSN_PROFILE_WALL   // the 100 MHz counter all compute units share, for comparing workgroups
+#define DBSN_PROF(step, slot) DBSN_PROF_VAL(step, slot, wall_clock64())
+#else
 #define DBSN_PROF(step, slot) DBSN_PROF_VAL(step, slot, clock64())
+#endif
 #define DBSN_PROF_FLUSH()                                                                               \
     do {                                                                                                \
         __syncthreads();                                                                                \
