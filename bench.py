@@ -39,7 +39,7 @@ def n_weights(sizes):
     return sum((sizes[i] + 1) * sizes[i + 1] for i in range(len(sizes) - 1))
 
 
-def cpu_baseline(sizes, img, lab, eta, budget_s=15.0):
+def cpu_baseline(sizes, img, lab, eta, budget_s=25.0):
     """The oracle (fp32 mode, OpenMP over independent neurons) on a bounded sample of the same
     workload: deform + bp_step per sample, on the host cores of this machine."""
     import numpy as np

@@ -246,7 +246,7 @@ __device__ void top_phase(const Layer& Ly, const float* __restrict__ xin, int la
             }
             if (gdst != nullptr) gdst[i] = gsum;
         }
-        if (do_update && threadIdx.x < n_out) Ly.b[threadIdx.x] -= eta * dL[threadIdx.x];
+        if (do_update && (int)threadIdx.x < n_out) Ly.b[threadIdx.x] -= eta * dL[threadIdx.x];
     }
     __syncthreads();
 }

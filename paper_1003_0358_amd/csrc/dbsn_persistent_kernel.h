@@ -80,7 +80,7 @@ constexpr int kProfLdsFloats = 2 * kProfSteps * kProfSlots;
 #define DBSN_PROF_DECL do { } while (0)
 #define DBSN_PROF_ARGS
 #define DBSN_PROF_PASS
-#define DBSN_PROF(step, slot) do { } while (0)
+#define DBSN_PROF(step, slot) do { (void)(step); (void)(slot); } while (0)
 #define DBSN_PROF_VAL(step, slot, val) do { } while (0)
 #define DBSN_PROF_FLUSH() do { } while (0)
 constexpr int kProfLdsFloats = 0;
@@ -872,7 +872,7 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
             if (last && g == 0) net.lay[L - 1].x[i] = xv;
         }
     }
-    if (threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
+    if ((int)threadIdx.x < nc) bL[threadIdx.x] -= eta * dL[threadIdx.x];
     lds_barrier();
     DBSN_PROF_SUB(ps, ph, 7);
     return true;
@@ -1010,7 +1010,7 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
             const int j = e / LyL.n_in, i = e - j * LyL.n_in;
             LyL.W[(size_t)j * LyL.ld + i] = lds[PLds::WL + e];
         }
-        if (threadIdx.x < LyL.n_out) LyL.b[threadIdx.x] = lds[PLds::bL + threadIdx.x];
+        if ((int)threadIdx.x < LyL.n_out) LyL.b[threadIdx.x] = lds[PLds::bL + threadIdx.x];
     }
 }
 
