@@ -145,23 +145,31 @@ def test_steps_equal_repeated_single_steps_and_runs_repeat():
 
 
 def test_full_size_net_in_bench_configuration(oracle):
-    """The 784-2500-2000-1500-1000-500-10 net, persistent mode, as bench.py runs it."""
+    """The 784-2500-2000-1500-1000-500-10 net in the launch configuration bench.py times: deformed
+    stroke images, 1000 on-line steps in one persistent launch, eta 1e-3.  Held to the 100-step bar
+    over all 1000 steps (measured: 1.3e-7 against the float32 oracle, 1.7e-7 against the float64
+    one, which differ by 1.8e-7 between themselves)."""
     torch = _torch()
-    X, y = _data(40, seed=2)
-    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    from paper_1003_0358_amd import binding
+    img, y = datagen.stroke_images(1000, seed=2)
+    src = torch.from_numpy(img).cuda()
+    xs = binding.deform_batch(src, 0, 0)
+    ys = torch.from_numpy(y).cuda()
+    X = xs.cpu().numpy()
     m = _mk(NET4, 1, seed=0)
     p0 = m.get_params()
-    loss = torch.zeros(40, dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1000, dtype=torch.float32, device="cuda")
     m.bp_steps(xs, ys, 1e-3, loss)
     m.status()
     got = m.get_params()
+    m.close()
     oracle.set_threads(8)
     ref, l32 = oracle.bp_steps(NET4, p0, X, y, np.float32(1e-3), "f32")
     oracle.set_threads(1)
+    gl = loss.cpu().numpy()
     assert np.abs(got - ref).max() <= 1e-4
-    assert np.abs(loss.cpu().numpy() - l32).max() <= 1e-4
-    assert np.abs(got - p0).max() > 1e-4
-    m.close()
+    assert np.abs(gl - l32).max() <= 1e-4
+    assert np.abs(got - p0).max() > 1e-3
 
 
 def test_forward_and_classify(oracle):
