@@ -53,14 +53,20 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
     const int tk = threadIdx.x & (kBatchK - 1), tr = threadIdx.x / kBatchK;
     constexpr int kRowStep = kBatchThreads / kBatchK;
     float xr[kBatchRows], wrg[kBatchRows];
+    // element offsets of this thread's first staged row (32-bit: a pass holds fewer than 2^31 floats);
+    // rows further down are a uniform stride away, the chunk moves the uniform base
+    const unsigned xoff = (unsigned)(s0 + tr) * (unsigned)ldx + (unsigned)tk;
+    const unsigned woff = (unsigned)(j0 + tr) * (unsigned)ldw + (unsigned)tk;
+    const unsigned xstep = (unsigned)kRowStep * (unsigned)ldx, wstep = (unsigned)kRowStep * (unsigned)ldw;
     auto fetch = [&](int k0) {
-        const int k = k0 + tk;
+        const bool kin = k0 + tk < n_in;
+        const float* __restrict__ Xk = X + k0;
+        const float* __restrict__ Wk = W + k0;
 #pragma unroll
         for (int r = 0; r < kBatchRows; ++r) {
             const int row = tr + kRowStep * r;
-            const int s = s0 + row, j = j0 + row;
-            xr[r] = (s < S && k < n_in) ? X[(size_t)s * ldx + k] : 0.0f;
-            wrg[r] = (j < n_out && k < n_in) ? W[(size_t)j * ldw + k] : 0.0f;
+            xr[r] = (kin && s0 + row < S) ? Xk[xoff + (unsigned)r * xstep] : 0.0f;
+            wrg[r] = (kin && j0 + row < n_out) ? Wk[woff + (unsigned)r * wstep] : 0.0f;
         }
     };
     auto stage = [&](int buf) {
