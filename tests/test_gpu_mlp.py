@@ -320,3 +320,32 @@ def test_wait_timeout_is_reported_not_hung():
     ref.bp_steps(xs, ys, 1e-3)
     assert np.abs(m.get_params() - ref.get_params()).max() <= 1e-6
     m.close(); ref.close()
+
+
+def test_random_shapes_three_steps(oracle):
+    """Seeded random architectures (1 to 6 hidden layers, widths 1 to 2600, 1 to 64 classes, inputs 1
+    to 1200): three steps in one persistent launch against the float64 oracle.  Exercises ragged
+    tiles, layers narrower than a wavefront, single-row tiles, both output-layer paths, both register
+    layouts and both parities of the hand-over buffers."""
+    torch = _torch()
+    rng = np.random.default_rng(1234)
+    for case in range(24):
+        nh = int(rng.integers(1, 7))
+        widths = [int(rng.choice([1, 3, 7, 33, 64, 100, 257, 511, 512, 513, 900, 1300, 2600])) for _ in range(nh)]
+        sizes = [int(rng.choice([1, 5, 64, 300, 784, 1200]))] + widths + [int(rng.choice([1, 2, 10, 17, 64]))]
+        X = rng.uniform(-1, 1, (3, sizes[0])).astype(np.float32)
+        y = rng.integers(0, sizes[-1], 3).astype(np.int32)
+        m = _mk(sizes, 1, seed=case)
+        # somewhat larger weights than the initialisation so that narrow layers carry signal too
+        p0 = (m.get_params() * 2).astype(np.float32)
+        m.set_params(p0)
+        m.bp_steps(torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), 1e-3)
+        m.status()
+        got = m.get_params()
+        ref = oracle.bp_steps(sizes, p0, X, y, 1e-3, "f64")[0]
+        assert _close(got, ref, rtol=2e-5), (sizes, float(np.abs(got - ref).max()))
+        if sizes[-1] > 1:     # (a single class has probability 1 and nothing to learn)
+            assert np.abs(got - p0).max() > 0
+        else:
+            assert np.array_equal(got, p0)
+        m.close()
