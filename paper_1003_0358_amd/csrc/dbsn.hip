@@ -43,6 +43,7 @@ int32_t fail(int32_t code, const char* fmt, ...) {
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+constexpr int kZerosAt = 16;         // four ints of the flag block that stay zero (a float4 of zeros for the kernels)
 constexpr int kTileCounterAt = 32;   // first tile counter, in ints from the start of the arena's flag block
 static_assert((kTileCounterAt + kMaxLayers + 1) * sizeof(int) <= 256, "flag block holds the tile counters");
 constexpr int kArenaGroups = 512;  // partial-sum rows the arena is sized for (>= workgroups launched)
@@ -514,10 +515,18 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kVecLdsBytes));
                     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_ws<true>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsBytes));
+                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes));
                     m->batch_ready = true;
                 }
-                static const bool ws = getenv("DBSN_BATCH_WS") ? atoi(getenv("DBSN_BATCH_WS")) != 0 : true;
-                if (ws) {
+                static const int ws = getenv("DBSN_BATCH_WS") ? atoi(getenv("DBSN_BATCH_WS")) : 2;
+                if (ws == 2 && Ly.n_in % 4 == 0) {
+                    const int nt = (int)(grid.x * grid.y);
+                    const float* zeros = reinterpret_cast<const float*>(m->err + kZerosAt);
+                    hipLaunchKernelGGL(k_layer_batch_dma<true>, dim3(std::min(nt, m->cus)), dim3(kWsThreads), kDmaLdsBytes,
+                                       m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, (int)grid.x, nt,
+                                       zeros);
+                } else if (ws) {
                     const int nt = (int)(grid.x * grid.y);
                     hipLaunchKernelGGL(k_layer_batch_ws<true>, dim3(std::min(nt, m->cus)), dim3(kWsThreads), kWsLdsBytes,
                                        m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, (int)grid.x, nt);

@@ -29,6 +29,34 @@ constexpr int kBatchThreads = 256;
 constexpr int kBatchRows = kBatchTile * kBatchK / kBatchThreads;   // elements of each operand tile a thread stages per chunk
 constexpr int kBatchSamples = 8192;     // samples per pass through the layers (sizes the activation buffers)
 
+// End of a tile for one wavefront: its 64 x 64 quadrant (2 x 2 accumulators, first sample s_base,
+// first neuron j_base) gets bias and activation and goes to Y.  The two bias values are pinned in
+// registers before the first guarded store: a guard that were the first to touch them would make
+// every later one wait for all memory operations in flight, the stores before it included, since
+// the compiler cannot know which guards were taken.
+template <bool ACT>
+__device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], const float* __restrict__ b,
+                                               float* __restrict__ Y, int ldy, int S, int n_out, int s_base,
+                                               int j_base, int lane) {
+    const int jl = j_base + (lane & 31);
+    float bj[2] = {b[min(jl, n_out - 1)], b[min(jl + 32, n_out - 1)]};
+    asm volatile("" : "+v"(bj[0]), "+v"(bj[1]));
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int j = jl + 32 * c;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int s = s_base + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
+                if (j < n_out && s < S) {
+                    const float v = acc[a][c][r] + bj[c];
+                    Y[(size_t)s * ldy + j] = ACT ? act_fast(v) : v;
+                }
+            }
+    }
+}
+
 // Y[s][j] = f(b[j] + sum_i W[j][i] X[s][i]) for s < S, j < n_out; f = scaled tanh (ACT) or identity
 // (the output layer's pre-activations, whose largest entry is the class).  X: [S][ldx], W: [n_out][ldw],
 // Y: [S][ldy].
@@ -103,24 +131,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
         }
         __syncthreads();
     }
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const int j = j0 + jw + 32 * c + (lane & 31);
-        if (j < n_out) {
-            const float bj = b[j];
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int s = s0 + sw + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
-                    if (s < S) {
-                        const float v = acc[a][c][r] + bj;
-                        Y[(size_t)s * ldy + j] = ACT ? act_fast(v) : v;
-                    }
-                }
-            }
-        }
-    }
+    store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
 }
 
 // The same layer for operands whose rows start on 16-byte boundaries (every activation buffer of
@@ -254,24 +265,7 @@ __global__ __launch_bounds__(kBatchThreads, 2) void k_layer_batch_vec(const floa
             }
             __syncthreads();
         }
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int j = j0 + jw + 32 * c + (lane & 31);
-            if (j < n_out) {
-                const float bj = b[j];
-#pragma unroll
-                for (int a = 0; a < 2; ++a) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int s = s0 + sw + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
-                        if (s < S) {
-                            const float v = acc[a][c][r] + bj;
-                            Y[(size_t)s * ldy + j] = ACT ? act_fast(v) : v;
-                        }
-                    }
-                }
-            }
-        }
+        store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
     }
 }
 
@@ -451,24 +445,183 @@ __global__ __launch_bounds__(kWsThreads) void k_layer_batch_ws(const float* __re
         // for the next tile)
         const int tile = (int)blockIdx.x + t * (int)gridDim.x;
         const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int j = j0 + jw + 32 * c + (lane & 31);
-            const float bj = j < n_out ? b[j] : 0.0f;
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int s = s0 + sw + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
-                    if (j < n_out && s < S) {
-                        const float v = acc[a][c][r] + bj;
-                        Y[(size_t)s * ldy + j] = ACT ? act_fast(v) : v;
-                    }
-                }
-            }
-        }
+        store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
     }
     for (int i = total; i < padded; ++i) __syncthreads();   // the barriers of the producers' padding iterations
+}
+
+// The wave-specialised layer with the producers loading straight into LDS.  While the matrix
+// instructions of a SIMD run, loads that return into vector registers of the same SIMD crawl (the
+// kernel above measures it: the same producers finish an iteration three to four times faster
+// when the consumers' matrix instructions are taken out), so here the data never passes through
+// registers: global_load_lds_dwordx4 writes the 64 x 16 bytes of a wavefront's load to 1 KB of
+// consecutive LDS.  That fixes the LDS layout: rows of 32 floats without padding, eight rows per
+// load.  Bank conflicts are avoided by permuting the float4 inside each row instead: slot p of
+// row r holds the chunk's float4 number p ^ ((r >> 1) & 7), which each lane arranges by the
+// global address it supplies; a consumer reads float4 q of row r at slot q ^ ((r >> 1) & 7), and
+// the 16 rows r .. r + 15 that neighbouring lanes read then fall in 16 different bank groups.
+// Four stages of 32 KB: in iteration i the consumers work on chunk i (and, at its end, read the
+// first operands of chunk i + 1), the producers start the loads of chunk i + 3 into the stage
+// chunk i - 1 left at the last barrier and wait for those of chunk i + 2, issued an iteration
+// earlier, before they join the barrier.  A float4 of the weights past n_in comes from 16 zero
+// bytes at `zeros`, the matching one of the other operand from the start of its row (finite,
+// times zero).  Needs n_in % 4 == 0 on top of the alignment of the 128-bit kernels.
+constexpr int kDmaStages = 4;
+constexpr int kDmaOperand = kBatchTile * kVecK;   // floats of one operand tile of a stage, unpadded
+constexpr size_t kDmaLdsBytes = sizeof(float) * kDmaStages * 2 * kDmaOperand;
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and for
+// nothing else
+constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <bool ACT>
+__global__ __launch_bounds__(kWsThreads) void k_layer_batch_dma(const float* __restrict__ X, int ldx, int S,
+                                                                 const float* __restrict__ W, int ldw,
+                                                                 const float* __restrict__ b, int n_in, int n_out,
+                                                                 float* __restrict__ Y, int ldy, int nx, int ntiles,
+                                                                 const float* __restrict__ zeros) {
+    extern __shared__ __attribute__((aligned(16))) float lds_batch[];
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: the roles branch on the scalar unit)
+    const int nchunks = (n_in + kVecK - 1) / kVecK;
+    const int my_tiles = ((int)blockIdx.x < ntiles) ? (ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+    const int total = my_tiles * nchunks;   // iterations of this workgroup
+    if (total == 0) return;                 // (the whole workgroup: no barrier is left behind)
+
+    if (wave >= 4) {
+        // ---- producer: wavefront pw brings rows 32 pw .. 32 pw + 31 of both operands, eight rows a load
+        const int pw = wave - 4;
+        const int prow = lane >> 3, pslot = lane & 7;
+        int ptile = 0, pchunk = 0, pleft = total;   // next chunk to load; chunks not loaded yet
+        // byte offsets from the (uniform) operand pointers: 32 bits each, so that a load is one
+        // instruction with a scalar base and no address arithmetic on the vector unit
+        unsigned xoff[4], woff[4], xrow[4], qoff[4];
+        auto tile_offsets = [&]() {
+            const int tile = (int)blockIdx.x + ptile * (int)gridDim.x;
+            const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 32 * pw + 8 * r + prow;
+                qoff[r] = 4u * (unsigned)(pslot ^ ((row >> 1) & 7));   // first k of this lane's float4 in the chunk
+                xrow[r] = 4u * (unsigned)min(s0 + row, S - 1) * (unsigned)ldx;
+                xoff[r] = xrow[r] + 4u * qoff[r];
+                woff[r] = 4u * ((unsigned)min(j0 + row, n_out - 1) * (unsigned)ldw + qoff[r]);
+            }
+        };
+        auto load_next = [&](int stage) {
+            const int k0 = pchunk * kVecK;
+            float* xs = lds_batch + stage * 2 * kDmaOperand + (32 * pw) * kVecK;
+            float* ws = xs + kDmaOperand;
+            const char* Xk = reinterpret_cast<const char*>(X + k0);
+            const char* Wk = reinterpret_cast<const char*>(W + k0);
+            if (k0 + kVecK <= n_in) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    __builtin_amdgcn_global_load_lds((gptr)(Xk + xoff[r]), (lptr)(xs + 8 * r * kVecK), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr)(Wk + woff[r]), (lptr)(ws + 8 * r * kVecK), 16, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const bool in = k0 + (int)qoff[r] < n_in;
+                    const char* xp = in ? Xk + xoff[r] : reinterpret_cast<const char*>(X) + xrow[r];
+                    const char* wp = in ? Wk + woff[r] : reinterpret_cast<const char*>(zeros);
+                    __builtin_amdgcn_global_load_lds((gptr)xp, (lptr)(xs + 8 * r * kVecK), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr)wp, (lptr)(ws + 8 * r * kVecK), 16, 0, 0);
+                }
+            }
+            // on to the next chunk; past the end the last chunk is loaded again, into stages nobody reads
+            if (pleft > 1) {
+                --pleft;
+                if (++pchunk == nchunks) {
+                    pchunk = 0;
+                    ++ptile;
+                    tile_offsets();
+                }
+            }
+        };
+        tile_offsets();
+        load_next(0);
+        load_next(1);
+        load_next(2);
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(8));   // chunks 0 and 1 have landed
+        __builtin_amdgcn_s_barrier();
+        int stage = 3;   // (i + 3) % 4
+        for (int i = 0; i < total; ++i) {
+            load_next(stage);
+            __builtin_amdgcn_s_waitcnt(vmcnt_only(8));   // all but the eight loads just issued: chunk i + 2 has landed
+            stage = (stage + 1) & (kDmaStages - 1);
+            __builtin_amdgcn_s_barrier();
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));   // nothing may land in LDS after the workgroup has gone
+        return;
+    }
+
+    // ---- consumer
+    const int sw = (wave & 1) * 64, jw = ((wave >> 1) & 1) * 64;
+    const int lrow = lane & 31, half = lane >> 5, swz = (lrow >> 1) & 7;
+    int slot[kVecK / 8];   // float offset, inside a row, of the float4 this lane feeds to group m
+#pragma unroll
+    for (int m = 0; m < kVecK / 8; ++m) slot[m] = 4 * ((m + 4 * half) ^ swz);
+    const float* xs0 = lds_batch + (sw + lrow) * kVecK;
+    const float* ws0 = lds_batch + kDmaOperand + (jw + lrow) * kVecK;
+    __syncthreads();
+    // operands of the next group of matrix instructions, read one group ahead
+    floatx4 pa0 = *reinterpret_cast<const floatx4*>(xs0 + slot[0]);
+    floatx4 pa1 = *reinterpret_cast<const floatx4*>(xs0 + 32 * kVecK + slot[0]);
+    floatx4 pw0 = *reinterpret_cast<const floatx4*>(ws0 + slot[0]);
+    floatx4 pw1 = *reinterpret_cast<const floatx4*>(ws0 + 32 * kVecK + slot[0]);
+    int stage = 0;   // i % 4 of iteration i
+    for (int t = 0; t < my_tiles; ++t) {
+        floatx16 acc[2][2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+        for (int cc = 0; cc < nchunks; ++cc) {
+            const int stage1 = (stage + 1) & (kDmaStages - 1);
+            const float* xs = xs0 + stage * 2 * kDmaOperand;
+            const float* ws = ws0 + stage * 2 * kDmaOperand;
+            // the first group of the next chunk sits in the next stage, complete since the last barrier
+            const float* xn = xs0 + stage1 * 2 * kDmaOperand;
+            const float* wn = ws0 + stage1 * 2 * kDmaOperand;
+#pragma unroll
+            for (int m = 0; m < kVecK / 8; ++m) {
+                const floatx4 a0 = pa0, a1 = pa1, w0 = pw0, w1 = pw1;
+                if (m + 1 < kVecK / 8) {
+                    pa0 = *reinterpret_cast<const floatx4*>(xs + slot[m + 1]);
+                    pa1 = *reinterpret_cast<const floatx4*>(xs + 32 * kVecK + slot[m + 1]);
+                    pw0 = *reinterpret_cast<const floatx4*>(ws + slot[m + 1]);
+                    pw1 = *reinterpret_cast<const floatx4*>(ws + 32 * kVecK + slot[m + 1]);
+                } else {
+                    pa0 = *reinterpret_cast<const floatx4*>(xn + slot[0]);
+                    pa1 = *reinterpret_cast<const floatx4*>(xn + 32 * kVecK + slot[0]);
+                    pw0 = *reinterpret_cast<const floatx4*>(wn + slot[0]);
+                    pw1 = *reinterpret_cast<const floatx4*>(wn + 32 * kVecK + slot[0]);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // the reads go out before the matrix instructions, not after
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w0[e], acc[0][0], 0, 0, 0);
+                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w1[e], acc[0][1], 0, 0, 0);
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w0[e], acc[1][0], 0, 0, 0);
+                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w1[e], acc[1][1], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stage = stage1;
+            __syncthreads();
+        }
+        // the tile is complete: bias, activation, store (the producers are already filling the ring
+        // for the next tile)
+        const int tile = (int)blockIdx.x + t * (int)gridDim.x;
+        const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
+        store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
+    }
 }
 
 // Zeroes the tile counters of a pass (a kernel rather than a memset, so that a caller may record
