@@ -44,8 +44,6 @@ int32_t fail(int32_t code, const char* fmt, ...) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 constexpr int kZerosAt = 16;         // four ints of the flag block that stay zero (a float4 of zeros for the kernels)
-constexpr int kTileCounterAt = 32;   // first tile counter, in ints from the start of the arena's flag block
-static_assert((kTileCounterAt + kMaxLayers + 1) * sizeof(int) <= 256, "flag block holds the tile counters");
 constexpr int kArenaGroups = 512;  // partial-sum rows the arena is sized for (>= workgroups launched)
 
 bool shape_ok(const int32_t* sizes, int32_t n_sizes) {
@@ -84,8 +82,7 @@ ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
         p.gpart[k] = off;
         off = align_up(off + sizeof(float) * (size_t)kArenaGroups * p.gld);
     }
-    // error word of the training kernels; from int kTileCounterAt on, the tile counters of the
-    // batched classification layers
+    // error word of the training kernels; ints kZerosAt .. kZerosAt + 3 stay zero for good
     p.flags = off; off = align_up(off + 256);
     // activations of a batch of samples for the forward-only classification passes, two buffers
     // that the layers use in turn
@@ -491,53 +488,37 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     if (n == 0) return DBSN_OK;
     if (!samples_dev || !labels_out_dev) return fail(DBSN_E_ARG, "null pointer");
     if (!aligned(samples_dev, 4) || !aligned(labels_out_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
-    // the samples go through the layers in passes of kBatchSamples (full passes keep every compute
-    // unit at its four resident workgroups, which is where the kernel runs best), one launch per layer
+    // the samples go through the layers in passes of kBatchSamples (what the activation buffers
+    // hold), one launch per layer
     const int L = m->net.L, n0 = m->sizes[0], ldact = m->plan.ldact;
     float* act[2] = {reinterpret_cast<float*>(m->arena + m->plan.act[0]),
                      reinterpret_cast<float*>(m->arena + m->plan.act[1])};
     const int64_t per = kBatchSamples;
-    int* counters = m->err + kTileCounterAt;
     for (int64_t at = 0; at < n; at += per) {
         const int S = (int)std::min<int64_t>(per, n - at);
         const float* X = samples_dev + at * n0;
         int ldx = n0;
-        hipLaunchKernelGGL(k_zero_counters, dim3(1), dim3(64), 0, m->stream, counters, kMaxLayers + 1);
         for (int l = 1; l < L; ++l) {
             const Layer& Ly = m->net.lay[l];
             float* Y = act[l & 1];
             const dim3 grid((Ly.n_out + kBatchTile - 1) / kBatchTile, (S + kBatchTile - 1) / kBatchTile);
-            // 128-bit path when every operand row starts on a 16-byte boundary (always true of the
-            // weights and the activation buffers; of the caller's samples when sizes[0] % 4 == 0)
-            if (ldx % 4 == 0 && Ly.ld % 4 == 0 && aligned(X, 16) && aligned(Ly.W, 16)) {
+            // the fast kernel when every operand row starts on a 16-byte boundary and holds a whole
+            // number of float4 (always true of the activation buffers; of the caller's samples and
+            // the first layer when sizes[0] % 4 == 0), else the kernel that stages by element
+            // (and when its 32-bit byte offsets reach every element)
+            const bool fits = (uint64_t)Ly.n_out * Ly.ld * sizeof(float) < (1ull << 32) &&
+                              (uint64_t)S * std::max(ldx, ldact) * sizeof(float) < (1ull << 32);
+            if (fits && ldx % 4 == 0 && Ly.ld % 4 == 0 && Ly.n_in % 4 == 0 && aligned(X, 16) && aligned(Ly.W, 16)) {
                 if (!m->batch_ready) {
-                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_vec<true>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kVecLdsBytes));
-                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_ws<true>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWsLdsBytes));
                     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes));
                     m->batch_ready = true;
                 }
-                static const int ws = getenv("DBSN_BATCH_WS") ? atoi(getenv("DBSN_BATCH_WS")) : 2;
-                if (ws == 2 && Ly.n_in % 4 == 0) {
-                    const int nt = (int)(grid.x * grid.y);
-                    const float* zeros = reinterpret_cast<const float*>(m->err + kZerosAt);
-                    hipLaunchKernelGGL(k_layer_batch_dma<true>, dim3(std::min(nt, m->cus)), dim3(kWsThreads), kDmaLdsBytes,
-                                       m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, (int)grid.x, nt,
-                                       zeros);
-                } else if (ws) {
-                    const int nt = (int)(grid.x * grid.y);
-                    hipLaunchKernelGGL(k_layer_batch_ws<true>, dim3(std::min(nt, m->cus)), dim3(kWsThreads), kWsLdsBytes,
-                                       m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, (int)grid.x, nt);
-                } else {
-                // persistent workgroups that take tiles from counter l, zeroed at the start of the pass
-                const int ntiles = (int)(grid.x * grid.y);
-                const int groups = std::min(ntiles, kVecPerCu * m->cus);
-                hipLaunchKernelGGL(k_layer_batch_vec<true>, dim3(groups), dim3(kBatchThreads), kVecLdsBytes, m->stream,
-                                   X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, counters + l, (int)grid.x,
-                                   ntiles);
-                }
+                const int nt = (int)(grid.x * grid.y);
+                const float* zeros = reinterpret_cast<const float*>(m->err + kZerosAt);
+                hipLaunchKernelGGL(k_layer_batch_dma<true>, dim3(std::min(nt, m->cus)), dim3(kDmaThreads), kDmaLdsBytes,
+                                   m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, (int)grid.x, nt,
+                                   zeros);
             } else {
                 hipLaunchKernelGGL(k_layer_batch<true>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W,
                                    Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact);

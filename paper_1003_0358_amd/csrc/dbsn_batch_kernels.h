@@ -4,14 +4,13 @@
 // training step it belongs on the matrix cores: fp32 MFMA (products and sums in binary32, as
 // everywhere in this library), each weight tile read from memory once per 128 samples.
 //
-// One workgroup of 4 wavefronts computes a tile of 128 samples x 128 neurons; wavefront w owns the
-// 64 x 64 quadrant (w & 1, w >> 1) as 2 x 2 v_mfma_f32_32x32x2 accumulators (64 registers).  The k
-// dimension is walked in chunks of 16 staged in LDS (pitch 17: the operand reads, row = lane % 32,
-// k = lane / 32, fall in distinct banks), in two buffers used in turn: while the matrix
-// instructions work on one chunk, the next one is written to the other buffer and the one after
-// that is on its way from memory into registers, so a chunk costs one barrier and memory latency
-// hides behind the arithmetic.  Operand layout of the instruction: lane t supplies
-// A[i = t % 32][k = t / 32] and B[k = t / 32][j = t % 32]; result register r of lane t is
+// Two kernels compute it.  k_layer_batch_dma is the fast one and needs aligned rows;
+// k_layer_batch takes anything: one workgroup of 4 wavefronts per tile of 128 samples x 128
+// neurons, wavefront w on the 64 x 64 quadrant (w & 1, w >> 1) as 2 x 2 v_mfma_f32_32x32x2
+// accumulators, the k dimension in chunks of 16 staged element by element through two LDS buffers
+// (pitch 17: the operand reads, row = lane % 32, k = lane / 32, fall in distinct banks).
+// Operand layout of the instruction: lane t supplies A[i = t % 32][k = t / 32] and
+// B[k = t / 32][j = t % 32]; result register r of lane t is
 // D[i = r % 4 + 4 (t / 32) + 8 (r / 4)][j = t % 32].
 #pragma once
 #include <hip/hip_runtime.h>
@@ -27,20 +26,38 @@ constexpr int kBatchK = 16;             // k-chunk staged in LDS
 constexpr int kBatchPitch = kBatchK + 1;
 constexpr int kBatchThreads = 256;
 constexpr int kBatchRows = kBatchTile * kBatchK / kBatchThreads;   // elements of each operand tile a thread stages per chunk
-constexpr int kBatchSamples = 8192;     // samples per pass through the layers (sizes the activation buffers)
+constexpr int kBatchSamples = 16384;    // samples per pass through the layers (sizes the activation buffers)
+
+// The activation for the batched passes: act_fast with the hardware reciprocal (one ulp) in place
+// of the division, a third of the instructions; only class labels come out of these passes.
+__device__ __forceinline__ float act_batch(float a) {
+    const float t = kB * a;
+    const float at = fabsf(t);
+    const float e = __expf(2.0f * at);
+    const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+    const float t2 = t * t;
+    const float small = at * fmaf(t2, fmaf(t2, fmaf(t2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
+    const float r = (at < 0.125f) ? small : big;
+    return kA * copysignf(r, t);
+}
 
 // End of a tile for one wavefront: its 64 x 64 quadrant (2 x 2 accumulators, first sample s_base,
 // first neuron j_base) gets bias and activation and goes to Y.  The two bias values are pinned in
 // registers before the first guarded store: a guard that were the first to touch them would make
 // every later one wait for all memory operations in flight, the stores before it included, since
-// the compiler cannot know which guards were taken.
+// the compiler cannot know which guards were taken.  Addresses are 32-bit byte offsets from Y (a
+// pass's activations stay far below 4 GB): one addition per store.
 template <bool ACT>
 __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], const float* __restrict__ b,
                                                float* __restrict__ Y, int ldy, int S, int n_out, int s_base,
                                                int j_base, int lane) {
     const int jl = j_base + (lane & 31);
+    const int sl = s_base + 4 * (lane >> 5);
     float bj[2] = {b[min(jl, n_out - 1)], b[min(jl + 32, n_out - 1)]};
     asm volatile("" : "+v"(bj[0]), "+v"(bj[1]));
+    char* Yb = reinterpret_cast<char*>(Y);
+    const unsigned pitch = 4u * (unsigned)ldy;
+    const unsigned at = (unsigned)sl * pitch + 4u * (unsigned)jl;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
         const int j = jl + 32 * c;
@@ -48,10 +65,10 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], cons
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int s = s_base + 32 * a + (r & 3) + 4 * (lane >> 5) + 8 * (r >> 2);
-                if (j < n_out && s < S) {
+                const int ds = 32 * a + (r & 3) + 8 * (r >> 2);   // sample of this element, from the lane's first
+                if (j < n_out && sl + ds < S) {
                     const float v = acc[a][c][r] + bj[c];
-                    Y[(size_t)s * ldy + j] = ACT ? act_fast(v) : v;
+                    *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_batch(v) : v;
                 }
             }
     }
@@ -134,338 +151,40 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
     store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
 }
 
-// The same layer for operands whose rows start on 16-byte boundaries (every activation buffer of
-// the library, and the caller's samples when their length is a multiple of four): 128-bit memory
-// and LDS operations throughout.  The k dimension is walked in chunks of 32; a thread brings four
-// float4 of each operand per chunk (eight lanes cover the 128 bytes of one row's chunk), rows past
-// the end of the operand are clamped to its last row (computed, never stored), and only the last,
-// ragged chunk masks by element.  LDS rows have a pitch of 36 floats, so the float4 that 16
-// consecutive lanes read (same k, consecutive rows) fall in disjoint banks.  The matrix instruction
-// sums over two k per issue, one from each half of the wavefront; which two is free as long as both
-// operands agree, so lanes 0..31 walk the first 16 k of the chunk and lanes 32..63 the second 16,
-// and one float4 read per operand quadrant feeds four instructions: per chunk and wavefront 16 LDS
-// reads for 64 matrix instructions.
+// The same layer at speed, for operands whose rows start on 16-byte boundaries and n_in % 4 == 0
+// (every activation buffer of the library; the caller's samples when their length is a multiple of
+// four).  A persistent workgroup per compute unit walks tiles blockIdx.x, + gridDim.x, ... of
+// 128 samples x 128 neurons, the k dimension in chunks of 32, and is WAVE-SPECIALISED: four
+// CONSUMER wavefronts (one per SIMD) only read operands from LDS and issue matrix instructions,
+// each on a 64 x 64 quadrant (2 x 2 accumulators of v_mfma_f32_32x32x2); four PRODUCER wavefronts
+// only move chunks from memory into a ring of four LDS stages.  Both choices come from
+// measurements on this chip: a wavefront issues in order, so every memory instruction that waits
+// for its queue holds back the matrix instructions behind it, and while the matrix instructions
+// of a SIMD run, loads that return into vector registers of that SIMD take three to four times
+// as long.  So the producers' loads never touch registers: global_load_lds_dwordx4 writes the
+// 64 x 16 bytes of a wavefront's load to 1 KB of consecutive LDS, with a scalar base and a
+// constant 32-bit offset per lane (no vector arithmetic in the steady state).
 //
-// Launch shape: workgroups are persistent, two per compute unit (that is what the LDS footprint
-// admits), and take tiles from a counter in device memory until none is left.  Two resident
-// workgroups overlap each other's memory phases, tile prologues and epilogues with matrix
-// instructions, which one workgroup alone cannot do (a wavefront issues in order), and handing
-// out tiles on demand leaves at most one tile's time of imbalance at the end of a layer, where a
-// grid of one workgroup per tile pays a whole round of the dispatcher.  *counter must be zero at
-// launch; tile t covers columns 128 (t % nx) and samples 128 (t / nx).
+// That fixes the LDS layout: rows of 32 floats without padding, eight rows per load.  Bank
+// conflicts are avoided by permuting the float4 inside each row instead: slot p of row r holds the
+// chunk's float4 number p ^ ((r >> 1) & 7), which each lane arranges by the global address it
+// supplies; a consumer reads float4 q of row r at slot q ^ ((r >> 1) & 7), and the 16 rows
+// r .. r + 15 that neighbouring lanes read then fall in 16 different bank groups.  The matrix
+// instruction sums over two k per issue, one from each half of the wavefront; which two is free as
+// long as both operands agree, so lanes 0..31 walk the first 16 k of the chunk and lanes 32..63
+// the second 16, and one float4 read per operand quadrant feeds four instructions: per chunk and
+// consumer 16 LDS reads for 64 matrix instructions, each read issued one group of 16 ahead.
+//
+// Pipeline: chunks are numbered straight through the tiles of a workgroup.  In iteration i the
+// consumers work on chunk i in stage i % 4 (and, at its end, read the first operands of chunk
+// i + 1); the producers start the loads of chunk i + 3 into the stage that chunk i - 1 left at the
+// last barrier, wait for those of chunk i + 2, issued an iteration earlier, and join the barrier
+// that closes the iteration.  So the ring is already filling for the next tile while the
+// consumers store the current one.  A float4 of the weights past n_in comes from 16 zero bytes at
+// `zeros`, the matching one of the other operand from the start of its row (finite, times zero).
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int kDmaThreads = 512;
 constexpr int kVecK = 32;
-constexpr int kVecPitch = kVecK + 4;
-constexpr int kVecOperand = kBatchTile * kVecPitch;                         // floats of one staged operand tile
-constexpr int kVecLoads = kBatchTile * (kVecK / 4) / kBatchThreads;          // float4 per operand, thread and chunk
-constexpr size_t kVecLdsBytes = sizeof(float) * 4 * kVecOperand;             // two operands, two buffers
-constexpr int kVecPerCu = 2;                                                 // resident workgroups per compute unit
-
-template <bool ACT>
-__global__ __launch_bounds__(kBatchThreads, 2) void k_layer_batch_vec(const float* __restrict__ X, int ldx, int S,
-                                                                       const float* __restrict__ W, int ldw,
-                                                                       const float* __restrict__ b, int n_in,
-                                                                       int n_out, float* __restrict__ Y, int ldy,
-                                                                       int* __restrict__ counter, int nx, int ntiles) {
-    extern __shared__ __attribute__((aligned(16))) float lds_batch[];
-    __shared__ int tile_next;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int sw = (wave & 1) * 64, jw = (wave >> 1) * 64;
-    // staging: float4 number tq of the chunk, rows tr, tr + 32, ...
-    const int tq = threadIdx.x & 7, tr = threadIdx.x >> 3;
-    constexpr int kRowStep = kBatchThreads / 8;
-    const int nchunks = (n_in + kVecK - 1) / kVecK;
-    const int rd = (lane & 31) * kVecPitch + (lane >> 5) * (kVecK / 2);
-    for (;;) {
-        if (threadIdx.x == 0) tile_next = atomicAdd(counter, 1);
-        __syncthreads();
-        const int tile = tile_next;   // (the barriers inside the tile keep the next write behind this read)
-        if (tile >= ntiles) break;
-        const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
-        floatx16 acc[2][2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-        unsigned xoff[kVecLoads], woff[kVecLoads];
-#pragma unroll
-        for (int r = 0; r < kVecLoads; ++r) {
-            const int row = tr + kRowStep * r;
-            xoff[r] = (unsigned)min(s0 + row, S - 1) * (unsigned)ldx + 4u * tq;
-            woff[r] = (unsigned)min(j0 + row, n_out - 1) * (unsigned)ldw + 4u * tq;
-        }
-        floatx4 xr[kVecLoads], wrg[kVecLoads];
-        auto fetch = [&](int k0) {
-            const float* __restrict__ Xk = X + k0;
-            const float* __restrict__ Wk = W + k0;
-#pragma unroll
-            for (int r = 0; r < kVecLoads; ++r) {
-                xr[r] = *reinterpret_cast<const floatx4*>(Xk + xoff[r]);
-                wrg[r] = *reinterpret_cast<const floatx4*>(Wk + woff[r]);
-            }
-        };
-        // the chunk that reaches past n_in: float4 wholly past the end are not read, the one that
-        // straddles it is (its row is padded to a multiple of four) and loses the elements past the end
-        auto fetch_tail = [&](int k0) {
-            const int rem = n_in - k0 - 4 * tq;
-            const unsigned kk = rem > 0 ? (unsigned)k0 : 0u - 4u * tq;   // past the end: the row's first float4, unused
-#pragma unroll
-            for (int r = 0; r < kVecLoads; ++r) {
-                floatx4 x = *reinterpret_cast<const floatx4*>(X + (xoff[r] + kk));
-                floatx4 w = *reinterpret_cast<const floatx4*>(W + (woff[r] + kk));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    x[e] = rem > e ? x[e] : 0.0f;
-                    w[e] = rem > e ? w[e] : 0.0f;
-                }
-                xr[r] = x;
-                wrg[r] = w;
-            }
-        };
-        auto fetch_any = [&](int k0) {
-            if (k0 + kVecK <= n_in) fetch(k0);
-            else fetch_tail(k0);
-        };
-        auto stage = [&](int buf) {
-            float* xs = lds_batch + buf * 2 * kVecOperand;
-            float* ws = xs + kVecOperand;
-#pragma unroll
-            for (int r = 0; r < kVecLoads; ++r) {
-                const int at = (tr + kRowStep * r) * kVecPitch + 4 * tq;
-                *reinterpret_cast<floatx4*>(xs + at) = xr[r];
-                *reinterpret_cast<floatx4*>(ws + at) = wrg[r];
-            }
-        };
-        fetch_any(0);
-        stage(0);   // (the last tile's reads ended before its closing barrier)
-        __syncthreads();
-        if (nchunks > 1) fetch_any(kVecK);
-        for (int c = 0; c < nchunks; ++c) {
-            const int cur = c & 1;
-            // the other buffer was last read one chunk ago, before the barrier every wavefront has passed
-            if (c + 1 < nchunks) stage(cur ^ 1);
-            if (c + 2 < nchunks) fetch_any((c + 2) * kVecK);   // in flight during the matrix instructions below
-            const float* xs = lds_batch + cur * 2 * kVecOperand + sw * kVecPitch + rd;
-            const float* ws = lds_batch + cur * 2 * kVecOperand + kVecOperand + jw * kVecPitch + rd;
-#pragma unroll
-            for (int m = 0; m < kVecK / 8; ++m) {
-                const floatx4 a0 = *reinterpret_cast<const floatx4*>(xs + 4 * m);
-                const floatx4 a1 = *reinterpret_cast<const floatx4*>(xs + 32 * kVecPitch + 4 * m);
-                const floatx4 w0 = *reinterpret_cast<const floatx4*>(ws + 4 * m);
-                const floatx4 w1 = *reinterpret_cast<const floatx4*>(ws + 32 * kVecPitch + 4 * m);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w0[e], acc[0][0], 0, 0, 0);
-                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w1[e], acc[0][1], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w0[e], acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w1[e], acc[1][1], 0, 0, 0);
-                }
-            }
-            __syncthreads();
-        }
-        store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
-    }
-}
-
-// Wave-specialised form of the same layer.  A wavefront issues its instructions in order, so in
-// the kernel above every wide memory or LDS-write instruction that waits for its queue also holds
-// back the matrix instructions behind it; here they are in different wavefronts.  A workgroup has
-// eight: four CONSUMERS (one per SIMD) that only read operands from LDS and issue matrix
-// instructions, each on a 64 x 64 quadrant of the 128 x 128 tile, and four PRODUCERS that bring
-// the k-chunks from memory into a ring of three LDS stages.  In iteration i the consumers work on
-// chunk i in stage i % 3 while the producers write chunk i + 2 (loaded one iteration earlier) into
-// stage (i + 2) % 3, last read in iteration i - 1, and start the loads of chunk i + 3; one barrier
-// closes the iteration.  Chunks are numbered straight through the tiles of a workgroup (tile
-// blockIdx.x, then + gridDim.x, ...), so the producers are already filling the ring for the next
-// tile while the consumers finish and store the current one.  One workgroup per compute unit
-// (the ring takes 108 KB of LDS).
-constexpr int kWsThreads = 512;
-constexpr int kWsStages = 3;
-constexpr int kWsAhead = 3;   // iterations between the issue of a chunk's loads and their write into the ring
-constexpr size_t kWsLdsBytes = sizeof(float) * kWsStages * 2 * kVecOperand;
-
-template <bool ACT>
-__global__ __launch_bounds__(kWsThreads) void k_layer_batch_ws(const float* __restrict__ X, int ldx, int S,
-                                                                const float* __restrict__ W, int ldw,
-                                                                const float* __restrict__ b, int n_in, int n_out,
-                                                                float* __restrict__ Y, int ldy, int nx, int ntiles) {
-    extern __shared__ __attribute__((aligned(16))) float lds_batch[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: the roles branch on the scalar unit)
-    const bool producer = wave >= 4;
-    const int nchunks = (n_in + kVecK - 1) / kVecK;
-    const int my_tiles = ((int)blockIdx.x < ntiles) ? (ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
-    const int total = my_tiles * nchunks;   // iterations of this workgroup
-    if (total == 0) return;                 // (the whole workgroup: no barrier is left behind)
-    // the producers' loop is unrolled over their register sets; both roles run this many barriers
-    const int padded = (total + kWsAhead - 1) / kWsAhead * kWsAhead;
-
-    // ---- producer state: the next chunk to load is chunk pchunk of tile number ptile in the
-    // workgroup's sequence; registers -> stage
-    const int pt = threadIdx.x & 255;
-    const int tq = pt & 7, tr = pt >> 3;
-    constexpr int kRowStep = 256 / 8;
-    floatx4 xr[kWsAhead][kVecLoads], wrg[kWsAhead][kVecLoads];   // register sets that loads in flight target
-    int rem[kWsAhead];
-    unsigned xoff[kVecLoads], woff[kVecLoads];
-    int ptile = 0, pchunk = 0, pleft = total;   // pleft: chunks not loaded yet
-    auto tile_offsets = [&]() {
-        const int tile = (int)blockIdx.x + ptile * (int)gridDim.x;
-        const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
-#pragma unroll
-        for (int r = 0; r < kVecLoads; ++r) {
-            const int row = tr + kRowStep * r;
-            xoff[r] = (unsigned)min(s0 + row, S - 1) * (unsigned)ldx + 4u * tq;
-            woff[r] = (unsigned)min(j0 + row, n_out - 1) * (unsigned)ldw + 4u * tq;
-        }
-    };
-    // Loads the next chunk of the sequence.  A float4 wholly past n_in is not read (the row's first
-    // one is, in its place); of the weights, every element past n_in becomes zero on its way into
-    // LDS, so the matching element of the other operand only has to be finite: stale activations in
-    // the padding of a row, or whatever the replaced read returned.  Straight-line code, the same
-    // for every chunk, and nothing touches the loaded registers before the write into LDS, so the
-    // loads really stay in flight for kWsAhead iterations.
-    auto load_next = [&](floatx4 (&xr)[kVecLoads], floatx4 (&wrg)[kVecLoads], int& rem) {
-        const int k0 = pchunk * kVecK;
-        rem = n_in - k0 - 4 * tq;   // elements of this thread's float4 that lie inside the row
-        const unsigned kk = rem > 0 ? (unsigned)k0 : 0u - 4u * tq;
-#pragma unroll
-        for (int r = 0; r < kVecLoads; ++r) {
-            xr[r] = *reinterpret_cast<const floatx4*>(X + (xoff[r] + kk));
-            wrg[r] = *reinterpret_cast<const floatx4*>(W + (woff[r] + kk));
-        }
-        // on to the next chunk; past the end the last chunk is loaded again (and never used)
-        if (pleft > 1) {
-            --pleft;
-            if (++pchunk == nchunks) {
-                pchunk = 0;
-                ++ptile;
-                tile_offsets();
-            }
-        }
-    };
-    auto store_chunk = [&](int stage, const floatx4 (&xr)[kVecLoads], const floatx4 (&wrg)[kVecLoads], int rem) {
-        float* xs = lds_batch + stage * 2 * kVecOperand;
-        float* ws = xs + kVecOperand;
-#pragma unroll
-        for (int r = 0; r < kVecLoads; ++r) {
-            const int at = (tr + kRowStep * r) * kVecPitch + 4 * tq;
-            floatx4 w = wrg[r];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = rem > e ? w[e] : 0.0f;
-            *reinterpret_cast<floatx4*>(xs + at) = xr[r];
-            *reinterpret_cast<floatx4*>(ws + at) = w;
-        }
-    };
-
-    // The two roles run separate loops that meet at the barriers: one after the fill, one per
-    // iteration, `total` of them in either loop.
-    if (producer) {
-        // fill: chunks 0 and 1 into their stages, chunks 2 .. 2 + kWsAhead - 1 on their way
-        tile_offsets();
-        load_next(xr[0], wrg[0], rem[0]);
-        store_chunk(0, xr[0], wrg[0], rem[0]);
-        load_next(xr[0], wrg[0], rem[0]);
-        store_chunk(1, xr[0], wrg[0], rem[0]);
-#pragma unroll
-        for (int d = 0; d < kWsAhead; ++d) load_next(xr[d], wrg[d], rem[d]);
-        __syncthreads();
-        int stage = 0;   // i % 3
-        for (int i = 0; i < padded; i += kWsAhead) {
-#pragma unroll
-            for (int d = 0; d < kWsAhead; ++d) {
-                // iteration i + d: chunk i + d + 2, loaded kWsAhead iterations ago, into stage
-                // (i + d + 2) % 3; its register set then takes chunk i + d + 2 + kWsAhead (past the
-                // end: repeats of the last chunk, into stages nobody reads any more)
-                store_chunk(stage == 0 ? kWsStages - 1 : stage - 1, xr[d], wrg[d], rem[d]);
-                load_next(xr[d], wrg[d], rem[d]);
-                stage = stage == kWsStages - 1 ? 0 : stage + 1;
-                __syncthreads();
-            }
-        }
-        return;
-    }
-
-    const int sw = (wave & 1) * 64, jw = ((wave >> 1) & 1) * 64;
-    const int rd = (lane & 31) * kVecPitch + (lane >> 5) * (kVecK / 2);
-    const float* xs0 = lds_batch + sw * kVecPitch + rd;
-    const float* ws0 = lds_batch + kVecOperand + jw * kVecPitch + rd;
-    __syncthreads();
-    // operands of the next group of matrix instructions, read one group ahead
-    floatx4 pa0 = *reinterpret_cast<const floatx4*>(xs0);
-    floatx4 pa1 = *reinterpret_cast<const floatx4*>(xs0 + 32 * kVecPitch);
-    floatx4 pw0 = *reinterpret_cast<const floatx4*>(ws0);
-    floatx4 pw1 = *reinterpret_cast<const floatx4*>(ws0 + 32 * kVecPitch);
-    int stage = 0;   // i % 3 of iteration i
-    for (int t = 0; t < my_tiles; ++t) {
-        floatx16 acc[2][2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-        for (int cc = 0; cc < nchunks; ++cc) {
-            const int stage1 = stage == kWsStages - 1 ? 0 : stage + 1;
-            const float* xs = xs0 + stage * 2 * kVecOperand;
-            const float* ws = ws0 + stage * 2 * kVecOperand;
-            // the first group of the next chunk sits in stage (i + 1) % 3, complete since the last barrier
-            const float* xn = xs0 + stage1 * 2 * kVecOperand;
-            const float* wn = ws0 + stage1 * 2 * kVecOperand;
-#pragma unroll
-            for (int m = 0; m < kVecK / 8; ++m) {
-                const floatx4 a0 = pa0, a1 = pa1, w0 = pw0, w1 = pw1;
-                if (m + 1 < kVecK / 8) {
-                    pa0 = *reinterpret_cast<const floatx4*>(xs + 4 * (m + 1));
-                    pa1 = *reinterpret_cast<const floatx4*>(xs + 32 * kVecPitch + 4 * (m + 1));
-                    pw0 = *reinterpret_cast<const floatx4*>(ws + 4 * (m + 1));
-                    pw1 = *reinterpret_cast<const floatx4*>(ws + 32 * kVecPitch + 4 * (m + 1));
-                } else {
-                    pa0 = *reinterpret_cast<const floatx4*>(xn);
-                    pa1 = *reinterpret_cast<const floatx4*>(xn + 32 * kVecPitch);
-                    pw0 = *reinterpret_cast<const floatx4*>(wn);
-                    pw1 = *reinterpret_cast<const floatx4*>(wn + 32 * kVecPitch);
-                }
-                __builtin_amdgcn_sched_barrier(0);   // the reads go out before the matrix instructions, not after
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w0[e], acc[0][0], 0, 0, 0);
-                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w1[e], acc[0][1], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w0[e], acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w1[e], acc[1][1], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            stage = stage1;
-            __syncthreads();
-        }
-        // the tile is complete: bias, activation, store (the producers are already filling the ring
-        // for the next tile)
-        const int tile = (int)blockIdx.x + t * (int)gridDim.x;
-        const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
-        store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
-    }
-    for (int i = total; i < padded; ++i) __syncthreads();   // the barriers of the producers' padding iterations
-}
-
-// The wave-specialised layer with the producers loading straight into LDS.  While the matrix
-// instructions of a SIMD run, loads that return into vector registers of the same SIMD crawl (the
-// kernel above measures it: the same producers finish an iteration three to four times faster
-// when the consumers' matrix instructions are taken out), so here the data never passes through
-// registers: global_load_lds_dwordx4 writes the 64 x 16 bytes of a wavefront's load to 1 KB of
-// consecutive LDS.  That fixes the LDS layout: rows of 32 floats without padding, eight rows per
-// load.  Bank conflicts are avoided by permuting the float4 inside each row instead: slot p of
-// row r holds the chunk's float4 number p ^ ((r >> 1) & 7), which each lane arranges by the
-// global address it supplies; a consumer reads float4 q of row r at slot q ^ ((r >> 1) & 7), and
-// the 16 rows r .. r + 15 that neighbouring lanes read then fall in 16 different bank groups.
-// Four stages of 32 KB: in iteration i the consumers work on chunk i (and, at its end, read the
-// first operands of chunk i + 1), the producers start the loads of chunk i + 3 into the stage
-// chunk i - 1 left at the last barrier and wait for those of chunk i + 2, issued an iteration
-// earlier, before they join the barrier.  A float4 of the weights past n_in comes from 16 zero
-// bytes at `zeros`, the matching one of the other operand from the start of its row (finite,
-// times zero).  Needs n_in % 4 == 0 on top of the alignment of the 128-bit kernels.
 constexpr int kDmaStages = 4;
 constexpr int kDmaOperand = kBatchTile * kVecK;   // floats of one operand tile of a stage, unpadded
 constexpr size_t kDmaLdsBytes = sizeof(float) * kDmaStages * 2 * kDmaOperand;
@@ -475,7 +194,7 @@ constexpr size_t kDmaLdsBytes = sizeof(float) * kDmaStages * 2 * kDmaOperand;
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 template <bool ACT>
-__global__ __launch_bounds__(kWsThreads) void k_layer_batch_dma(const float* __restrict__ X, int ldx, int S,
+__global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __restrict__ X, int ldx, int S,
                                                                  const float* __restrict__ W, int ldw,
                                                                  const float* __restrict__ b, int n_in, int n_out,
                                                                  float* __restrict__ Y, int ldy, int nx, int ntiles,
@@ -582,6 +301,10 @@ __global__ __launch_bounds__(kWsThreads) void k_layer_batch_dma(const float* __r
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+        // nothing is outstanding on the LDS / scalar-memory counter when the chunk loop is entered:
+        // with scalar loads possibly in flight the compiler would have to drain the counter before
+        // the first matrix instruction of every chunk, the reads just issued included
+        __builtin_amdgcn_s_waitcnt(0xc07f);
         for (int cc = 0; cc < nchunks; ++cc) {
             const int stage1 = (stage + 1) & (kDmaStages - 1);
             const float* xs = xs0 + stage * 2 * kDmaOperand;
@@ -622,13 +345,6 @@ __global__ __launch_bounds__(kWsThreads) void k_layer_batch_dma(const float* __r
         const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
         store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
     }
-}
-
-// Zeroes the tile counters of a pass (a kernel rather than a memset, so that a caller may record
-// the classification pass in a graph).
-__global__ void k_zero_counters(int* __restrict__ counters, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) counters[i] = 0;
 }
 
 // Output layer of the classification pass: labels[s] = index of the largest pre-activation

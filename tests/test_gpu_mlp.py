@@ -215,18 +215,21 @@ def _margins(oracle, sizes, p, X):
     return np.array(out)
 
 
-def test_classify_batches_ragged_shapes(oracle):
-    """The batched forward pass: widths that are no multiple of the 128 x 128 tiles or of the k-chunk,
-    more samples than one pass takes (8192) plus a ragged tail, against the oracle and against the
-    one-sample forward call."""
+@pytest.mark.parametrize("sizes", [[37, 70, 33, 7], [20, 136, 260, 36, 7]], ids=["odd-widths", "multiples-of-four"])
+def test_classify_batches_ragged_shapes(oracle, sizes):
+    """The batched forward pass: widths that are no multiple of the 128 x 128 tiles or of the k-chunk
+    (odd ones, which go through the kernel that stages by element, and multiples of four, which go
+    through the one that loads straight into LDS, down to a layer with fewer inputs than one
+    chunk), more samples than one pass takes (16384) plus a ragged tail, against the oracle and
+    against the one-sample forward call."""
     torch = _torch()
-    sizes = [37, 70, 33, 7]
-    n = 8300
+    n = 16384 + 108
+    L = len(sizes) - 1
     rng = np.random.default_rng(5)
     X = rng.uniform(-1, 1, (n, sizes[0])).astype(np.float32)
     m = _mk(sizes, 1, seed=2)
     # weights large enough for the classes to differ clearly
-    for l in range(1, 4):
+    for l in range(1, L + 1):
         W = rng.normal(0, 0.5, (sizes[l], sizes[l - 1])).astype(np.float32)
         b = rng.normal(0, 0.5, sizes[l]).astype(np.float32)
         m.set_weights(l, W, b)
@@ -235,11 +238,11 @@ def test_classify_batches_ragged_shapes(oracle):
     got = m.classify(xs).cpu().numpy()
     ref = oracle.classify(sizes, p, X, "f64")
     clear = _margins(oracle, sizes, p, X[:400]) > 1e-4
-    assert clear.sum() >= 390
+    assert clear.sum() >= 380
     assert np.array_equal(got[:400][clear], ref[:400][clear])
-    assert (got != ref).sum() <= 2            # the rest: only decisions within rounding may differ
+    assert (got != ref).sum() <= 4            # the rest: only decisions within rounding may differ
     assert len(np.unique(got)) >= 5
-    for s in (0, 127, 128, 8191, 8192, 8299):   # tile and pass boundaries
+    for s in (0, 127, 128, 16383, 16384, n - 1):   # tile and pass boundaries
         probs = m.forward(xs[s]).cpu().numpy()
         assert int(np.argmax(probs)) == int(got[s]) or np.sort(probs)[-1] - np.sort(probs)[-2] < 1e-5
     assert m.classify(xs[:1]).cpu().tolist() == [int(got[0])]
