@@ -58,6 +58,21 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], cons
     char* Yb = reinterpret_cast<char*>(Y);
     const unsigned pitch = 4u * (unsigned)ldy;
     const unsigned at = (unsigned)sl * pitch + 4u * (unsigned)jl;
+    if (s_base + 64 <= S && j_base + 64 <= n_out) {
+        // the quadrant lies inside the matrix (a uniform test): no guards, one basic block, so the 64
+        // independent activations interleave instead of each waiting out its own latencies
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ds = 32 * a + (r & 3) + 8 * (r >> 2);   // sample of this element, from the lane's first
+                    const float v = acc[a][c][r] + bj[c];
+                    *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_batch(v) : v;
+                }
+        return;
+    }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
         const int j = jl + 32 * c;
@@ -65,7 +80,7 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], cons
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int ds = 32 * a + (r & 3) + 8 * (r >> 2);   // sample of this element, from the lane's first
+                const int ds = 32 * a + (r & 3) + 8 * (r >> 2);
                 if (j < n_out && sl + ds < S) {
                     const float v = acc[a][c][r] + bj[c];
                     *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_batch(v) : v;
