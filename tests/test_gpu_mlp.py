@@ -267,6 +267,37 @@ def test_classify_full_size_net(oracle):
     m.close()
 
 
+def test_classify_full_size_net_in_bench_configuration(oracle):
+    """The 12 M-weight net over the bench's 10,000 images (79 rows of tiles, up to seven tiles per
+    persistent workgroup, a last row of tiles with 16 samples): the oracle classifies a sample of
+    them one by one, spread over the tile rows and the ends; the whole set must also classify the
+    same way when it is cut into pieces that move every sample to another place in its tile."""
+    torch = _torch()
+    n = 10000
+    img, _ = datagen.stroke_images(n, seed=1)
+    X = datagen.to_inputs(img)
+    m = _mk(NET4, 1, seed=4)
+    Xt, yt = _data(30, seed=22)
+    m.bp_steps(torch.from_numpy(Xt).cuda(), torch.from_numpy(yt).cuda(), 1e-2)
+    p = m.get_params()
+    xs = torch.from_numpy(X).cuda()
+    got = m.classify(xs).cpu().numpy()
+    rng = np.random.default_rng(9)
+    pick = np.unique(np.concatenate([[0, 1, 127, 128, 4095, 4096, 8191, 8192, 9983, 9984, 9998, 9999],
+                                     rng.integers(0, n, 52)]))
+    oracle.set_threads(8)
+    ref = oracle.classify(NET4, p, X[pick], "f64")
+    clear = _margins(oracle, NET4, p, X[pick]) > 1e-4
+    oracle.set_threads(1)
+    assert clear.sum() >= len(pick) - 6
+    assert np.array_equal(got[pick][clear], ref[clear])
+    # the same samples at other tile positions: a shifted cut of the set
+    pieces = [(0, 37), (37, 5037), (5037, 5100), (5100, n)]
+    again = np.concatenate([m.classify(xs[a:b]).cpu().numpy() for a, b in pieces])
+    assert (again != got).sum() == 0
+    m.close()
+
+
 def test_set_get_weights_roundtrip_and_errors():
     from paper_1003_0358_amd import binding
     torch = _torch()
