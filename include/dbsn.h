@@ -147,7 +147,13 @@ int32_t dbsn_bp_step(dbsn_mlp* mlp, const float* sample_dev, int32_t label, floa
 int32_t dbsn_forward(dbsn_mlp* mlp, const float* sample_dev, float* probs_dev);
 
 /* Forward-only classification of n samples: labels_out_dev[s] = index of the largest output
- * (lowest index on ties), as used for validation and test passes (sections "Data", "Results"). */
+ * (lowest index on ties), as used for validation and test passes (sections "Data", "Results").
+ * samples_dev: [n][sizes[0]] float, labels_out_dev: [n] int32, both device memory, 4-byte aligned.
+ * The samples go through the layers 16384 at a time as dense products on the fp32 matrix units:
+ * products and sums in binary32 like dbsn_forward, in another order, so the two agree wherever the
+ * two largest outputs differ by more than rounding.  Fastest when sizes[0] is a multiple of 4 and
+ * samples_dev is 16-byte aligned (other shapes take a slower kernel, same results).  Asynchronous
+ * on the network's stream; n == 0 is a no-op. */
 int32_t dbsn_classify(dbsn_mlp* mlp, const float* samples_dev, int64_t n, int32_t* labels_out_dev);
 
 /* Message for the last error on this host thread ("" if none). */
