@@ -569,8 +569,15 @@ int32_t dbsn_deform_batch_beta(const dbsn_deform_params* p, const uint8_t* src_d
     a.first_index = first_index;
     a.n = n;
     const int blocks = (int)(n < 65536 ? n : 65536);
-    hipLaunchKernelGGL(k_deform, dim3(blocks), dim3(kDeformThreads), 0, static_cast<hipStream_t>(hip_stream), a,
-                       src_dev, dst_dev);
+    // the paper's 21 taps have a kernel of their own, same results (DBSN_DEFORM_GENERIC=1 keeps
+    // the general kernel, for comparing the two)
+    const char* generic = getenv("DBSN_DEFORM_GENERIC");
+    if (p->ktaps == 21 && !(generic && atoi(generic) != 0))
+        hipLaunchKernelGGL(k_deform_taps<21>, dim3(blocks), dim3(kDeformThreads), 0, static_cast<hipStream_t>(hip_stream),
+                           a, src_dev, dst_dev);
+    else
+        hipLaunchKernelGGL(k_deform, dim3(blocks), dim3(kDeformThreads), 0, static_cast<hipStream_t>(hip_stream), a,
+                           src_dev, dst_dev);
     HIP_TRY(hipGetLastError());
     return DBSN_OK;
 }

@@ -118,4 +118,135 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
     }
 }
 
+// The same deformation with the number of taps known at compile time, for the 21 taps the paper
+// uses.  k_deform above spends most of its instructions around the convolutions (per tap and
+// field: a bounds test, an index, an LDS read, a tap fetch for one multiply-add).  Here the fields
+// live in LDS lines padded with zeros on both sides (no bounds test: a tap outside the image adds
+// an exact zero, where k_deform adds nothing, so the sums are the same numbers), a thread computes
+// four neighbouring outputs of both fields from one window of 4 + 2R values read as float4 (one
+// LDS read per 14 multiply-adds), the taps sit in scalar registers, and the row pass writes its
+// result transposed, so that the column pass is the same walk along a line.  Every sum runs over
+// the taps in the order of k_deform: the two kernels agree bit for bit.
+constexpr int kPadLine = 52;   // floats per padded line: 13 float4, and 52 * c mod 64 visits 16 bank groups
+
+template <int KT>
+__global__ __launch_bounds__(kDeformThreads, 4) void k_deform_taps(DeformArgs a, const uint8_t* __restrict__ src,
+                                                                 float* __restrict__ dst) {
+    constexpr int R = (KT - 1) / 2;
+    constexpr int kWin = 4 + 2 * R;                 // values a run of four outputs needs
+    static_assert(KT == 2 * R + 1 && kWin % 4 == 0 && kSide + 2 * R <= kPadLine, "window of whole float4 inside a line");
+    constexpr int kRuns = kSide / 4;                // runs of four outputs per line
+    constexpr int kItems = kSide * kRuns;           // (line, run) pairs: 196 of the 256 threads work
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ float img[kPix];
+    __shared__ __attribute__((aligned(16))) float fld[2][kSide][kPadLine];   // raw fields: line r, pixel c at [R + c]
+    __shared__ __attribute__((aligned(16))) float row[2][kSide][kPadLine];   // after the row pass, transposed: line c, pixel r at [R + r]
+    __shared__ float aff[6];               // linear part p, q, r, t (X' = p u + q v, Y' = r u + t v), then sx, sy
+    for (int i = threadIdx.x; i < 2 * kSide * kPadLine; i += kDeformThreads) {
+        (&fld[0][0][0])[i] = 0.0f;   // the padding stays zero from here on
+        (&row[0][0][0])[i] = 0.0f;
+    }
+    float w[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) w[t] = a.taps[t];
+    const int line = threadIdx.x / kRuns, run = threadIdx.x - line * kRuns;   // row pass: image row, run of columns
+    const int crun = threadIdx.x / kSide, ccol = threadIdx.x - crun * kSide;   // column pass: run of rows, image column
+    __syncthreads();
+
+    for (long long k = blockIdx.x; k < a.n; k += gridDim.x) {
+        const uint64_t key = rng_key(a.seed, a.first_index + (uint64_t)k);
+        const uint8_t* s = src + k * kPix;
+        for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
+            const int r = i / kSide, c = i - r * kSide;
+            img[i] = (float)s[i];
+            fld[0][r][R + c] = rng_unit(rng_draw(key, 3ull + (uint64_t)i));
+            fld[1][r][R + c] = rng_unit(rng_draw(key, 3ull + (uint64_t)kPix + (uint64_t)i));
+        }
+        if (threadIdx.x == 0) {
+            // per-image scalars are formed in double and rounded once to float
+            const double u0 = (double)rng_unit(rng_draw(key, 0));
+            const double u1 = (double)rng_unit(rng_draw(key, 1));
+            const double u2 = (double)rng_unit(rng_draw(key, 2));
+            const double beta = a.beta_each ? (double)a.beta_each[k] : (double)a.beta_deg;
+            const double th = beta * u0 * (3.14159265358979323846 / 180.0);
+            if (a.shear) {
+                aff[0] = 1.0f; aff[1] = (float)tan(th); aff[2] = 0.0f; aff[3] = 1.0f;
+            } else {
+                aff[0] = (float)cos(th); aff[1] = (float)(-sin(th)); aff[2] = (float)sin(th); aff[3] = (float)cos(th);
+            }
+            aff[4] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
+            aff[5] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
+        }
+        __syncthreads();
+        // row pass: outputs (line, 4 run .. 4 run + 3) of both fields; the window starts at padded index 4 run
+        if (threadIdx.x < kItems) {
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                float in[kWin];
+#pragma unroll
+                for (int q = 0; q < kWin / 4; ++q) {
+                    const f4 v = *reinterpret_cast<const f4*>(&fld[f][line][4 * run + 4 * q]);
+                    in[4 * q] = v[0]; in[4 * q + 1] = v[1]; in[4 * q + 2] = v[2]; in[4 * q + 3] = v[3];
+                }
+#pragma unroll
+                for (int o = 0; o < 4; ++o) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) sum = fmaf(w[t], in[o + t], sum);
+                    row[f][4 * run + o][R + line] = sum;
+                }
+            }
+        }
+        __syncthreads();
+        const float lp = aff[0], lq = aff[1], lr = aff[2], lt = aff[3], scx = aff[4], scy = aff[5];
+        const float c0 = 0.5f * (float)(kSide - 1);
+        float* out = dst + k * kPix;
+        // column pass and resampling: pixels (4 crun .. 4 crun + 3, ccol)
+        if (threadIdx.x < kItems) {
+            float g[2][4];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                float in[kWin];
+#pragma unroll
+                for (int q = 0; q < kWin / 4; ++q) {
+                    const f4 v = *reinterpret_cast<const f4*>(&row[f][ccol][4 * crun + 4 * q]);
+                    in[4 * q] = v[0]; in[4 * q + 1] = v[1]; in[4 * q + 2] = v[2]; in[4 * q + 3] = v[3];
+                }
+#pragma unroll
+                for (int o = 0; o < 4; ++o) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) sum = fmaf(w[t], in[o + t], sum);
+                    g[f][o] = sum;
+                }
+            }
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int r = 4 * crun + o, c = ccol;
+                const float u = (float)c - c0, v = (float)r - c0;
+                // X = sx (p u + q v) + c0 + alpha * smoothed dx;  Y = sy (r u + t v) + c0 + alpha * smoothed dy
+                const float X = fmaf(a.alpha, g[0][o], fmaf(scx, fmaf(lp, u, lq * v), c0));
+                const float Y = fmaf(a.alpha, g[1][o], fmaf(scy, fmaf(lr, u, lt * v), c0));
+                const float xf = floorf(X), yf = floorf(Y);
+                const float wx = X - xf, wy = Y - yf;
+                float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
+                if (xf >= -1.0f && xf <= (float)kSide && yf >= -1.0f && yf <= (float)kSide) {
+                    const int x0 = (int)xf, y0 = (int)yf;
+                    const bool xa = (x0 >= 0 && x0 < kSide), xb = (x0 + 1 >= 0 && x0 + 1 < kSide);
+                    const bool ya = (y0 >= 0 && y0 < kSide), yb = (y0 + 1 >= 0 && y0 + 1 < kSide);
+                    if (ya && xa) p00 = img[y0 * kSide + x0];
+                    if (ya && xb) p01 = img[y0 * kSide + x0 + 1];
+                    if (yb && xa) p10 = img[(y0 + 1) * kSide + x0];
+                    if (yb && xb) p11 = img[(y0 + 1) * kSide + x0 + 1];
+                }
+                const float top = (1.0f - wx) * p00 + wx * p01;
+                const float bot = (1.0f - wx) * p10 + wx * p11;
+                const float val = (1.0f - wy) * top + wy * bot;
+                out[r * kSide + c] = val / 127.5f - 1.0f;   // section "Data": intensity/127.5 - 1
+            }
+        }
+        __syncthreads();   // LDS is reused by the next image of this workgroup
+    }
+}
+
 }  // namespace dbsn

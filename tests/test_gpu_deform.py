@@ -118,3 +118,25 @@ def test_shear_and_per_image_angle_bounds(oracle):
     lib = binding.load()
     out = torch.empty((1, 784), dtype=torch.float32, device="cuda")
     assert lib.deform_batch(p, src, 1, 0, 0, out) == binding.E_ARG
+
+
+def test_the_21_tap_kernel_and_the_general_kernel_agree_bit_for_bit():
+    """21 taps run in a kernel of their own (padded lines, windows in registers); the general kernel
+    computes the same sums in the same order, so the two must give identical floats, rotation and
+    shear alike."""
+    import os
+    import torch
+    from paper_1003_0358_amd import binding, datagen
+    img, lab = datagen.stroke_images(300, seed=31)
+    src = torch.from_numpy(img.reshape(300, 784)).cuda()
+    for shear in (0, 1):
+        p = binding.default_deform_params()
+        p.shear = shear
+        fast = binding.deform_batch(src, 7, 1234, p).cpu().numpy()
+        os.environ["DBSN_DEFORM_GENERIC"] = "1"
+        try:
+            general = binding.deform_batch(src, 7, 1234, p).cpu().numpy()
+        finally:
+            del os.environ["DBSN_DEFORM_GENERIC"]
+        assert np.array_equal(fast, general)
+        assert np.abs(fast - (img.reshape(300, 784) / 127.5 - 1.0)).max() > 0.1   # it did deform
