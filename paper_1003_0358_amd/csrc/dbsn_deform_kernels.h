@@ -125,8 +125,9 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
 // an exact zero, where k_deform adds nothing, so the sums are the same numbers), a thread computes
 // four neighbouring outputs of both fields from one window of 4 + 2R values read as float4 (one
 // LDS read per 14 multiply-adds), the taps sit in scalar registers, and the row pass writes its
-// result transposed, so that the column pass is the same walk along a line.  Every sum runs over
-// the taps in the order of k_deform: the two kernels agree bit for bit.
+// result transposed, so that the column pass is the same walk along a line; it puts its result
+// back into the field lines, and the resampling then takes a pixel per thread like k_deform.
+// Every sum runs over the taps in the order of k_deform: the two kernels agree bit for bit.
 constexpr int kPadLine = 52;   // floats per padded line: 13 float4, and 52 * c mod 64 visits 16 bank groups
 
 template <int KT>
@@ -201,9 +202,9 @@ __global__ __launch_bounds__(kDeformThreads, 4) void k_deform_taps(DeformArgs a,
         const float lp = aff[0], lq = aff[1], lr = aff[2], lt = aff[3], scx = aff[4], scy = aff[5];
         const float c0 = 0.5f * (float)(kSide - 1);
         float* out = dst + k * kPix;
-        // column pass and resampling: pixels (4 crun .. 4 crun + 3, ccol)
+        // column pass: pixels (4 crun .. 4 crun + 3, ccol) of both fields, back into the field lines
+        // (the raw fields are spent)
         if (threadIdx.x < kItems) {
-            float g[2][4];
 #pragma unroll
             for (int f = 0; f < 2; ++f) {
                 float in[kWin];
@@ -217,33 +218,35 @@ __global__ __launch_bounds__(kDeformThreads, 4) void k_deform_taps(DeformArgs a,
                     float sum = 0.0f;
 #pragma unroll
                     for (int t = 0; t < KT; ++t) sum = fmaf(w[t], in[o + t], sum);
-                    g[f][o] = sum;
+                    fld[f][4 * crun + o][R + ccol] = sum;
                 }
             }
-#pragma unroll
-            for (int o = 0; o < 4; ++o) {
-                const int r = 4 * crun + o, c = ccol;
-                const float u = (float)c - c0, v = (float)r - c0;
-                // X = sx (p u + q v) + c0 + alpha * smoothed dx;  Y = sy (r u + t v) + c0 + alpha * smoothed dy
-                const float X = fmaf(a.alpha, g[0][o], fmaf(scx, fmaf(lp, u, lq * v), c0));
-                const float Y = fmaf(a.alpha, g[1][o], fmaf(scy, fmaf(lr, u, lt * v), c0));
-                const float xf = floorf(X), yf = floorf(Y);
-                const float wx = X - xf, wy = Y - yf;
-                float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
-                if (xf >= -1.0f && xf <= (float)kSide && yf >= -1.0f && yf <= (float)kSide) {
-                    const int x0 = (int)xf, y0 = (int)yf;
-                    const bool xa = (x0 >= 0 && x0 < kSide), xb = (x0 + 1 >= 0 && x0 + 1 < kSide);
-                    const bool ya = (y0 >= 0 && y0 < kSide), yb = (y0 + 1 >= 0 && y0 + 1 < kSide);
-                    if (ya && xa) p00 = img[y0 * kSide + x0];
-                    if (ya && xb) p01 = img[y0 * kSide + x0 + 1];
-                    if (yb && xa) p10 = img[(y0 + 1) * kSide + x0];
-                    if (yb && xb) p11 = img[(y0 + 1) * kSide + x0 + 1];
-                }
-                const float top = (1.0f - wx) * p00 + wx * p01;
-                const float bot = (1.0f - wx) * p10 + wx * p11;
-                const float val = (1.0f - wy) * top + wy * bot;
-                out[r * kSide + c] = val / 127.5f - 1.0f;   // section "Data": intensity/127.5 - 1
+        }
+        __syncthreads();
+        // resampling, a pixel per thread and round
+        for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
+            const int r = i / kSide, c = i - r * kSide;
+            const float gx = fld[0][r][R + c], gy = fld[1][r][R + c];
+            const float u = (float)c - c0, v = (float)r - c0;
+            // X = sx (p u + q v) + c0 + alpha * smoothed dx;  Y = sy (r u + t v) + c0 + alpha * smoothed dy
+            const float X = fmaf(a.alpha, gx, fmaf(scx, fmaf(lp, u, lq * v), c0));
+            const float Y = fmaf(a.alpha, gy, fmaf(scy, fmaf(lr, u, lt * v), c0));
+            const float xf = floorf(X), yf = floorf(Y);
+            const float wx = X - xf, wy = Y - yf;
+            float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
+            if (xf >= -1.0f && xf <= (float)kSide && yf >= -1.0f && yf <= (float)kSide) {
+                const int x0 = (int)xf, y0 = (int)yf;
+                const bool xa = (x0 >= 0 && x0 < kSide), xb = (x0 + 1 >= 0 && x0 + 1 < kSide);
+                const bool ya = (y0 >= 0 && y0 < kSide), yb = (y0 + 1 >= 0 && y0 + 1 < kSide);
+                if (ya && xa) p00 = img[y0 * kSide + x0];
+                if (ya && xb) p01 = img[y0 * kSide + x0 + 1];
+                if (yb && xa) p10 = img[(y0 + 1) * kSide + x0];
+                if (yb && xb) p11 = img[(y0 + 1) * kSide + x0 + 1];
             }
+            const float top = (1.0f - wx) * p00 + wx * p01;
+            const float bot = (1.0f - wx) * p10 + wx * p11;
+            const float val = (1.0f - wy) * top + wy * bot;
+            out[i] = val / 127.5f - 1.0f;   // section "Data": intensity/127.5 - 1
         }
         __syncthreads();   // LDS is reused by the next image of this workgroup
     }
