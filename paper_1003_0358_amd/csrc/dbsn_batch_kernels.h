@@ -29,7 +29,7 @@ constexpr int kBatchRows = kBatchTile * kBatchK / kBatchThreads;   // elements o
 constexpr int kBatchSamples = 16384;    // samples per pass through the layers (sizes the activation buffers)
 
 // The activation for the batched passes: act_fast with the hardware reciprocal (one ulp) in place
-// of the division, a third of the instructions; only class labels come out of these passes.
+// of the division, under half the instructions; only class labels come out of these passes.
 __device__ __forceinline__ float act_batch(float a) {
     const float t = kB * a;
     const float at = fabsf(t);
@@ -199,9 +199,9 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
 // `zeros`, the matching one of the other operand from the start of its row (finite, times zero).
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kDmaThreads = 512;
-constexpr int kVecK = 32;
+constexpr int kDmaK = 32;            // k-chunk of a stage
 constexpr int kDmaStages = 4;
-constexpr int kDmaOperand = kBatchTile * kVecK;   // floats of one operand tile of a stage, unpadded
+constexpr int kDmaOperand = kBatchTile * kDmaK;   // floats of one operand tile of a stage, unpadded
 constexpr size_t kDmaLdsBytes = sizeof(float) * kDmaStages * 2 * kDmaOperand;
 
 // s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and for
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
     typedef __attribute__((address_space(3))) void* lptr;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: the roles branch on the scalar unit)
-    const int nchunks = (n_in + kVecK - 1) / kVecK;
+    const int nchunks = (n_in + kDmaK - 1) / kDmaK;
     const int my_tiles = ((int)blockIdx.x < ntiles) ? (ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
     const int total = my_tiles * nchunks;   // iterations of this workgroup
     if (total == 0) return;                 // (the whole workgroup: no barrier is left behind)
@@ -245,16 +245,16 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
             }
         };
         auto load_next = [&](int stage) {
-            const int k0 = pchunk * kVecK;
-            float* xs = lds_batch + stage * 2 * kDmaOperand + (32 * pw) * kVecK;
+            const int k0 = pchunk * kDmaK;
+            float* xs = lds_batch + stage * 2 * kDmaOperand + (32 * pw) * kDmaK;
             float* ws = xs + kDmaOperand;
             const char* Xk = reinterpret_cast<const char*>(X + k0);
             const char* Wk = reinterpret_cast<const char*>(W + k0);
-            if (k0 + kVecK <= n_in) {
+            if (k0 + kDmaK <= n_in) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    __builtin_amdgcn_global_load_lds((gptr)(Xk + xoff[r]), (lptr)(xs + 8 * r * kVecK), 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((gptr)(Wk + woff[r]), (lptr)(ws + 8 * r * kVecK), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr)(Xk + xoff[r]), (lptr)(xs + 8 * r * kDmaK), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr)(Wk + woff[r]), (lptr)(ws + 8 * r * kDmaK), 16, 0, 0);
                 }
             } else {
 #pragma unroll
@@ -262,8 +262,8 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
                     const bool in = k0 + (int)qoff[r] < n_in;
                     const char* xp = in ? Xk + xoff[r] : reinterpret_cast<const char*>(X) + xrow[r];
                     const char* wp = in ? Wk + woff[r] : reinterpret_cast<const char*>(zeros);
-                    __builtin_amdgcn_global_load_lds((gptr)xp, (lptr)(xs + 8 * r * kVecK), 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((gptr)wp, (lptr)(ws + 8 * r * kVecK), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr)xp, (lptr)(xs + 8 * r * kDmaK), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr)wp, (lptr)(ws + 8 * r * kDmaK), 16, 0, 0);
                 }
             }
             // on to the next chunk; past the end the last chunk is loaded again, into stages nobody reads
@@ -296,17 +296,17 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
     // ---- consumer
     const int sw = (wave & 1) * 64, jw = ((wave >> 1) & 1) * 64;
     const int lrow = lane & 31, half = lane >> 5, swz = (lrow >> 1) & 7;
-    int slot[kVecK / 8];   // float offset, inside a row, of the float4 this lane feeds to group m
+    int slot[kDmaK / 8];   // float offset, inside a row, of the float4 this lane feeds to group m
 #pragma unroll
-    for (int m = 0; m < kVecK / 8; ++m) slot[m] = 4 * ((m + 4 * half) ^ swz);
-    const float* xs0 = lds_batch + (sw + lrow) * kVecK;
-    const float* ws0 = lds_batch + kDmaOperand + (jw + lrow) * kVecK;
+    for (int m = 0; m < kDmaK / 8; ++m) slot[m] = 4 * ((m + 4 * half) ^ swz);
+    const float* xs0 = lds_batch + (sw + lrow) * kDmaK;
+    const float* ws0 = lds_batch + kDmaOperand + (jw + lrow) * kDmaK;
     __syncthreads();
     // operands of the next group of matrix instructions, read one group ahead
     floatx4 pa0 = *reinterpret_cast<const floatx4*>(xs0 + slot[0]);
-    floatx4 pa1 = *reinterpret_cast<const floatx4*>(xs0 + 32 * kVecK + slot[0]);
+    floatx4 pa1 = *reinterpret_cast<const floatx4*>(xs0 + 32 * kDmaK + slot[0]);
     floatx4 pw0 = *reinterpret_cast<const floatx4*>(ws0 + slot[0]);
-    floatx4 pw1 = *reinterpret_cast<const floatx4*>(ws0 + 32 * kVecK + slot[0]);
+    floatx4 pw1 = *reinterpret_cast<const floatx4*>(ws0 + 32 * kDmaK + slot[0]);
     int stage = 0;   // i % 4 of iteration i
     for (int t = 0; t < my_tiles; ++t) {
         floatx16 acc[2][2];
@@ -328,18 +328,18 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
             const float* xn = xs0 + stage1 * 2 * kDmaOperand;
             const float* wn = ws0 + stage1 * 2 * kDmaOperand;
 #pragma unroll
-            for (int m = 0; m < kVecK / 8; ++m) {
+            for (int m = 0; m < kDmaK / 8; ++m) {
                 const floatx4 a0 = pa0, a1 = pa1, w0 = pw0, w1 = pw1;
-                if (m + 1 < kVecK / 8) {
+                if (m + 1 < kDmaK / 8) {
                     pa0 = *reinterpret_cast<const floatx4*>(xs + slot[m + 1]);
-                    pa1 = *reinterpret_cast<const floatx4*>(xs + 32 * kVecK + slot[m + 1]);
+                    pa1 = *reinterpret_cast<const floatx4*>(xs + 32 * kDmaK + slot[m + 1]);
                     pw0 = *reinterpret_cast<const floatx4*>(ws + slot[m + 1]);
-                    pw1 = *reinterpret_cast<const floatx4*>(ws + 32 * kVecK + slot[m + 1]);
+                    pw1 = *reinterpret_cast<const floatx4*>(ws + 32 * kDmaK + slot[m + 1]);
                 } else {
                     pa0 = *reinterpret_cast<const floatx4*>(xn + slot[0]);
-                    pa1 = *reinterpret_cast<const floatx4*>(xn + 32 * kVecK + slot[0]);
+                    pa1 = *reinterpret_cast<const floatx4*>(xn + 32 * kDmaK + slot[0]);
                     pw0 = *reinterpret_cast<const floatx4*>(wn + slot[0]);
-                    pw1 = *reinterpret_cast<const floatx4*>(wn + 32 * kVecK + slot[0]);
+                    pw1 = *reinterpret_cast<const floatx4*>(wn + 32 * kDmaK + slot[0]);
                 }
                 __builtin_amdgcn_sched_barrier(0);   // the reads go out before the matrix instructions, not after
 #pragma unroll
