@@ -106,6 +106,18 @@ int32_t dbsn_mlp_set_mode(dbsn_mlp* mlp, int32_t mode);
  * exercised from the host. */
 int32_t dbsn_mlp_set_spin_limit(dbsn_mlp* mlp, uint32_t polls);
 
+/* Optional tuning of the persistent kernel for this network on this device.  Between the phases
+ * of a step a workgroup pauses before it first looks for the partial sums of the phase before (a
+ * look that comes too early costs a round trip through memory, one that comes late costs the
+ * delay); the best pauses depend on the layer sizes and on the machine.  This call finds them by
+ * timing launches of min(n, 512) steps over the given samples with eta = 0, which leave every
+ * weight as it was, bit for bit (w - 0 * delta * x = w), and keeps them for all later calls.
+ * Results never depend on the pauses, only speed does.  samples_dev: [n][sizes[0]] float,
+ * labels_dev: [n] int32, device memory, n >= 64.  Takes a second or two and synchronises the
+ * network's stream; a no-op in DBSN_MODE_LAUNCHES.  Not part of the paper's method: for callers
+ * that want the last few per cent. */
+int32_t dbsn_mlp_autotune(dbsn_mlp* mlp, const float* samples_dev, const int32_t* labels_dev, int64_t n);
+
 /* Synchronise the network's stream and report deferred errors: DBSN_E_TIMEOUT if a wait inside a
  * persistent kernel gave up (the weights are then undefined), DBSN_E_HIP for a failed launch. */
 int32_t dbsn_mlp_status(dbsn_mlp* mlp);

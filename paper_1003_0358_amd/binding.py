@@ -18,7 +18,7 @@ MODE_LAUNCHES, MODE_PERSISTENT = 0, 1
 SYMBOLS = [
     "dbsn_mlp_arena_bytes", "dbsn_mlp_init", "dbsn_mlp_free", "dbsn_mlp_set_weights", "dbsn_mlp_get_weights",
     "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
-    "dbsn_mlp_status", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify",
+    "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify",
     "dbsn_last_error",
 ]
 
@@ -65,6 +65,7 @@ class Lib:
         c.dbsn_mlp_set_mode.argtypes = [vp, i32]
         c.dbsn_mlp_set_spin_limit.argtypes = [vp, C.c_uint32]
         c.dbsn_mlp_status.argtypes = [vp]
+        c.dbsn_mlp_autotune.argtypes = [vp, vp, vp, i64]
         c.dbsn_deform_batch.argtypes = [C.POINTER(DeformParams), vp, i64, u64, u64, vp, vp]
         c.dbsn_deform_batch_beta.argtypes = [C.POINTER(DeformParams), vp, vp, i64, u64, u64, vp, vp]
         c.dbsn_bp_steps.argtypes = [vp, vp, vp, i64, f32, vp]
@@ -119,6 +120,9 @@ class Lib:
 
     def mlp_status(self, h):
         return self.c.dbsn_mlp_status(h)
+
+    def mlp_autotune(self, h, samples, labels, n):
+        return self.c.dbsn_mlp_autotune(h, _ptr(samples), _ptr(labels), n)
 
     def deform_batch(self, params, src, n, seed, first_index, dst, stream=0):
         return self.c.dbsn_deform_batch(C.byref(params) if params is not None else None, _ptr(src), n, seed,
@@ -203,6 +207,10 @@ class Mlp:
 
     def status(self):
         self.lib.check(self.lib.mlp_status(self.h))
+
+    def autotune(self, samples, labels):
+        """Tunes the persistent kernel's pauses on these samples (steps with eta = 0: weights unchanged)."""
+        self.lib.check(self.lib.mlp_autotune(self.h, samples, labels, samples.shape[0]))
 
     def get_weights(self, layer):
         W = np.empty((self.sizes[layer], self.sizes[layer - 1]), dtype=np.float32)

@@ -320,10 +320,30 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     pn.err = m->err;
     pn.spin_limit = 1u << 22;
     pn.stationary = plan.stationary ? 1 : 0;
-    pn.fwd_delay = 12;
+    int fwd_delay = 17;
     pn.adapt = 0;
-    if (const char* e = getenv("DBSN_ADAPT")) pn.adapt = atoi(e) != 0;
-    if (const char* e = getenv("DBSN_FWD_DELAY")) pn.fwd_delay = atoi(e) < 0 ? 0 : (atoi(e) > 48 ? 48 : atoi(e));
+    if (const char* e = getenv("DBSN_ADAPT")) pn.adapt = atoi(e) < 0 ? 0 : (atoi(e) > 12 ? 12 : atoi(e));
+    if (const char* e = getenv("DBSN_FWD_DELAY")) fwd_delay = atoi(e) < 0 ? 0 : (atoi(e) > 48 ? 48 : atoi(e));
+    for (int l = 0; l <= kMaxLayers; ++l) {
+        pn.pace[0][l] = (unsigned char)fwd_delay;
+        pn.pace[1][l] = 0;
+    }
+    // DBSN_PACE="f1,...,fL;b1,...,bL": one pause per forward layer (fL: the output layer), then per
+    // backward layer; layers left out keep the default
+    if (const char* e = getenv("DBSN_PACE")) {
+        int dir = 0, l = 1;
+        for (const char* c = e; *c; ++c) {
+            if (*c == ';') { dir = 1; l = 1; continue; }
+            if (*c == ',') continue;
+            if (*c >= '0' && *c <= '9') {
+                int v = 0;
+                while (*c >= '0' && *c <= '9') v = 10 * v + (*c++ - '0');
+                --c;
+                if (l <= kMaxLayers && dir < 2) pn.pace[dir][l] = (unsigned char)(v > 48 ? 48 : v);
+                ++l;
+            }
+        }
+    }
     if (const char* e = getenv("DBSN_STATIONARY")) pn.stationary = (atoi(e) != 0 && plan.stationary) ? 1 : 0;
     // a compile-time register layout when the net is stationary and fits it
     m->layout = 0;
@@ -458,6 +478,65 @@ int32_t dbsn_bp_steps(dbsn_mlp* m, const float* samples_dev, const int32_t* labe
     if (!std::isfinite(eta)) return fail(DBSN_E_ARG, "eta is not finite");
     if (use_persistent(m)) return steps_persistent(m, samples_dev, labels_dev, 0, n, eta, loss_dev);
     return steps_launches(m, samples_dev, labels_dev, 0, n, eta, loss_dev);
+}
+
+int32_t dbsn_mlp_autotune(dbsn_mlp* m, const float* samples_dev, const int32_t* labels_dev, int64_t n) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    if (n < 64) return fail(DBSN_E_ARG, "autotune needs at least 64 samples");
+    if (!samples_dev || !labels_dev) return fail(DBSN_E_ARG, "samples or labels pointer is null");
+    if (!aligned(samples_dev, 4) || !aligned(labels_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    if (!use_persistent(m)) return DBSN_OK;   // the launch-per-phase mode has nothing to tune
+    // Coordinate descent over the pauses of the persistent kernel, timing launches of steps with
+    // eta = 0: w - 0 * delta * x is w, bit for bit, so the weights come out as they went in.
+    const int64_t steps = std::min<int64_t>(n, 512);
+    const int L = m->net.L;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    int32_t rc = DBSN_OK;
+    auto measure = [&](float& best_ms) -> int32_t {
+        best_ms = 1e30f;
+        for (int rep = 0; rep < 3; ++rep) {
+            if (hipEventRecord(e0, m->stream) != hipSuccess) return fail(DBSN_E_HIP, "hipEventRecord");
+            const int32_t r = steps_persistent(m, samples_dev, labels_dev, 0, steps, 0.0f, nullptr);
+            if (r) return r;
+            if (hipEventRecord(e1, m->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess)
+                return fail(DBSN_E_HIP, "hipEventSynchronize");
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return fail(DBSN_E_HIP, "hipEventElapsedTime");
+            best_ms = std::min(best_ms, ms);
+        }
+        return DBSN_OK;
+    };
+    float best = 0.0f;
+    rc = measure(best);   // (also warms the launch up)
+    if (!rc) rc = measure(best);
+    const int coarse[] = {-4, -2, 2, 4, 8}, fine[] = {-1, 1};
+    for (int sweep = 0; sweep < 2 && !rc; ++sweep) {
+        const int* deltas = sweep == 0 ? coarse : fine;
+        const int nd = sweep == 0 ? 5 : 2;
+        for (int dir = 0; dir < 2 && !rc; ++dir)
+            for (int l = 1; l <= L && !rc; ++l) {
+                unsigned char& cell = m->pnet.pace[dir][l];
+                int base = cell;
+                for (int k = 0; k < nd && !rc; ++k) {
+                    const int v = base + deltas[k];
+                    if (v < 0 || v > 48) continue;
+                    cell = (unsigned char)v;
+                    float ms = 0.0f;
+                    rc = measure(ms);
+                    if (!rc && ms < best * 0.9985f) {   // keep what is better by more than the noise
+                        best = ms;
+                        base = v;
+                    }
+                    cell = (unsigned char)base;
+                }
+            }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    return dbsn_mlp_status(m);
 }
 
 int32_t dbsn_bp_step(dbsn_mlp* m, const float* sample_dev, int32_t label, float eta) {

@@ -123,7 +123,9 @@ struct PNet {
     int L;
     unsigned spin_limit;
     int stationary;   // 1: every layer has its own register groups for the whole launch
-    int fwd_delay;    // first guess of the pause before looking at forward partials, in units of 64 clocks
+    // pause of each (direction, layer) before its first look at the partials, in units of 64 clocks
+    // ([0]: forward, index L the output layer; [1]: backward); the adaptive mode starts from these
+    unsigned char pace[2][kMaxLayers + 1];
     int adapt;        // 1: every wavefront tunes its pauses while it runs (see pace_begin)
 };
 
@@ -307,7 +309,7 @@ __device__ __forceinline__ void pace_end(float* lds, int dir, int l, int d, unsi
     int* tab = reinterpret_cast<int*>(lds + PLds::pace);
     int nd = d;
     if (rereads != 0) nd = min(d + 2, kPaceMax);
-    else if ((tag & 7u) == 0u && d > 0) nd = d - 1;
+    else if ((tag & ((1u << adapt) - 1u)) == 0u && d > 0) nd = d - 1;
     if (nd != d && (threadIdx.x & 63) == 0) tab[((threadIdx.x >> 6) * 2 + dir) * (kMaxLayers + 1) + l] = nd;
 }
 
@@ -900,7 +902,7 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
     for (int e = threadIdx.x; e < kWaves * 2 * (kMaxLayers + 1); e += kThreads)
-        reinterpret_cast<int*>(lds + PLds::pace)[e] = ((e / (kMaxLayers + 1)) & 1) ? 0 : net.fwd_delay;
+        reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[(e / (kMaxLayers + 1)) & 1][e % (kMaxLayers + 1)];
     if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
 
     for (int l = 1; l < L; ++l) {

@@ -298,6 +298,31 @@ def test_classify_full_size_net_in_bench_configuration(oracle):
     m.close()
 
 
+@pytest.mark.parametrize("sizes", [NET0, [784] + [300] * 9 + [10]])
+def test_autotune_leaves_weights_and_results_alone(sizes):
+    """dbsn_mlp_autotune times steps with eta = 0: the weights must come out bit for bit as they
+    went in, and training afterwards must give the same floats as on a network that was never tuned
+    (the pauses it sets change when a workgroup looks, not what it computes)."""
+    from paper_1003_0358_amd import binding
+    torch = _torch()
+    X, y = _data(300, seed=3)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    tuned, plain = _mk(sizes, 1, seed=5), _mk(sizes, 1, seed=5)
+    before = tuned.get_params()
+    tuned.autotune(Xd[:128], yd[:128])
+    assert np.array_equal(tuned.get_params(), before)
+    tuned.bp_steps(Xd, yd, 1e-3)
+    plain.bp_steps(Xd, yd, 1e-3)
+    tuned.status(); plain.status()
+    assert np.array_equal(tuned.get_params(), plain.get_params())
+    lib = tuned.lib
+    assert lib.mlp_autotune(tuned.h, Xd, yd, 10) == binding.E_ARG        # too few samples to time
+    assert lib.mlp_autotune(tuned.h, None, yd, 128) == binding.E_ARG
+    tuned.set_mode(binding.MODE_LAUNCHES)
+    assert lib.mlp_autotune(tuned.h, Xd, yd, 128) == binding.OK          # nothing to tune: a no-op
+    tuned.close(); plain.close()
+
+
 def test_set_get_weights_roundtrip_and_errors():
     from paper_1003_0358_amd import binding
     torch = _torch()
