@@ -226,6 +226,8 @@ int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, i
     const size_t lds = sizeof(float) * (size_t)(PLds::total + kProfLdsFloats);
     const void* fn = !m->pnet.stationary ? reinterpret_cast<const void*>(&k_bp_dataflow<false, 0>)
                      : m->layout == 1    ? reinterpret_cast<const void*>(&k_bp_dataflow<true, 1>)
+                     : m->layout == 2    ? reinterpret_cast<const void*>(&k_bp_dataflow<true, 2>)
+                     : m->layout == 3    ? reinterpret_cast<const void*>(&k_bp_dataflow<true, 3>)
                                          : reinterpret_cast<const void*>(&k_bp_dataflow<true, 0>);
     if (!m->persistent_ready) {
         if (lds > m->lds_limit) return fail(DBSN_E_SHAPE, "persistent kernel needs %zu B of LDS", lds);
@@ -347,10 +349,12 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     if (const char* e = getenv("DBSN_STATIONARY")) pn.stationary = (atoi(e) != 0 && plan.stationary) ? 1 : 0;
     // a compile-time register layout when the net is stationary and fits it
     m->layout = 0;
-    if (pn.stationary && plan.persistent_ok && net.L - 1 <= kLayoutDepth && !getenv("DBSN_NO_LAYOUT")) {
-        m->layout = 1;
-        for (int l = 1; l < net.L; ++l)
-            if (plan.ng[l] > kLayoutNG[l - 1]) m->layout = 0;
+    if (pn.stationary && plan.persistent_ok && !getenv("DBSN_NO_LAYOUT")) {
+        for (int cand = 1; cand < kLayouts && m->layout == 0; ++cand) {
+            bool fits = net.L - 1 <= kLayoutDepth[cand];
+            for (int l = 1; l < net.L && fits; ++l) fits = plan.ng[l] <= kLayoutNG[cand][l - 1];
+            if (fits) m->layout = cand;
+        }
     }
     for (int l = 1; l <= net.L; ++l) {
         PLayer& P = pn.lay[l];
@@ -359,7 +363,7 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
         if (l < net.L && plan.persistent_ok) {
             P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
-            P.g0 = m->layout == 1 ? kLayoutG0[l - 1] : (pn.stationary ? plan.g0[l] : 0);
+            P.g0 = m->layout ? kLayoutG0[m->layout][l - 1] : (pn.stationary ? plan.g0[l] : 0);
             P.ng = plan.ng[l];
             P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
             if (l <= net.L - 2) {

@@ -344,11 +344,23 @@ __device__ __forceinline__ void for_layer_groups(int g0, int gend, F&& f) {
 // (layer l owns the groups [g0(l), g0(l) + ngmax(l)), of which it uses its first ng) skip it: the
 // loops below then see constant group numbers, selected by one plain switch on the layer.
 // LAYOUT 0: groups packed in layer order at run time (any network);
-// LAYOUT 1: up to five hidden layers of at most 3, 5, 3, 2, 1 groups (the paper's nets with up to
-//           five hidden layers of 2500, 2000, 1500, 1000, 500 units or fewer fit).
-constexpr int kLayoutDepth = 5;
-constexpr int kLayoutG0[kLayoutDepth] = {0, 3, 8, 11, 13};
-constexpr int kLayoutNG[kLayoutDepth] = {3, 5, 3, 2, 1};
+// LAYOUT 1: up to four hidden layers of at most 2, 3, 2, 1 groups (the paper's nets of two to four
+//           hidden layers: 1000-500, 1500-1000-500, 2000-1500-1000-500);
+// LAYOUT 2: up to five hidden layers of at most 3, 5, 3, 2, 1 groups (2500-2000-1500-1000-500);
+// LAYOUT 3: up to nine hidden layers of one group each (the paper's net of nine hidden layers of
+//           1000 units, and other deep nets of narrow layers).
+// The host takes the first layout a network fits.
+constexpr int kLayouts = 4;
+constexpr int kLayoutMaxDepth = 9;
+constexpr int kLayoutDepth[kLayouts] = {0, 5, 5, 9};
+constexpr int kLayoutG0[kLayouts][kLayoutMaxDepth] = {{0, 0, 0, 0, 0, 0, 0, 0, 0},
+                                                      {0, 2, 5, 7, 8, 8, 8, 8, 8},
+                                                      {0, 3, 8, 11, 13, 14, 14, 14, 14},
+                                                      {0, 1, 2, 3, 4, 5, 6, 7, 8}};
+constexpr int kLayoutNG[kLayouts][kLayoutMaxDepth] = {{0, 0, 0, 0, 0, 0, 0, 0, 0},
+                                                      {2, 3, 2, 1, 0, 0, 0, 0, 0},
+                                                      {3, 5, 3, 2, 1, 0, 0, 0, 0},
+                                                      {1, 1, 1, 1, 1, 1, 1, 1, 1}};
 // (All groups of the layer's static range run, used or not: an unused group holds zero weights and
 // meets zero deltas, so it publishes nothing and stays zero, and the code has no branch to merge.)
 template <int G, int GEND, class F>
@@ -358,12 +370,16 @@ __device__ __forceinline__ void run_groups(F&& f) {
         run_groups<G + 1, GEND>(f);
     }
 }
-// POS = 0: the layer is known at run time only (LAYOUT 0); POS = 1 .. kLayoutDepth: the phase is
-// compiled for hidden layer POS of LAYOUT 1.
-template <int POS, class F>
+// POS = 0: the layer is known at run time only (LAYOUT 0); POS = 1 .. kLayoutDepth[LAYOUT]: the
+// phase is compiled for hidden layer POS of that layout.
+template <int LAYOUT, int POS, class F>
 __device__ __forceinline__ void layer_groups(int g0, int gend, F&& f) {
     if constexpr (POS == 0) for_layer_groups(g0, gend, f);
-    else run_groups<kLayoutG0[POS - 1], kLayoutG0[POS - 1] + kLayoutNG[POS - 1]>(f);
+    else {
+        static_assert(POS <= kLayoutDepth[LAYOUT] && kLayoutG0[LAYOUT][POS - 1] + kLayoutNG[LAYOUT][POS - 1] <= kNG,
+                      "the layout has this layer and its groups exist");
+        run_groups<kLayoutG0[LAYOUT][POS - 1], kLayoutG0[LAYOUT][POS - 1] + kLayoutNG[LAYOUT][POS - 1]>(f);
+    }
 }
 
 // Register slot a = kGR * G + q of group G holds tile row wave + 8 * (a - kGR * g0) of the layer
@@ -494,7 +510,7 @@ __device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
 
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
 // partial sums of the rows over the tile's columns, the bias riding on column block 0.
-template <bool ST, int POS>
+template <bool ST, int LAYOUT, int POS>
 __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float x0pre,
                                            unsigned tag, bool last, float* lds, const PlanRow& pl, long long ps, int ph DBSN_PROF_ARGS) {
     const int flags = uniform(pl[PL_FLAGS]);
@@ -544,7 +560,7 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     // of 16 lanes; lane 16 r + (a & 15) keeps the sum of slot a over lane row r
     float res0 = 0.0f, res1 = 0.0f;
     const int lane14 = lane & 14;
-    layer_groups<POS>(g0, gend, [&](auto Gc) {
+    layer_groups<LAYOUT, POS>(g0, gend, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
         const float v2 = pair_sum2(dot4(wr[kGR * G + 0], x4), dot4(wr[kGR * G + 1], x4));
         if (kGR * G < 16) res0 = (lane14 == ((kGR * G) & 14)) ? v2 : res0;
@@ -565,7 +581,7 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
 // "Weight updating" over the same registers): deltas of the tile's rows, partial W^T delta of its
 // columns from the OLD weights, published at once (it is what other workgroups wait for), then
 // the rank-1 update of the tile.
-template <bool ST, int POS>
+template <bool ST, int LAYOUT, int POS>
 __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net, int l, int g, float eta,
                                            unsigned tag, bool last, float* lds, const PlanRow& pl, long long ps,
                                            int ph DBSN_PROF_ARGS) {
@@ -629,7 +645,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 3);
     if (l > 1) {
         float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
-        layer_groups<POS>(g0, gend, [&](auto Gc) {
+        layer_groups<LAYOUT, POS>(g0, gend, [&](auto Gc) {
             constexpr int G = decltype(Gc)::value;
 #pragma unroll
             for (int q = 0; q < kGR; ++q) {
@@ -672,7 +688,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 6);
     // rank-1 update of the tile held in registers, w[j][i] -= eta * delta_j * x_i; rows beyond the
     // tile hold zeros and get a zero delta, so they stay zero
-    layer_groups<POS>(g0, gend, [&](auto Gc) {
+    layer_groups<LAYOUT, POS>(g0, gend, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
 #pragma unroll
         for (int q = 0; q < kGR; ++q) {
@@ -952,17 +968,23 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
             if (labels) labpre = labels[s + 1];
         }
         const bool last = (s + 1 == n);
-#define DBSN_FWD(POS, l, row) p_fwd_tile<ST, POS>(wr, net, l, g, x0cur, tag, last, lds, row, s, (l) - 1 DBSN_PROF_PASS)
-#define DBSN_BWD(POS, l, row) p_bwd_tile<ST, POS>(wr, net, l, g, eta, tag, last, lds, row, s, L + (L - 1 - (l)) DBSN_PROF_PASS)
+#define DBSN_FWD(POS, l, row) p_fwd_tile<ST, ((POS) ? LAYOUT : 0), POS>(wr, net, l, g, x0cur, tag, last, lds, row, s, (l) - 1 DBSN_PROF_PASS)
+#define DBSN_BWD(POS, l, row) p_bwd_tile<ST, ((POS) ? LAYOUT : 0), POS>(wr, net, l, g, eta, tag, last, lds, row, s, L + (L - 1 - (l)) DBSN_PROF_PASS)
         if constexpr (LAYOUT == 0) {
             for (int l = 1; l < L && alive; ++l) alive = DBSN_FWD(0, l, load_plan(lds, l));
         } else {
-            static_assert(kLayoutDepth == 5, "one line per hidden layer of the layout");
+            static_assert(kLayoutDepth[LAYOUT] == 5 || kLayoutDepth[LAYOUT] == 9, "one line per hidden layer of the layout");
             alive = DBSN_FWD(1, 1, row1);
             if (L > 2 && alive) alive = DBSN_FWD(2, 2, row2);
             if (L > 3 && alive) alive = DBSN_FWD(3, 3, row3);
             if (L > 4 && alive) alive = DBSN_FWD(4, 4, row4);
             if (L > 5 && alive) alive = DBSN_FWD(5, 5, row5);
+            if constexpr (kLayoutDepth[LAYOUT] > 5) {   // (table rows of the deeper layers: fetched at each phase)
+                if (L > 6 && alive) alive = DBSN_FWD(6, 6, load_plan(lds, 6));
+                if (L > 7 && alive) alive = DBSN_FWD(7, 7, load_plan(lds, 7));
+                if (L > 8 && alive) alive = DBSN_FWD(8, 8, load_plan(lds, 8));
+                if (L > 9 && alive) alive = DBSN_FWD(9, 9, load_plan(lds, 9));
+            }
         }
         if (alive)
             alive = p_top(net, g, label, eta, tag, loss_out ? loss_out + s : nullptr, last, lds, rowL, tr, s, L - 1 DBSN_PROF_PASS);
@@ -974,6 +996,16 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
                 if (l == L - 1) top_update(tr, eta, lds);
             }
         } else {
+            if constexpr (kLayoutDepth[LAYOUT] > 5) {
+                if (L > 9 && alive) alive = DBSN_BWD(9, 9, load_plan(lds, 9));
+                if (L == 10) top_update(tr, eta, lds);
+                if (L > 8 && alive) alive = DBSN_BWD(8, 8, load_plan(lds, 8));
+                if (L == 9) top_update(tr, eta, lds);
+                if (L > 7 && alive) alive = DBSN_BWD(7, 7, load_plan(lds, 7));
+                if (L == 8) top_update(tr, eta, lds);
+                if (L > 6 && alive) alive = DBSN_BWD(6, 6, load_plan(lds, 6));
+                if (L == 7) top_update(tr, eta, lds);
+            }
             if (L > 5 && alive) alive = DBSN_BWD(5, 5, row5);
             if (L == 6) top_update(tr, eta, lds);
             if (L > 4 && alive) alive = DBSN_BWD(4, 4, row4);
