@@ -496,7 +496,10 @@ int32_t dbsn_mlp_autotune(dbsn_mlp* m, const float* samples_dev, const int32_t* 
     const int L = m->net.L;
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
-    HIP_TRY(hipEventCreate(&e1));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(DBSN_E_HIP, "hipEventCreate");
+    }
     int32_t rc = DBSN_OK;
     auto measure = [&](float& best_ms) -> int32_t {
         best_ms = 1e30f;
