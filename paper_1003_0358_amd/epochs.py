@@ -36,7 +36,7 @@ def identity_params():
 
 def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6, params=None,
                beta_by_label=True, seed=0, chunk=1000, val_u8=None, val_labels=None, keep_best=True,
-               log=None):
+               log=None, autotune=True):
     """Train `mlp` (binding.Mlp) for `epochs` epochs.
 
     train_u8: uint8 device tensor [n, 784]; train_labels: int32 device tensor [n];
@@ -44,6 +44,8 @@ def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6
     rotation / shear angle follows the label: the look-alike digits 1 and 7 get params.beta_deg, all
     others twice that (7.5 and 15 degrees with the default), instead of params.beta_deg for all;
     val_u8 / val_labels: validation set (default: the un-deformed training set).
+    autotune: tune the training kernel's pauses once before the first epoch (dbsn_mlp_autotune on the
+    first deformed chunk; steps with eta = 0, so the weights and every result stay as they are).
     Returns the history: one dict per epoch with eta, mean training loss, validation errors.
     With keep_best the network ends with the weights of the epoch of lowest validation error.
     """
@@ -60,6 +62,11 @@ def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6
     xbuf = torch.empty((chunk, 784), dtype=torch.float32, device=train_u8.device)
     loss = torch.zeros(n, dtype=torch.float32, device=train_u8.device)
     history, best, best_params = [], None, None
+    if autotune and min(chunk, n) >= 64:
+        m0 = min(chunk, n)
+        binding.deform_batch(train_u8[:m0], seed, 0, params, out=xbuf[:m0],
+                             beta_deg=None if beta is None else beta[:m0])
+        mlp.autotune(xbuf[:m0], train_labels[:m0])
     for e, eta in enumerate(eta_schedule(epochs, eta_start, eta_end)):
         for a in range(0, n, chunk):
             m = min(chunk, n - a)
