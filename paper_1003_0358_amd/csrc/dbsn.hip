@@ -613,9 +613,15 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
             ldx = ldact;
         }
         const Layer& Lt = m->net.lay[L];
-        const int per_block = kBatchThreads / 64;
-        hipLaunchKernelGGL(k_top_batch, dim3((S + per_block - 1) / per_block), dim3(kBatchThreads), 0, m->stream, X, ldx,
-                           S, Lt.W, Lt.ld, Lt.b, Lt.n_in, Lt.n_out, labels_out_dev + at);
+        if (ldx % 4 == 0 && Lt.ld % 4 == 0 && aligned(X, 16) && aligned(Lt.W, 16)) {
+            const int per_block = (kBatchThreads / 64) * kTopPerWave;
+            hipLaunchKernelGGL(k_top_batch, dim3((S + per_block - 1) / per_block), dim3(kBatchThreads), 0, m->stream, X,
+                               ldx, S, Lt.W, Lt.ld, Lt.b, Lt.n_in, Lt.n_out, labels_out_dev + at);
+        } else {
+            const int per_block = kBatchThreads / 64;
+            hipLaunchKernelGGL(k_top_batch_any, dim3((S + per_block - 1) / per_block), dim3(kBatchThreads), 0, m->stream,
+                               X, ldx, S, Lt.W, Lt.ld, Lt.b, Lt.n_in, Lt.n_out, labels_out_dev + at);
+        }
     }
     HIP_TRY(hipGetLastError());
     return DBSN_OK;

@@ -365,8 +365,9 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
 // Output layer of the classification pass: labels[s] = index of the largest pre-activation
 // b[c] + sum_i W[c][i] X[s][i] over the classes (the lowest index on ties).  The layer has only a
 // few rows, so it is no job for 128-wide tiles: one wavefront per sample, lanes over the inputs,
-// classes 16 at a time in registers, sums over the lanes on the vector ALU.
-__global__ __launch_bounds__(kBatchThreads) void k_top_batch(const float* __restrict__ X, int ldx, int S,
+// classes 16 at a time in registers, sums over the lanes on the vector ALU.  This form takes any
+// strides and alignment (a network without hidden layers classifies the caller's samples with it).
+__global__ __launch_bounds__(kBatchThreads) void k_top_batch_any(const float* __restrict__ X, int ldx, int S,
                                                               const float* __restrict__ W, int ldw,
                                                               const float* __restrict__ b, int n_in, int n_out,
                                                               int* __restrict__ labels) {
@@ -398,6 +399,69 @@ __global__ __launch_bounds__(kBatchThreads) void k_top_batch(const float* __rest
         }
     }
     if (lane == 0) labels[s] = best;
+}
+
+// The same for rows that start on 16-byte boundaries (the activation buffers): a wavefront takes
+// four samples at once and reads float4, so a weight row is fetched once per four samples and a
+// 500-input layer is two rounds of loads instead of eight per sample.  A float4 that straddles
+// n_in meets the zero padding of the weight rows.
+constexpr int kTopPerWave = 4;
+__global__ __launch_bounds__(kBatchThreads) void k_top_batch(const float* __restrict__ X, int ldx, int S,
+                                                              const float* __restrict__ W, int ldw,
+                                                              const float* __restrict__ b, int n_in, int n_out,
+                                                              int* __restrict__ labels) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+    const int s0 = (blockIdx.x * (kBatchThreads / 64) + (threadIdx.x >> 6)) * kTopPerWave;
+    if (s0 >= S) return;
+    const float* xrow[kTopPerWave];
+#pragma unroll
+    for (int q = 0; q < kTopPerWave; ++q) xrow[q] = X + (size_t)min(s0 + q, S - 1) * ldx;
+    int best[kTopPerWave];
+    float bv[kTopPerWave];
+#pragma unroll
+    for (int q = 0; q < kTopPerWave; ++q) { best[q] = 0; bv[q] = 0.0f; }
+    for (int c0 = 0; c0 < n_out; c0 += 16) {
+        float acc[kTopPerWave][16];
+#pragma unroll
+        for (int q = 0; q < kTopPerWave; ++q)
+#pragma unroll
+            for (int c = 0; c < 16; ++c) acc[q][c] = 0.0f;
+        for (int i = 4 * lane; i < n_in; i += 256) {
+            f4 x[kTopPerWave];
+#pragma unroll
+            for (int q = 0; q < kTopPerWave; ++q) x[q] = *reinterpret_cast<const f4*>(xrow[q] + i);
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                if (c0 + c < n_out) {   // (uniform)
+                    const f4 w = *reinterpret_cast<const f4*>(W + (size_t)(c0 + c) * ldw + i);
+#pragma unroll
+                    for (int q = 0; q < kTopPerWave; ++q)
+                        acc[q][c] = fmaf(w[3], x[q][3], fmaf(w[2], x[q][2], fmaf(w[1], x[q][1], fmaf(w[0], x[q][0], acc[q][c]))));
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            if (c0 + c < n_out) {   // (uniform)
+                const float bc = b[c0 + c];
+#pragma unroll
+                for (int q = 0; q < kTopPerWave; ++q) {
+                    float v = acc[q][c];
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+                    v += bc;
+                    if ((c0 + c == 0) || v > bv[q]) { bv[q] = v; best[q] = c0 + c; }
+                }
+            }
+        }
+    }
+    if (lane < kTopPerWave && s0 + lane < S) {
+        int out = best[0];
+#pragma unroll
+        for (int q = 1; q < kTopPerWave; ++q) out = lane == q ? best[q] : out;
+        labels[s0 + lane] = out;
+    }
 }
 
 }  // namespace dbsn
