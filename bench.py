@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # counter reads for a plain kernel of known size (--traffic-probe).  Counters cannot be read from
 # inside the process, so the figure is the one recorded in profiles/k_bp_dataflow_net4_pmc.txt
 # (commands there); it applies to the default chunk of 1000 samples in persistent mode only.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1.823e10
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1.824e10
 
 
 def n_weights(sizes):
