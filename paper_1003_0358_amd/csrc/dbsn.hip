@@ -596,15 +596,26 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
                               (uint64_t)S * std::max(ldx, ldact) * sizeof(float) < (1ull << 32);
             if (fits && ldx % 4 == 0 && Ly.ld % 4 == 0 && Ly.n_in % 4 == 0 && aligned(X, 16) && aligned(Ly.W, 16)) {
                 if (!m->batch_ready) {
-                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes));
+                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true, 128>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(128)));
+                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true, 64>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(64)));
                     m->batch_ready = true;
                 }
-                const int nt = (int)(grid.x * grid.y);
+                // tiles of 128 samples, or of 64 where that fills the rounds of the persistent
+                // workgroups better: a 64-sample tile costs a little more than half a 128-sample one
+                const int nx = (int)grid.x, G = m->cus;
+                const int nt128 = nx * ((S + 127) / 128), nt64 = nx * ((S + 63) / 64);
+                const double cost128 = (double)((nt128 + G - 1) / G), cost64 = 0.54 * (double)((nt64 + G - 1) / G);
                 const float* zeros = reinterpret_cast<const float*>(m->err + kZerosAt);
-                hipLaunchKernelGGL(k_layer_batch_dma<true>, dim3(std::min(nt, m->cus)), dim3(kDmaThreads), kDmaLdsBytes,
-                                   m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact, (int)grid.x, nt,
-                                   zeros);
+                if (cost64 < cost128)
+                    hipLaunchKernelGGL((k_layer_batch_dma<true, 64>), dim3(std::min(nt64, G)), dim3(kDmaThreads),
+                                       dma_lds_bytes(64), m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y,
+                                       ldact, nx, nt64, zeros);
+                else
+                    hipLaunchKernelGGL((k_layer_batch_dma<true, 128>), dim3(std::min(nt128, G)), dim3(kDmaThreads),
+                                       dma_lds_bytes(128), m->stream, X, ldx, S, Ly.W, Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y,
+                                       ldact, nx, nt128, zeros);
             } else {
                 hipLaunchKernelGGL(k_layer_batch<true>, grid, dim3(kBatchThreads), 0, m->stream, X, ldx, S, Ly.W,
                                    Ly.ld, Ly.b, Ly.n_in, Ly.n_out, Y, ldact);

@@ -41,14 +41,14 @@ __device__ __forceinline__ float act_batch(float a) {
     return kA * copysignf(r, t);
 }
 
-// End of a tile for one wavefront: its 64 x 64 quadrant (2 x 2 accumulators, first sample s_base,
-// first neuron j_base) gets bias and activation and goes to Y.  The two bias values are pinned in
+// End of a tile for one wavefront: its quadrant of 32 NA samples x 64 neurons (NA x 2 accumulators,
+// first sample s_base, first neuron j_base) gets bias and activation and goes to Y.  The two bias values are pinned in
 // registers before the first guarded store: a guard that were the first to touch them would make
 // every later one wait for all memory operations in flight, the stores before it included, since
 // the compiler cannot know which guards were taken.  Addresses are 32-bit byte offsets from Y (a
 // pass's activations stay far below 4 GB): one addition per store.
-template <bool ACT>
-__device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], const float* __restrict__ b,
+template <bool ACT, int NA>
+__device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[NA][2], const float* __restrict__ b,
                                                float* __restrict__ Y, int ldy, int S, int n_out, int s_base,
                                                int j_base, int lane) {
     const int jl = j_base + (lane & 31);
@@ -58,13 +58,13 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], cons
     char* Yb = reinterpret_cast<char*>(Y);
     const unsigned pitch = 4u * (unsigned)ldy;
     const unsigned at = (unsigned)sl * pitch + 4u * (unsigned)jl;
-    if (s_base + 64 <= S && j_base + 64 <= n_out) {
+    if (s_base + 32 * NA <= S && j_base + 64 <= n_out) {
         // the quadrant lies inside the matrix (a uniform test): no guards, one basic block, so the 64
         // independent activations interleave instead of each waiting out its own latencies
 #pragma unroll
         for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < NA; ++a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ds = 32 * a + (r & 3) + 8 * (r >> 2);   // sample of this element, from the lane's first
@@ -77,7 +77,7 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[2][2], cons
     for (int c = 0; c < 2; ++c) {
         const int j = jl + 32 * c;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int ds = 32 * a + (r & 3) + 8 * (r >> 2);
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_layer_batch(const float* __re
         }
         __syncthreads();
     }
-    store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
+    store_quadrant<ACT, 2>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
 }
 
 // The same layer at speed, for operands whose rows start on 16-byte boundaries and n_in % 4 == 0
@@ -201,19 +201,30 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kDmaThreads = 512;
 constexpr int kDmaK = 32;            // k-chunk of a stage
 constexpr int kDmaStages = 4;
-constexpr int kDmaOperand = kBatchTile * kDmaK;   // floats of one operand tile of a stage, unpadded
-constexpr size_t kDmaLdsBytes = sizeof(float) * kDmaStages * 2 * kDmaOperand;
+// floats of a stage: TM sample rows and 128 weight rows of 32, unpadded
+constexpr int dma_stage_floats(int TM) { return (TM + kBatchTile) * kDmaK; }
+constexpr size_t dma_lds_bytes(int TM) { return sizeof(float) * kDmaStages * dma_stage_floats(TM); }
 
 // s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and for
 // nothing else
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-template <bool ACT>
+// TM = samples per tile: 128, or 64 for layers whose 128-sample tiles would leave the last round of
+// the persistent workgroups mostly empty (the host chooses).  With 64 a consumer's quadrant is
+// 32 x 64 (1 x 2 accumulators), everything else alike.
+template <bool ACT, int TM>
 __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __restrict__ X, int ldx, int S,
                                                                  const float* __restrict__ W, int ldw,
                                                                  const float* __restrict__ b, int n_in, int n_out,
                                                                  float* __restrict__ Y, int ldy, int nx, int ntiles,
                                                                  const float* __restrict__ zeros) {
+    static_assert(TM == 128 || TM == 64, "two or one 32-row block per consumer");
+    constexpr int NA = TM / 64;                     // 32-row blocks of samples per consumer
+    constexpr int kXLoads = TM / 32;                // loads of eight sample rows per producer and chunk
+    constexpr int kWLoads = kBatchTile / 32;        // loads of eight weight rows per producer and chunk
+    constexpr int kLoads = kXLoads + kWLoads;
+    constexpr int kXop = TM * kDmaK;                // floats of the sample rows of a stage
+    constexpr int kStage = dma_stage_floats(TM);
     extern __shared__ __attribute__((aligned(16))) float lds_batch[];
     typedef const __attribute__((address_space(1))) void* gptr;
     typedef __attribute__((address_space(3))) void* lptr;
@@ -225,44 +236,52 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
     if (total == 0) return;                 // (the whole workgroup: no barrier is left behind)
 
     if (wave >= 4) {
-        // ---- producer: wavefront pw brings rows 32 pw .. 32 pw + 31 of both operands, eight rows a load
+        // ---- producer: wavefront pw brings a quarter of the rows of both operands, eight rows a load
         const int pw = wave - 4;
         const int prow = lane >> 3, pslot = lane & 7;
         int ptile = 0, pchunk = 0, pleft = total;   // next chunk to load; chunks not loaded yet
         // byte offsets from the (uniform) operand pointers: 32 bits each, so that a load is one
         // instruction with a scalar base and no address arithmetic on the vector unit
-        unsigned xoff[4], woff[4], xrow[4], qoff[4];
+        unsigned xoff[kXLoads], xrow[kXLoads], xq[kXLoads], woff[kWLoads], wq[kWLoads];
         auto tile_offsets = [&]() {
             const int tile = (int)blockIdx.x + ptile * (int)gridDim.x;
-            const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
+            const int s0 = (tile / nx) * TM, j0 = (tile % nx) * kBatchTile;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = 32 * pw + 8 * r + prow;
-                qoff[r] = 4u * (unsigned)(pslot ^ ((row >> 1) & 7));   // first k of this lane's float4 in the chunk
+            for (int r = 0; r < kXLoads; ++r) {
+                const int row = 8 * kXLoads * pw + 8 * r + prow;
+                xq[r] = 4u * (unsigned)(pslot ^ ((row >> 1) & 7));   // first k of this lane's float4 in the chunk
                 xrow[r] = 4u * (unsigned)min(s0 + row, S - 1) * (unsigned)ldx;
-                xoff[r] = xrow[r] + 4u * qoff[r];
-                woff[r] = 4u * ((unsigned)min(j0 + row, n_out - 1) * (unsigned)ldw + qoff[r]);
+                xoff[r] = xrow[r] + 4u * xq[r];
+            }
+#pragma unroll
+            for (int r = 0; r < kWLoads; ++r) {
+                const int row = 8 * kWLoads * pw + 8 * r + prow;
+                wq[r] = 4u * (unsigned)(pslot ^ ((row >> 1) & 7));
+                woff[r] = 4u * ((unsigned)min(j0 + row, n_out - 1) * (unsigned)ldw + wq[r]);
             }
         };
         auto load_next = [&](int stage) {
             const int k0 = pchunk * kDmaK;
-            float* xs = lds_batch + stage * 2 * kDmaOperand + (32 * pw) * kDmaK;
-            float* ws = xs + kDmaOperand;
+            float* xs = lds_batch + stage * kStage + (8 * kXLoads * pw) * kDmaK;
+            float* ws = lds_batch + stage * kStage + kXop + (8 * kWLoads * pw) * kDmaK;
             const char* Xk = reinterpret_cast<const char*>(X + k0);
             const char* Wk = reinterpret_cast<const char*>(W + k0);
             if (k0 + kDmaK <= n_in) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
+                for (int r = 0; r < kXLoads; ++r)
                     __builtin_amdgcn_global_load_lds((gptr)(Xk + xoff[r]), (lptr)(xs + 8 * r * kDmaK), 16, 0, 0);
+#pragma unroll
+                for (int r = 0; r < kWLoads; ++r)
                     __builtin_amdgcn_global_load_lds((gptr)(Wk + woff[r]), (lptr)(ws + 8 * r * kDmaK), 16, 0, 0);
-                }
             } else {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const bool in = k0 + (int)qoff[r] < n_in;
-                    const char* xp = in ? Xk + xoff[r] : reinterpret_cast<const char*>(X) + xrow[r];
-                    const char* wp = in ? Wk + woff[r] : reinterpret_cast<const char*>(zeros);
+                for (int r = 0; r < kXLoads; ++r) {
+                    const char* xp = k0 + (int)xq[r] < n_in ? Xk + xoff[r] : reinterpret_cast<const char*>(X) + xrow[r];
                     __builtin_amdgcn_global_load_lds((gptr)xp, (lptr)(xs + 8 * r * kDmaK), 16, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < kWLoads; ++r) {
+                    const char* wp = k0 + (int)wq[r] < n_in ? Wk + woff[r] : reinterpret_cast<const char*>(zeros);
                     __builtin_amdgcn_global_load_lds((gptr)wp, (lptr)(ws + 8 * r * kDmaK), 16, 0, 0);
                 }
             }
@@ -280,12 +299,12 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
         load_next(0);
         load_next(1);
         load_next(2);
-        __builtin_amdgcn_s_waitcnt(vmcnt_only(8));   // chunks 0 and 1 have landed
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(kLoads));   // chunks 0 and 1 have landed
         __builtin_amdgcn_s_barrier();
         int stage = 3;   // (i + 3) % 4
         for (int i = 0; i < total; ++i) {
             load_next(stage);
-            __builtin_amdgcn_s_waitcnt(vmcnt_only(8));   // all but the eight loads just issued: chunk i + 2 has landed
+            __builtin_amdgcn_s_waitcnt(vmcnt_only(kLoads));   // all but the loads just issued: chunk i + 2 has landed
             stage = (stage + 1) & (kDmaStages - 1);
             __builtin_amdgcn_s_barrier();
         }
@@ -293,25 +312,26 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
         return;
     }
 
-    // ---- consumer
-    const int sw = (wave & 1) * 64, jw = ((wave >> 1) & 1) * 64;
+    // ---- consumer: quadrant (wave & 1, wave >> 1) of 32 NA samples x 64 neurons
+    const int sw = (wave & 1) * (32 * NA), jw = ((wave >> 1) & 1) * 64;
     const int lrow = lane & 31, half = lane >> 5, swz = (lrow >> 1) & 7;
     int slot[kDmaK / 8];   // float offset, inside a row, of the float4 this lane feeds to group m
 #pragma unroll
     for (int m = 0; m < kDmaK / 8; ++m) slot[m] = 4 * ((m + 4 * half) ^ swz);
     const float* xs0 = lds_batch + (sw + lrow) * kDmaK;
-    const float* ws0 = lds_batch + kDmaOperand + (jw + lrow) * kDmaK;
+    const float* ws0 = lds_batch + kXop + (jw + lrow) * kDmaK;
     __syncthreads();
     // operands of the next group of matrix instructions, read one group ahead
-    floatx4 pa0 = *reinterpret_cast<const floatx4*>(xs0 + slot[0]);
-    floatx4 pa1 = *reinterpret_cast<const floatx4*>(xs0 + 32 * kDmaK + slot[0]);
-    floatx4 pw0 = *reinterpret_cast<const floatx4*>(ws0 + slot[0]);
-    floatx4 pw1 = *reinterpret_cast<const floatx4*>(ws0 + 32 * kDmaK + slot[0]);
+    floatx4 pa[NA], pw0, pw1;
+#pragma unroll
+    for (int a = 0; a < NA; ++a) pa[a] = *reinterpret_cast<const floatx4*>(xs0 + 32 * a * kDmaK + slot[0]);
+    pw0 = *reinterpret_cast<const floatx4*>(ws0 + slot[0]);
+    pw1 = *reinterpret_cast<const floatx4*>(ws0 + 32 * kDmaK + slot[0]);
     int stage = 0;   // i % 4 of iteration i
     for (int t = 0; t < my_tiles; ++t) {
-        floatx16 acc[2][2];
+        floatx16 acc[NA][2];
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -322,32 +342,32 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
         __builtin_amdgcn_s_waitcnt(0xc07f);
         for (int cc = 0; cc < nchunks; ++cc) {
             const int stage1 = (stage + 1) & (kDmaStages - 1);
-            const float* xs = xs0 + stage * 2 * kDmaOperand;
-            const float* ws = ws0 + stage * 2 * kDmaOperand;
             // the first group of the next chunk sits in the next stage, complete since the last barrier
-            const float* xn = xs0 + stage1 * 2 * kDmaOperand;
-            const float* wn = ws0 + stage1 * 2 * kDmaOperand;
+            const float* xs = xs0 + stage * kStage;
+            const float* ws = ws0 + stage * kStage;
+            const float* xn = xs0 + stage1 * kStage;
+            const float* wn = ws0 + stage1 * kStage;
 #pragma unroll
             for (int m = 0; m < kDmaK / 8; ++m) {
-                const floatx4 a0 = pa0, a1 = pa1, w0 = pw0, w1 = pw1;
-                if (m + 1 < kDmaK / 8) {
-                    pa0 = *reinterpret_cast<const floatx4*>(xs + slot[m + 1]);
-                    pa1 = *reinterpret_cast<const floatx4*>(xs + 32 * kDmaK + slot[m + 1]);
-                    pw0 = *reinterpret_cast<const floatx4*>(ws + slot[m + 1]);
-                    pw1 = *reinterpret_cast<const floatx4*>(ws + 32 * kDmaK + slot[m + 1]);
-                } else {
-                    pa0 = *reinterpret_cast<const floatx4*>(xn + slot[0]);
-                    pa1 = *reinterpret_cast<const floatx4*>(xn + 32 * kDmaK + slot[0]);
-                    pw0 = *reinterpret_cast<const floatx4*>(wn + slot[0]);
-                    pw1 = *reinterpret_cast<const floatx4*>(wn + 32 * kDmaK + slot[0]);
-                }
+                floatx4 av[NA];
+#pragma unroll
+                for (int a = 0; a < NA; ++a) av[a] = pa[a];
+                const floatx4 w0 = pw0, w1 = pw1;
+                const float* xr = (m + 1 < kDmaK / 8) ? xs : xn;
+                const float* wr = (m + 1 < kDmaK / 8) ? ws : wn;
+                const int sl = slot[(m + 1) % (kDmaK / 8)];
+#pragma unroll
+                for (int a = 0; a < NA; ++a) pa[a] = *reinterpret_cast<const floatx4*>(xr + 32 * a * kDmaK + sl);
+                pw0 = *reinterpret_cast<const floatx4*>(wr + sl);
+                pw1 = *reinterpret_cast<const floatx4*>(wr + 32 * kDmaK + sl);
                 __builtin_amdgcn_sched_barrier(0);   // the reads go out before the matrix instructions, not after
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w0[e], acc[0][0], 0, 0, 0);
-                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[e], w1[e], acc[0][1], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w0[e], acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[e], w1[e], acc[1][1], 0, 0, 0);
+#pragma unroll
+                    for (int a = 0; a < NA; ++a) {
+                        acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a][e], w0[e], acc[a][0], 0, 0, 0);
+                        acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a][e], w1[e], acc[a][1], 0, 0, 0);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -357,8 +377,8 @@ __global__ __launch_bounds__(kDmaThreads) void k_layer_batch_dma(const float* __
         // the tile is complete: bias, activation, store (the producers are already filling the ring
         // for the next tile)
         const int tile = (int)blockIdx.x + t * (int)gridDim.x;
-        const int s0 = (tile / nx) * kBatchTile, j0 = (tile % nx) * kBatchTile;
-        store_quadrant<ACT>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
+        const int s0 = (tile / nx) * TM, j0 = (tile % nx) * kBatchTile;
+        store_quadrant<ACT, NA>(acc, b, Y, ldy, S, n_out, s0 + sw, j0 + jw, lane);
     }
 }
 
