@@ -28,19 +28,6 @@ constexpr int kBatchThreads = 256;
 constexpr int kBatchRows = kBatchTile * kBatchK / kBatchThreads;   // elements of each operand tile a thread stages per chunk
 constexpr int kBatchSamples = 16384;    // samples per pass through the layers (sizes the activation buffers)
 
-// The activation for the batched passes: act_fast with the hardware reciprocal (one ulp) in place
-// of the division, under half the instructions; only class labels come out of these passes.
-__device__ __forceinline__ float act_batch(float a) {
-    const float t = kB * a;
-    const float at = fabsf(t);
-    const float e = __expf(2.0f * at);
-    const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
-    const float t2 = t * t;
-    const float small = at * fmaf(t2, fmaf(t2, fmaf(t2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
-    const float r = (at < 0.125f) ? small : big;
-    return kA * copysignf(r, t);
-}
-
 // End of a tile for one wavefront: its quadrant of 32 NA samples x 64 neurons (NA x 2 accumulators,
 // first sample s_base, first neuron j_base) gets bias and activation and goes to Y.  The two bias values are pinned in
 // registers before the first guarded store: a guard that were the first to touch them would make
@@ -69,7 +56,7 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[NA][2], con
                 for (int r = 0; r < 16; ++r) {
                     const int ds = 32 * a + (r & 3) + 8 * (r >> 2);   // sample of this element, from the lane's first
                     const float v = acc[a][c][r] + bj[c];
-                    *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_batch(v) : v;
+                    *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_fast(v) : v;
                 }
         return;
     }
@@ -83,7 +70,7 @@ __device__ __forceinline__ void store_quadrant(const floatx16 (&acc)[NA][2], con
                 const int ds = 32 * a + (r & 3) + 8 * (r >> 2);
                 if (j < n_out && sl + ds < S) {
                     const float v = acc[a][c][r] + bj[c];
-                    *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_batch(v) : v;
+                    *reinterpret_cast<float*>(Yb + (at + (unsigned)ds * pitch + 128u * c)) = ACT ? act_fast(v) : v;
                 }
             }
     }

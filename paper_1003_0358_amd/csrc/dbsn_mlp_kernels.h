@@ -51,13 +51,14 @@ __device__ inline float wave_sum(float v) {
 }
 __device__ inline float act(float a) { return kA * tanhf(kB * a); }
 // y(a) = A tanh(B a) without the library routine: tanh(t) = 1 - 2 / (exp(2t) + 1) away from zero,
-// the odd Taylor polynomial up to t^7 below |t| = 0.125 (where the first form would cancel).
-// Absolute error below 3e-7 on the whole axis.
+// the odd Taylor polynomial up to t^7 below |t| = 0.125 (where the first form would cancel); the
+// quotient through the hardware reciprocal (one ulp, a tenth of the instructions of a division).
+// Absolute error below 4e-7 on the whole axis.
 __device__ inline float act_fast(float a) {
     const float t = kB * a;
     const float at = fabsf(t);
     const float e = __expf(2.0f * at);
-    const float big = 1.0f - __fdividef(2.0f, e + 1.0f);
+    const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
     const float t2 = t * t;
     const float small = at * fmaf(t2, fmaf(t2, fmaf(t2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
     const float r = (at < 0.125f) ? small : big;
