@@ -58,7 +58,13 @@ typedef struct {
     float   gamma_pct;
     int32_t ktaps;
     int32_t shear;
+    int32_t kernel;   /* DBSN_DEFORM_KERNEL_*: which of two kernels with bit-identical results runs */
 } dbsn_deform_params;
+
+/* AUTO: the kernel specialised for the paper's 21 taps when ktaps == 21, the general one otherwise.
+ * GENERAL: the general kernel whatever ktaps is (for comparing the two). */
+#define DBSN_DEFORM_KERNEL_AUTO    0
+#define DBSN_DEFORM_KERNEL_GENERAL 1
 
 /* Execution mode of dbsn_bp_steps / dbsn_bp_step.  0: one kernel launch per layer phase;
  * 1 (default): one persistent kernel per call, whose workgroups hand partial sums to each other
@@ -94,7 +100,8 @@ int32_t dbsn_mlp_get_weights(dbsn_mlp* mlp, int32_t layer, float* W_host, float*
 
 /* State left by the last dbsn_bp_step / dbsn_forward, for inspection: x_host[n_l] = outputs of
  * layer `layer` (1 .. L-1: scaled-tanh activations; L: softmax probabilities); d_host[n_l] =
- * deltas of layer `layer` (1 .. L) of the last bp step.  Synchronise the stream. */
+ * deltas of layer `layer` (1 .. L) of the last bp step (dbsn_forward leaves them alone).
+ * Synchronise the stream. */
 int32_t dbsn_mlp_get_activations(dbsn_mlp* mlp, int32_t layer, float* x_host);
 int32_t dbsn_mlp_get_deltas(dbsn_mlp* mlp, int32_t layer, float* d_host);
 
@@ -105,6 +112,21 @@ int32_t dbsn_mlp_set_mode(dbsn_mlp* mlp, int32_t mode);
  * it gives up (default 2^22, seconds of waiting).  Exists so that the time-out path can be
  * exercised from the host. */
 int32_t dbsn_mlp_set_spin_limit(dbsn_mlp* mlp, uint32_t polls);
+
+/* The pauses of the persistent kernel (see dbsn_mlp_autotune), in units of 64 shader clocks, 0 .. 48:
+ * fwd_host[l-1] for the forward phase of layer l = 1 .. L (L: the output phase), bwd_host[l-1] for
+ * the backward phase of layer l; either pointer may be NULL to leave / skip that direction.  Speed
+ * only: results never depend on them.  Defaults: 17 forward, 0 backward. */
+int32_t dbsn_mlp_set_pauses(dbsn_mlp* mlp, const int32_t* fwd_host, const int32_t* bwd_host);
+int32_t dbsn_mlp_get_pauses(dbsn_mlp* mlp, int32_t* fwd_host, int32_t* bwd_host);
+
+/* Variant of the persistent kernel, for measurements and tests (the default, chosen at
+ * dbsn_mlp_init, is the fastest the network allows).  stationary = 1: the weights of the hidden
+ * layers stay in registers for the whole call when they all fit (58 MB; else as 0); 0: every phase
+ * loads its tile from memory and the backward phase stores it back.  fixed_layout = 1: networks
+ * that fit one of the compiled register layouts use it; 0: register groups packed at run time.
+ * All variants give the same floats.  Synchronises the stream. */
+int32_t dbsn_mlp_set_variant(dbsn_mlp* mlp, int32_t stationary, int32_t fixed_layout);
 
 /* Optional tuning of the persistent kernel for this network on this device.  Between the phases
  * of a step a workgroup pauses before it first looks for the partial sums of the phase before (a
@@ -141,6 +163,17 @@ int32_t dbsn_deform_batch_beta(const dbsn_deform_params* params_host, const uint
                                const float* beta_deg_dev, int64_t n, uint64_t seed, uint64_t first_index,
                                float* dst_dev, void* hip_stream);
 
+/* The same with the bound of the angle following the class label of each image (section
+ * "Deforming images ..."): look-alike classes are rotated or sheared less than the others; the
+ * paper uses 7.5 degrees for the digits 1 and 7 and 15 degrees otherwise.  labels_dev: [n] int32
+ * (device); an image whose class c (0 .. 63) has bit c set in similar_mask takes
+ * beta_similar_deg, every other image (any other label included) params->beta_deg.
+ * The paper's rule: similar_mask = (1 << 1) | (1 << 7), beta_similar_deg = 7.5, beta_deg = 15. */
+int32_t dbsn_deform_batch_labels(const dbsn_deform_params* params_host, const uint8_t* src_dev,
+                                 const int32_t* labels_dev, uint64_t similar_mask, float beta_similar_deg,
+                                 int64_t n, uint64_t seed, uint64_t first_index, float* dst_dev,
+                                 void* hip_stream);
+
 /* n on-line back-propagation steps, strictly in order (sections "Architectures", "Training
  * algorithm"; appendix "Forward propagation", "Backward propagation", "Weight updating"): for
  * each sample, forward through scaled-tanh hidden layers y = 1.7159 tanh(0.6666 a) and a softmax
@@ -167,6 +200,16 @@ int32_t dbsn_forward(dbsn_mlp* mlp, const float* sample_dev, float* probs_dev);
  * samples_dev is 16-byte aligned (other shapes take a slower kernel, same results).  Asynchronous
  * on the network's stream; n == 0 is a no-op. */
 int32_t dbsn_classify(dbsn_mlp* mlp, const float* samples_dev, int64_t n, int32_t* labels_out_dev);
+
+/* Error count of a validation or test pass (section "Results"): *count_dev (int64, device, 8-byte
+ * aligned) = number of s < n with predicted_dev[s] != labels_dev[s] (both [n] int32, device).
+ * n == 0 writes 0.  Asynchronous on hip_stream. */
+int32_t dbsn_count_errors(const int32_t* predicted_dev, const int32_t* labels_dev, int64_t n,
+                          int64_t* count_dev, void* hip_stream);
+
+/* Mean of the per-step losses of an epoch: *mean_dev (float, device) = the sum of loss_dev[0 .. n)
+ * taken in binary64 in a fixed order, divided by n, rounded to binary32.  n >= 1. */
+int32_t dbsn_mean_loss(const float* loss_dev, int64_t n, float* mean_dev, void* hip_stream);
 
 /* Message for the last error on this host thread ("" if none). */
 const char* dbsn_last_error(void);

@@ -165,6 +165,18 @@ class Oracle:
                                                           C.c_int64(samples.shape[0]), _p(out, C.c_int32))
         return out
 
+    def logits_batch(self, sizes, params, samples, mode="f64"):
+        """Output-layer pre-activations of every sample: [n, classes]."""
+        dt, ct = self._t(mode)
+        s, sp, ns = self._sizes(sizes)
+        params = np.ascontiguousarray(params, dtype=dt)
+        samples = np.ascontiguousarray(samples, dtype=dt).reshape(-1, sizes[0])
+        assert params.size == self.param_count(sizes)
+        out = np.empty((samples.shape[0], sizes[-1]), dtype=dt)
+        getattr(self.lib, "dbsn_oracle_logits_batch_" + mode)(sp, ns, _p(params, ct), _p(samples, ct),
+                                                              C.c_int64(samples.shape[0]), _p(out, ct))
+        return out
+
     def act(self, a, mode="f64"):
         return getattr(self.lib, "dbsn_oracle_act_" + mode)(a)
 

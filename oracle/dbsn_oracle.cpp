@@ -183,6 +183,26 @@ void classify(const int32_t* sizes, int32_t n_sizes, const T* params, const T* s
     }
 }
 
+/* Output-layer pre-activations (logits) of n samples, sample by sample through
+ * forward(); the samples are independent, so they may be dealt to threads (each
+ * sample is then propagated by one thread, sums in the same order as ever). */
+template <class T>
+void logits_batch(const int32_t* sizes, int32_t n_sizes, const T* params, const T* samples, int64_t n, T* out) {
+    const int L = n_sizes - 1;
+    int64_t nact = 0;
+    for (int l = 1; l <= L; ++l) nact += sizes[l];
+    const int threads = g_threads;
+#pragma omp parallel num_threads(threads) if (threads > 1)
+    {
+        std::vector<T> acts(nact), probs(sizes[L]);
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t s = 0; s < n; ++s) {
+            forward<T>(sizes, n_sizes, params, samples + s * sizes[0], acts.data(), probs.data());
+            for (int k = 0; k < sizes[L]; ++k) out[s * sizes[L] + k] = acts[nact - sizes[L] + k];
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------
  * Deformation (section "Deforming images ...", appendix "Deformations").
  * ---------------------------------------------------------------------- */
@@ -392,6 +412,10 @@ void dbsn_oracle_init_params_f32(const int32_t* sizes, int32_t n_sizes, uint64_t
     void dbsn_oracle_classify_##SUF(const int32_t* sizes, int32_t n_sizes, const T* params, const T* samples,       \
                                     int64_t n, int32_t* out) {                                                      \
         classify<T>(sizes, n_sizes, params, samples, n, out);                                                       \
+    }                                                                                                               \
+    void dbsn_oracle_logits_batch_##SUF(const int32_t* sizes, int32_t n_sizes, const T* params, const T* samples,   \
+                                        int64_t n, T* out) {                                                        \
+        logits_batch<T>(sizes, n_sizes, params, samples, n, out);                                                   \
     }                                                                                                               \
     T dbsn_oracle_act_##SUF(T a) { return act<T>(a); }                                                              \
     T dbsn_oracle_dact_from_y_##SUF(T y) { return dact_from_y<T>(y); }                                              \

@@ -18,14 +18,17 @@ MODE_LAUNCHES, MODE_PERSISTENT = 0, 1
 SYMBOLS = [
     "dbsn_mlp_arena_bytes", "dbsn_mlp_init", "dbsn_mlp_free", "dbsn_mlp_set_weights", "dbsn_mlp_get_weights",
     "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
-    "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify",
+    "dbsn_mlp_set_pauses", "dbsn_mlp_get_pauses", "dbsn_mlp_set_variant",
+    "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_deform_batch_labels",
+    "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_count_errors", "dbsn_mean_loss",
     "dbsn_last_error",
 ]
+DEFORM_KERNEL_AUTO, DEFORM_KERNEL_GENERAL = 0, 1
 
 
 class DeformParams(C.Structure):
     _fields_ = [("sigma", C.c_float), ("alpha", C.c_float), ("beta_deg", C.c_float), ("gamma_pct", C.c_float),
-                ("ktaps", C.c_int32), ("shear", C.c_int32)]
+                ("ktaps", C.c_int32), ("shear", C.c_int32), ("kernel", C.c_int32)]
 
 
 class DbsnError(RuntimeError):
@@ -64,10 +67,16 @@ class Lib:
         c.dbsn_mlp_get_deltas.argtypes = [vp, i32, vp]
         c.dbsn_mlp_set_mode.argtypes = [vp, i32]
         c.dbsn_mlp_set_spin_limit.argtypes = [vp, C.c_uint32]
+        c.dbsn_mlp_set_pauses.argtypes = [vp, vp, vp]
+        c.dbsn_mlp_get_pauses.argtypes = [vp, vp, vp]
+        c.dbsn_mlp_set_variant.argtypes = [vp, i32, i32]
         c.dbsn_mlp_status.argtypes = [vp]
         c.dbsn_mlp_autotune.argtypes = [vp, vp, vp, i64]
         c.dbsn_deform_batch.argtypes = [C.POINTER(DeformParams), vp, i64, u64, u64, vp, vp]
         c.dbsn_deform_batch_beta.argtypes = [C.POINTER(DeformParams), vp, vp, i64, u64, u64, vp, vp]
+        c.dbsn_deform_batch_labels.argtypes = [C.POINTER(DeformParams), vp, vp, u64, f32, i64, u64, u64, vp, vp]
+        c.dbsn_count_errors.argtypes = [vp, vp, i64, vp, vp]
+        c.dbsn_mean_loss.argtypes = [vp, i64, vp, vp]
         c.dbsn_bp_steps.argtypes = [vp, vp, vp, i64, f32, vp]
         c.dbsn_bp_step.argtypes = [vp, vp, i32, f32]
         c.dbsn_forward.argtypes = [vp, vp, vp]
@@ -121,6 +130,15 @@ class Lib:
     def mlp_status(self, h):
         return self.c.dbsn_mlp_status(h)
 
+    def mlp_set_pauses(self, h, fwd_host, bwd_host):
+        return self.c.dbsn_mlp_set_pauses(h, _ptr(fwd_host), _ptr(bwd_host))
+
+    def mlp_get_pauses(self, h, fwd_host, bwd_host):
+        return self.c.dbsn_mlp_get_pauses(h, _ptr(fwd_host), _ptr(bwd_host))
+
+    def mlp_set_variant(self, h, stationary, fixed_layout):
+        return self.c.dbsn_mlp_set_variant(h, stationary, fixed_layout)
+
     def mlp_autotune(self, h, samples, labels, n):
         return self.c.dbsn_mlp_autotune(h, _ptr(samples), _ptr(labels), n)
 
@@ -131,6 +149,18 @@ class Lib:
     def deform_batch_beta(self, params, src, beta_deg, n, seed, first_index, dst, stream=0):
         return self.c.dbsn_deform_batch_beta(C.byref(params) if params is not None else None, _ptr(src),
                                              _ptr(beta_deg), n, seed, first_index, _ptr(dst), C.c_void_p(stream))
+
+    def deform_batch_labels(self, params, src, labels, similar_mask, beta_similar_deg, n, seed, first_index, dst,
+                            stream=0):
+        return self.c.dbsn_deform_batch_labels(C.byref(params) if params is not None else None, _ptr(src),
+                                               _ptr(labels), similar_mask, beta_similar_deg, n, seed, first_index,
+                                               _ptr(dst), C.c_void_p(stream))
+
+    def count_errors(self, predicted, labels, n, count, stream=0):
+        return self.c.dbsn_count_errors(_ptr(predicted), _ptr(labels), n, _ptr(count), C.c_void_p(stream))
+
+    def mean_loss(self, loss, n, mean, stream=0):
+        return self.c.dbsn_mean_loss(_ptr(loss), n, _ptr(mean), C.c_void_p(stream))
 
     def bp_steps(self, h, samples, labels, n, eta, loss=None):
         return self.c.dbsn_bp_steps(h, _ptr(samples), _ptr(labels), n, eta, _ptr(loss))
@@ -158,19 +188,10 @@ def load():
 
 def default_deform_params():
     """sigma 6, alpha 36, rotation +-7.5 degrees, scaling +-15 %, 21 taps (values the paper reports using)."""
-    return DeformParams(6.0, 36.0, 7.5, 15.0, 21, 0)
+    return DeformParams(6.0, 36.0, 7.5, 15.0, 21, 0, 0)
 
 
-def beta_for_labels(labels, similar=(1, 7), beta_similar=7.5, beta_other=15.0):
-    """Per-image bound of the rotation / shear angle from the class labels: the paper deforms the
-    look-alike digits 1 and 7 less (7.5 degrees) than the others (15 degrees).  labels: integer
-    device tensor [n] -> float32 device tensor [n]."""
-    import torch
-    hit = torch.zeros_like(labels, dtype=torch.bool)
-    for k in similar:
-        hit |= labels == k
-    return torch.where(hit, torch.tensor(beta_similar, device=labels.device),
-                       torch.tensor(beta_other, device=labels.device)).to(torch.float32).contiguous()
+PAPER_SIMILAR_MASK = (1 << 1) | (1 << 7)   # the look-alike digits 1 and 7 (section "Deforming images ...")
 
 
 class Mlp:
@@ -207,6 +228,21 @@ class Mlp:
 
     def status(self):
         self.lib.check(self.lib.mlp_status(self.h))
+
+    def set_variant(self, stationary=True, fixed_layout=True):
+        self.lib.check(self.lib.mlp_set_variant(self.h, int(stationary), int(fixed_layout)))
+
+    def get_pauses(self):
+        f = np.zeros(self.L, np.int32)
+        b = np.zeros(self.L, np.int32)
+        self.lib.check(self.lib.mlp_get_pauses(self.h, f, b))
+        return f, b
+
+    def set_pauses(self, fwd=None, bwd=None):
+        f = None if fwd is None else np.ascontiguousarray(fwd, dtype=np.int32)
+        b = None if bwd is None else np.ascontiguousarray(bwd, dtype=np.int32)
+        assert (f is None or f.size == self.L) and (b is None or b.size == self.L)
+        self.lib.check(self.lib.mlp_set_pauses(self.h, f, b))
 
     def autotune(self, samples, labels):
         """Tunes the persistent kernel's pauses on these samples (steps with eta = 0: weights unchanged)."""
@@ -268,9 +304,12 @@ class Mlp:
         return out
 
 
-def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None, beta_deg=None):
+def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None, beta_deg=None, labels=None,
+                 similar_mask=PAPER_SIMILAR_MASK, beta_similar_deg=None):
     """src_u8: uint8 device tensor [n, 784] -> float32 device tensor [n, 784].  beta_deg: optional
-    float32 device tensor [n], one bound of the angle per image instead of params.beta_deg."""
+    float32 device tensor [n], one bound of the angle per image instead of params.beta_deg.
+    labels: optional int32 device tensor [n]: images of the classes in similar_mask take
+    beta_similar_deg (default: half of params.beta_deg), all others params.beta_deg."""
     import torch
     lib = load()
     n = src_u8.shape[0]
@@ -279,9 +318,33 @@ def deform_batch(src_u8, seed, first_index, params=None, out=None, stream=None, 
     if stream is None:
         stream = torch.cuda.current_stream(src_u8.device).cuda_stream
     params = params or default_deform_params()
-    if beta_deg is None:
-        lib.check(lib.deform_batch(params, src_u8, n, seed, first_index, out, stream))
-    else:
+    if beta_deg is not None:
         assert beta_deg.dtype == torch.float32 and beta_deg.numel() == n and beta_deg.is_contiguous()
         lib.check(lib.deform_batch_beta(params, src_u8, beta_deg, n, seed, first_index, out, stream))
+    elif labels is not None:
+        assert labels.dtype == torch.int32 and labels.numel() == n and labels.is_contiguous()
+        bs = 0.5 * params.beta_deg if beta_similar_deg is None else beta_similar_deg
+        lib.check(lib.deform_batch_labels(params, src_u8, labels, similar_mask, bs, n, seed, first_index, out, stream))
+    else:
+        lib.check(lib.deform_batch(params, src_u8, n, seed, first_index, out, stream))
     return out
+
+
+def count_errors(predicted, labels):
+    """Number of positions where two int32 device tensors differ (one small kernel + one read-back)."""
+    import torch
+    lib = load()
+    n = predicted.numel()
+    assert labels.numel() == n and predicted.dtype == torch.int32 and labels.dtype == torch.int32
+    out = torch.empty(1, dtype=torch.int64, device=predicted.device)
+    lib.check(lib.count_errors(predicted, labels, n, out, torch.cuda.current_stream(predicted.device).cuda_stream))
+    return int(out.item())
+
+
+def mean_loss(loss):
+    """Mean of a float32 device tensor of per-step losses (one small kernel + one read-back)."""
+    import torch
+    lib = load()
+    out = torch.empty(1, dtype=torch.float32, device=loss.device)
+    lib.check(lib.mean_loss(loss, loss.numel(), out, torch.cuda.current_stream(loss.device).cuda_stream))
+    return float(out.item())

@@ -8,16 +8,17 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
 #include <vector>
 
+#include "dbsn_plan.h"
 #include "dbsn_deform_kernels.h"
 #include "dbsn_mlp_kernels.h"
 #include "dbsn_batch_kernels.h"
 #include "dbsn_persistent_kernel.h"
+#include "dbsn_reduce_kernels.h"
 
 using namespace dbsn;
 
@@ -41,100 +42,7 @@ int32_t fail(int32_t code, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(DBSN_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr size_t kAlign = 256;
-size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
-constexpr int kZerosAt = 16;         // four ints of the flag block that stay zero (a float4 of zeros for the kernels)
-constexpr int kArenaGroups = 512;  // partial-sum rows the arena is sized for (>= workgroups launched)
-
-bool shape_ok(const int32_t* sizes, int32_t n_sizes) {
-    if (!sizes || n_sizes < 2 || n_sizes > DBSN_MAX_LAYERS + 1) return false;
-    for (int i = 0; i < n_sizes; ++i)
-        if (sizes[i] < 1 || sizes[i] > DBSN_MAX_WIDTH) return false;
-    return sizes[n_sizes - 1] <= DBSN_MAX_CLASSES;
-}
-
-struct ArenaPlan {
-    size_t W[kMaxLayers + 1], b[kMaxLayers + 1], x[kMaxLayers + 1], d[kMaxLayers + 1];
-    size_t yp[kMaxLayers + 1], gp[kMaxLayers + 1];
-    size_t gpart[2], flags, act[2], total;
-    int ld[kMaxLayers + 1], gld, ldact;
-    // tile geometry of the persistent kernel (hidden layers 1 .. L-1), fixed for kPGroups workgroups
-    int nCB[kMaxLayers + 1], nRB[kMaxLayers + 1], C[kMaxLayers + 1], R[kMaxLayers + 1];
-    int g0[kMaxLayers + 1], ng[kMaxLayers + 1];   // register groups of each layer's tile
-    bool persistent_ok, stationary;
-};
-
-ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
-    ArenaPlan p{};
-    size_t off = 0;
-    int maxw = 0;
-    for (int l = 1; l < n_sizes; ++l) {
-        const int nin = sizes[l - 1], nout = sizes[l];
-        p.ld[l] = (nin + 3) / 4 * 4;
-        p.W[l] = off; off = align_up(off + sizeof(float) * (size_t)nout * p.ld[l]);
-        p.b[l] = off; off = align_up(off + sizeof(float) * (size_t)nout);
-        p.x[l] = off; off = align_up(off + sizeof(float) * (size_t)nout);
-        p.d[l] = off; off = align_up(off + sizeof(float) * (size_t)nout);
-        if (nin > maxw) maxw = nin;
-    }
-    p.gld = (maxw + 63) / 64 * 64;
-    for (int k = 0; k < 2; ++k) {
-        p.gpart[k] = off;
-        off = align_up(off + sizeof(float) * (size_t)kArenaGroups * p.gld);
-    }
-    // error word of the training kernels; ints kZerosAt .. kZerosAt + 3 stay zero for good
-    p.flags = off; off = align_up(off + 256);
-    // activations of a batch of samples for the forward-only classification passes, two buffers
-    // that the layers use in turn
-    int maxo = 0;
-    for (int l = 1; l < n_sizes; ++l) maxo = sizes[l] > maxo ? sizes[l] : maxo;
-    p.ldact = (maxo + 3) / 4 * 4;
-    for (int k = 0; k < 2; ++k) {
-        p.act[k] = off;
-        off = align_up(off + sizeof(float) * (size_t)kBatchSamples * p.ldact);
-    }
-
-    // Persistent kernel: layer l is cut into nRB x nCB tiles of R rows x C <= 256 columns, one per
-    // workgroup; yp_l holds the forward partial sums [2][nCB][n_l], gp_l the backward ones
-    // [2][nRB_{l+1}][n_l], as 64-bit {tag, float} words.
-    const int L = n_sizes - 1;
-    p.persistent_ok = (L >= 2);
-    for (int l = 1; l < L; ++l) {
-        const int nin = sizes[l - 1], nout = sizes[l];
-        p.nCB[l] = (nin + 255) / 256;
-        p.C[l] = ((nin + p.nCB[l] - 1) / p.nCB[l] + 3) / 4 * 4;
-        const int rb_max = kPGroups / p.nCB[l];
-        p.R[l] = (nout + rb_max - 1) / rb_max;
-        p.nRB[l] = (nout + p.R[l] - 1) / p.R[l];
-        if (p.R[l] > kMaxTileRows || p.C[l] > 256) p.persistent_ok = false;
-    }
-    for (int l = 1; l < L; ++l) {
-        p.yp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nCB[l] * sizes[l]);
-        if (l <= L - 2) {
-            // one chunk of nRB_{l+1} x R_l words per row block, see PLayer::gp
-            p.gp[l] = off; off = align_up(off + sizeof(u64) * 2 * (size_t)p.nRB[l] * p.R[l] * p.nRB[l + 1]);
-        }
-    }
-    // register groups of kGR rows per wavefront: stationary when every layer gets groups of its own
-    int groups = 0;
-    for (int l = 1; l < L; ++l) {
-        p.ng[l] = ((p.R[l] + kWaves - 1) / kWaves + kGR - 1) / kGR;
-        if (p.ng[l] > kNG) p.persistent_ok = false;
-        groups += p.ng[l];
-    }
-    p.stationary = groups <= kNG;
-    for (int l = 1, at = 0; l < L; ++l) {
-        p.g0[l] = p.stationary ? at : 0;
-        at += p.ng[l];
-    }
-    if (L >= 2) {
-        // W_L lives in LDS with its classes padded to a multiple of four
-        if ((size_t)((sizes[L] + 3) / 4 * 4) * sizes[L - 1] > (size_t)kTopWMax || sizes[L - 1] > kTopXMax)
-            p.persistent_ok = false;
-    }
-    p.total = off;
-    return p;
-}
+constexpr size_t kAlign = kArenaAlign;
 
 }  // namespace
 
@@ -150,8 +58,7 @@ struct dbsn_mlp {
     int device = 0;
     int cus = 0;
     size_t lds_limit = 0;
-    bool persistent_ready = false;
-    bool batch_ready = false;   // LDS size of the batched classify kernel registered
+    bool persistent_ready = false;   // LDS size and residency of the selected persistent kernel checked
     int layout = 0;            // register layout of the persistent kernel (0: packed at run time)
     int* err = nullptr;
 };
@@ -166,11 +73,18 @@ int32_t launch_fwd(dbsn_mlp* m, int l, const float* x0) {
 }
 template <int NCH>
 int32_t launch_bwd(dbsn_mlp* m, int l, const float* x0, float eta) {
+    const size_t lds = sizeof(float) * (size_t)phase_lds_floats(NCH);   // (registered by allow_bwd_lds at init)
+    hipLaunchKernelGGL(k_bwd<NCH>, dim3(m->net.G), dim3(kThreads), lds, m->stream, m->net, l, x0, eta);
+    return DBSN_OK;
+}
+
+// A backward kernel whose LDS exceeds the default limit has to be told so once.
+template <int NCH>
+int32_t allow_bwd_lds() {
     const size_t lds = sizeof(float) * (size_t)phase_lds_floats(NCH);
     if (lds > 64 * 1024)
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bwd<NCH>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(k_bwd<NCH>, dim3(m->net.G), dim3(kThreads), lds, m->stream, m->net, l, x0, eta);
     return DBSN_OK;
 }
 
@@ -247,6 +161,33 @@ int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, i
     return DBSN_OK;
 }
 
+// Fills the persistent kernel's view of the network for the chosen variant: weights stationary in
+// registers or streamed per phase; register groups in a compile-time layout or packed at run time.
+void configure_persistent(dbsn_mlp* m, bool stationary, bool fixed_layout) {
+    const ArenaPlan& plan = m->plan;
+    const Net& net = m->net;
+    PNet& pn = m->pnet;
+    pn.stationary = (stationary && plan.stationary) ? 1 : 0;
+    m->layout = (pn.stationary && fixed_layout) ? choose_layout(plan, net.L) : 0;
+    for (int l = 1; l <= net.L; ++l) {
+        PLayer& P = pn.lay[l];
+        const Layer& Ly = net.lay[l];
+        P.W = Ly.W; P.b = Ly.b; P.x = Ly.x; P.d = Ly.d;
+        P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
+        if (l < net.L && plan.persistent_ok) {
+            P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
+            P.g0 = m->layout ? kLayoutG0[m->layout][l - 1] : (pn.stationary ? plan.g0[l] : 0);
+            P.ng = plan.ng[l];
+            P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
+            if (l <= net.L - 2) {
+                P.gp = reinterpret_cast<u64*>(m->arena + plan.gp[l]);
+                P.gP = plan.nRB[l + 1];
+            }
+        }
+    }
+    m->persistent_ready = false;
+}
+
 bool use_persistent(const dbsn_mlp* m) { return m->mode == DBSN_MODE_PERSISTENT && m->plan.persistent_ok; }
 
 int32_t check_mlp(dbsn_mlp* m) { return m ? DBSN_OK : fail(DBSN_E_ARG, "null network handle"); }
@@ -321,55 +262,30 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     pn.L = net.L;
     pn.err = m->err;
     pn.spin_limit = 1u << 22;
-    pn.stationary = plan.stationary ? 1 : 0;
-    int fwd_delay = 17;
-    pn.adapt = 0;
-    if (const char* e = getenv("DBSN_ADAPT")) pn.adapt = atoi(e) < 0 ? 0 : (atoi(e) > 12 ? 12 : atoi(e));
-    if (const char* e = getenv("DBSN_FWD_DELAY")) fwd_delay = atoi(e) < 0 ? 0 : (atoi(e) > 48 ? 48 : atoi(e));
+    // pauses before the first look at the partial sums of a phase, in units of 64 clocks: forward
+    // consumers arrive about half a microsecond before the other tiles' words are visible, backward
+    // ones late enough by themselves (dbsn_mlp_autotune / dbsn_mlp_set_pauses refine them)
     for (int l = 0; l <= kMaxLayers; ++l) {
-        pn.pace[0][l] = (unsigned char)fwd_delay;
+        pn.pace[0][l] = 17;
         pn.pace[1][l] = 0;
     }
-    // DBSN_PACE="f1,...,fL;b1,...,bL": one pause per forward layer (fL: the output layer), then per
-    // backward layer; layers left out keep the default
-    if (const char* e = getenv("DBSN_PACE")) {
-        int dir = 0, l = 1;
-        for (const char* c = e; *c; ++c) {
-            if (*c == ';') { dir = 1; l = 1; continue; }
-            if (*c == ',') continue;
-            if (*c >= '0' && *c <= '9') {
-                int v = 0;
-                while (*c >= '0' && *c <= '9') v = 10 * v + (*c++ - '0');
-                --c;
-                if (l <= kMaxLayers && dir < 2) pn.pace[dir][l] = (unsigned char)(v > 48 ? 48 : v);
-                ++l;
-            }
+    configure_persistent(m, true, true);
+    // kernels that need more LDS than the default limit say so once, here
+    {
+        int32_t rc = DBSN_OK;
+        for (int l = 1; l < net.L && !rc; ++l) {
+            rc = DBSN_E_SHAPE;
+            DBSN_NCH_SWITCH(16, net.lay[l].nch, rc = allow_bwd_lds<N>());
         }
-    }
-    if (const char* e = getenv("DBSN_STATIONARY")) pn.stationary = (atoi(e) != 0 && plan.stationary) ? 1 : 0;
-    // a compile-time register layout when the net is stationary and fits it
-    m->layout = 0;
-    if (pn.stationary && plan.persistent_ok && !getenv("DBSN_NO_LAYOUT")) {
-        for (int cand = 1; cand < kLayouts && m->layout == 0; ++cand) {
-            bool fits = net.L - 1 <= kLayoutDepth[cand];
-            for (int l = 1; l < net.L && fits; ++l) fits = plan.ng[l] <= kLayoutNG[cand][l - 1];
-            if (fits) m->layout = cand;
-        }
-    }
-    for (int l = 1; l <= net.L; ++l) {
-        PLayer& P = pn.lay[l];
-        const Layer& Ly = net.lay[l];
-        P.W = Ly.W; P.b = Ly.b; P.x = Ly.x; P.d = Ly.d;
-        P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
-        if (l < net.L && plan.persistent_ok) {
-            P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
-            P.g0 = m->layout ? kLayoutG0[m->layout][l - 1] : (pn.stationary ? plan.g0[l] : 0);
-            P.ng = plan.ng[l];
-            P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
-            if (l <= net.L - 2) {
-                P.gp = reinterpret_cast<u64*>(m->arena + plan.gp[l]);
-                P.gP = plan.nRB[l + 1];
-            }
+        if (!rc && hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true, 128>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(128)) != hipSuccess)
+            rc = fail(DBSN_E_HIP, "hipFuncSetAttribute(k_layer_batch_dma<128>)");
+        if (!rc && hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true, 64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(64)) != hipSuccess)
+            rc = fail(DBSN_E_HIP, "hipFuncSetAttribute(k_layer_batch_dma<64>)");
+        if (rc) {
+            delete m;
+            return rc == DBSN_E_SHAPE ? fail(rc, "unsupported layer width") : rc;
         }
     }
 
@@ -412,6 +328,42 @@ int32_t dbsn_mlp_set_mode(dbsn_mlp* m, int32_t mode) {
 int32_t dbsn_mlp_set_spin_limit(dbsn_mlp* m, uint32_t polls) {
     if (check_mlp(m)) return DBSN_E_ARG;
     m->pnet.spin_limit = polls;
+    return DBSN_OK;
+}
+
+int32_t dbsn_mlp_set_pauses(dbsn_mlp* m, const int32_t* fwd_host, const int32_t* bwd_host) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    const int L = m->net.L;
+    for (int dir = 0; dir < 2; ++dir) {
+        const int32_t* src = dir == 0 ? fwd_host : bwd_host;
+        if (!src) continue;
+        for (int l = 1; l <= L; ++l)
+            if (src[l - 1] < 0 || src[l - 1] > kPaceMax)
+                return fail(DBSN_E_ARG, "pause %d of layer %d outside 0..%d", src[l - 1], l, kPaceMax);
+    }
+    for (int dir = 0; dir < 2; ++dir) {
+        const int32_t* src = dir == 0 ? fwd_host : bwd_host;
+        if (!src) continue;
+        for (int l = 1; l <= L; ++l) m->pnet.pace[dir][l] = (unsigned char)src[l - 1];
+    }
+    return DBSN_OK;
+}
+
+int32_t dbsn_mlp_get_pauses(dbsn_mlp* m, int32_t* fwd_host, int32_t* bwd_host) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    for (int l = 1; l <= m->net.L; ++l) {
+        if (fwd_host) fwd_host[l - 1] = m->pnet.pace[0][l];
+        if (bwd_host) bwd_host[l - 1] = m->pnet.pace[1][l];
+    }
+    return DBSN_OK;
+}
+
+int32_t dbsn_mlp_set_variant(dbsn_mlp* m, int32_t stationary, int32_t fixed_layout) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    if ((stationary != 0 && stationary != 1) || (fixed_layout != 0 && fixed_layout != 1))
+        return fail(DBSN_E_ARG, "stationary and fixed_layout must be 0 or 1");
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    configure_persistent(m, stationary != 0, fixed_layout != 0);
     return DBSN_OK;
 }
 
@@ -595,13 +547,6 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
             const bool fits = (uint64_t)Ly.n_out * Ly.ld * sizeof(float) < (1ull << 32) &&
                               (uint64_t)S * std::max(ldx, ldact) * sizeof(float) < (1ull << 32);
             if (fits && ldx % 4 == 0 && Ly.ld % 4 == 0 && Ly.n_in % 4 == 0 && aligned(X, 16) && aligned(Ly.W, 16)) {
-                if (!m->batch_ready) {
-                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true, 128>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(128)));
-                    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_layer_batch_dma<true, 64>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(64)));
-                    m->batch_ready = true;
-                }
                 // tiles of 128 samples, or of 64 where that fills the rounds of the persistent
                 // workgroups better: a 64-sample tile costs a little more than half a 128-sample one
                 const int nx = (int)grid.x, G = m->cus;
@@ -638,19 +583,28 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     return DBSN_OK;
 }
 
-int32_t dbsn_deform_batch_beta(const dbsn_deform_params* p, const uint8_t* src_dev, const float* beta_deg_dev,
-                               int64_t n, uint64_t seed, uint64_t first_index, float* dst_dev, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Checks and launch shared by the three deformation calls: at most one of beta_each / labels is set.
+int32_t deform_launch(const dbsn_deform_params* p, const uint8_t* src_dev, const float* beta_deg_dev,
+                      const int32_t* labels_dev, uint64_t similar_mask, float beta_similar_deg, int64_t n,
+                      uint64_t seed, uint64_t first_index, float* dst_dev, void* hip_stream) {
     if (!p) return fail(DBSN_E_ARG, "params is null");
     if (n < 0) return fail(DBSN_E_ARG, "n is negative");
     if (p->ktaps < 1 || p->ktaps > DBSN_MAX_KTAPS || (p->ktaps & 1) == 0)
         return fail(DBSN_E_ARG, "ktaps must be odd and in 1..%d", DBSN_MAX_KTAPS);
     if (!(p->sigma >= 0.0f) || !std::isfinite(p->sigma) || !std::isfinite(p->alpha) || !std::isfinite(p->beta_deg) ||
-        !std::isfinite(p->gamma_pct))
+        !std::isfinite(p->gamma_pct) || !std::isfinite(beta_similar_deg))
         return fail(DBSN_E_ARG, "deformation parameters must be finite, sigma >= 0");
     if (p->shear != 0 && p->shear != 1) return fail(DBSN_E_ARG, "shear must be 0 or 1");
+    if (p->kernel != DBSN_DEFORM_KERNEL_AUTO && p->kernel != DBSN_DEFORM_KERNEL_GENERAL)
+        return fail(DBSN_E_ARG, "kernel must be DBSN_DEFORM_KERNEL_AUTO or DBSN_DEFORM_KERNEL_GENERAL");
     if (n == 0) return DBSN_OK;
     if (!src_dev || !dst_dev) return fail(DBSN_E_ARG, "null pointer");
-    if (!aligned(dst_dev, 4) || !aligned(beta_deg_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    if (!aligned(dst_dev, 4) || !aligned(beta_deg_dev, 4) || !aligned(labels_dev, 4))
+        return fail(DBSN_E_SHAPE, "misaligned pointer");
 
     DeformArgs a{};
     // 1-D Gaussian exp(-t^2 / (2 sigma^2)), t = -R..R, scaled to sum 1 (sigma 0: unit impulse)
@@ -668,14 +622,15 @@ int32_t dbsn_deform_batch_beta(const dbsn_deform_params* p, const uint8_t* src_d
     a.gamma_pct = p->gamma_pct;
     a.shear = p->shear;
     a.beta_each = beta_deg_dev;
+    a.labels = labels_dev;
+    a.similar_mask = similar_mask;
+    a.beta_similar = beta_similar_deg;
     a.seed = seed;
     a.first_index = first_index;
     a.n = n;
     const int blocks = (int)(n < 65536 ? n : 65536);
-    // the paper's 21 taps have a kernel of their own, same results (DBSN_DEFORM_GENERIC=1 keeps
-    // the general kernel, for comparing the two)
-    const char* generic = getenv("DBSN_DEFORM_GENERIC");
-    if (p->ktaps == 21 && !(generic && atoi(generic) != 0))
+    // the paper's 21 taps have a kernel of their own, same results bit for bit
+    if (p->ktaps == 21 && p->kernel == DBSN_DEFORM_KERNEL_AUTO)
         hipLaunchKernelGGL(k_deform_taps<21>, dim3(blocks), dim3(kDeformThreads), 0, static_cast<hipStream_t>(hip_stream),
                            a, src_dev, dst_dev);
     else
@@ -685,9 +640,50 @@ int32_t dbsn_deform_batch_beta(const dbsn_deform_params* p, const uint8_t* src_d
     return DBSN_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
 int32_t dbsn_deform_batch(const dbsn_deform_params* p, const uint8_t* src_dev, int64_t n, uint64_t seed,
                           uint64_t first_index, float* dst_dev, void* hip_stream) {
-    return dbsn_deform_batch_beta(p, src_dev, nullptr, n, seed, first_index, dst_dev, hip_stream);
+    return deform_launch(p, src_dev, nullptr, nullptr, 0, 0.0f, n, seed, first_index, dst_dev, hip_stream);
+}
+
+int32_t dbsn_deform_batch_beta(const dbsn_deform_params* p, const uint8_t* src_dev, const float* beta_deg_dev,
+                               int64_t n, uint64_t seed, uint64_t first_index, float* dst_dev, void* hip_stream) {
+    if (n > 0 && !beta_deg_dev) return fail(DBSN_E_ARG, "beta_deg_dev is null");
+    return deform_launch(p, src_dev, beta_deg_dev, nullptr, 0, 0.0f, n, seed, first_index, dst_dev, hip_stream);
+}
+
+int32_t dbsn_deform_batch_labels(const dbsn_deform_params* p, const uint8_t* src_dev, const int32_t* labels_dev,
+                                 uint64_t similar_mask, float beta_similar_deg, int64_t n, uint64_t seed,
+                                 uint64_t first_index, float* dst_dev, void* hip_stream) {
+    if (n > 0 && !labels_dev) return fail(DBSN_E_ARG, "labels_dev is null");
+    return deform_launch(p, src_dev, nullptr, labels_dev, similar_mask, beta_similar_deg, n, seed, first_index, dst_dev,
+                         hip_stream);
+}
+
+int32_t dbsn_count_errors(const int32_t* predicted_dev, const int32_t* labels_dev, int64_t n, int64_t* count_dev,
+                          void* hip_stream) {
+    if (n < 0) return fail(DBSN_E_ARG, "n is negative");
+    if (!count_dev) return fail(DBSN_E_ARG, "count_dev is null");
+    if (n > 0 && (!predicted_dev || !labels_dev)) return fail(DBSN_E_ARG, "null pointer");
+    if (!aligned(predicted_dev, 4) || !aligned(labels_dev, 4) || !aligned(count_dev, 8))
+        return fail(DBSN_E_SHAPE, "misaligned pointer");
+    hipLaunchKernelGGL(k_count_errors, dim3(1), dim3(kReduceThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       predicted_dev, labels_dev, (long long)n, reinterpret_cast<long long*>(count_dev));
+    HIP_TRY(hipGetLastError());
+    return DBSN_OK;
+}
+
+int32_t dbsn_mean_loss(const float* loss_dev, int64_t n, float* mean_dev, void* hip_stream) {
+    if (n < 1) return fail(DBSN_E_ARG, "n must be at least 1");
+    if (!loss_dev || !mean_dev) return fail(DBSN_E_ARG, "null pointer");
+    if (!aligned(loss_dev, 4) || !aligned(mean_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    hipLaunchKernelGGL(k_mean, dim3(1), dim3(kReduceThreads), 0, static_cast<hipStream_t>(hip_stream), loss_dev,
+                       (long long)n, mean_dev);
+    HIP_TRY(hipGetLastError());
+    return DBSN_OK;
 }
 
 }  // extern "C"

@@ -26,7 +26,6 @@ constexpr int kBatchK = 16;             // k-chunk staged in LDS
 constexpr int kBatchPitch = kBatchK + 1;
 constexpr int kBatchThreads = 256;
 constexpr int kBatchRows = kBatchTile * kBatchK / kBatchThreads;   // elements of each operand tile a thread stages per chunk
-constexpr int kBatchSamples = 16384;    // samples per pass through the layers (sizes the activation buffers)
 
 // End of a tile for one wavefront: its quadrant of 32 NA samples x 64 neurons (NA x 2 accumulators,
 // first sample s_base, first neuron j_base) gets bias and activation and goes to Y.  The two bias values are pinned in

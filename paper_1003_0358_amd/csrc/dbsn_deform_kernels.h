@@ -25,10 +25,39 @@ struct DeformArgs {
     int ktaps;
     float alpha, beta_deg, gamma_pct;
     int shear;                 // 0: rotation by the angle, 1: horizontal shear with tan(angle) = displacement / height
-    const float* beta_each;    // per-image bound of the angle in degrees, or null for beta_deg everywhere
+    const float* beta_each;    // per-image bound of the angle in degrees, or null
+    const int* labels;         // or: per-image class labels (null: beta_deg everywhere); an image whose class has its
+    uint64_t similar_mask;     //   bit set in similar_mask (bit c = class c < 64) takes beta_similar, any other beta_deg
+    float beta_similar;
     uint64_t seed, first_index;
     long long n;
 };
+
+// Per-image scalars of image k (one thread): the linear part p, q, r, t of the inverse map
+// (X' = p u + q v, Y' = r u + t v) and the two scale factors, formed in double from the first three
+// draws of the image's stream and rounded once to float.  The bound of the angle is the image's own
+// (beta_each), or follows its class label (section "Deforming images ...": look-alike classes are
+// rotated or sheared less), or is beta_deg.
+__device__ inline void image_affine(const DeformArgs& a, uint64_t key, long long k, float* aff) {
+    const double u0 = (double)rng_unit(rng_draw(key, 0));
+    const double u1 = (double)rng_unit(rng_draw(key, 1));
+    const double u2 = (double)rng_unit(rng_draw(key, 2));
+    double beta = (double)a.beta_deg;
+    if (a.beta_each) {
+        beta = (double)a.beta_each[k];
+    } else if (a.labels) {
+        const int c = a.labels[k];
+        if (c >= 0 && c < 64 && ((a.similar_mask >> c) & 1ull)) beta = (double)a.beta_similar;
+    }
+    const double th = beta * u0 * (3.14159265358979323846 / 180.0);
+    if (a.shear) {
+        aff[0] = 1.0f; aff[1] = (float)tan(th); aff[2] = 0.0f; aff[3] = 1.0f;
+    } else {
+        aff[0] = (float)cos(th); aff[1] = (float)(-sin(th)); aff[2] = (float)sin(th); aff[3] = (float)cos(th);
+    }
+    aff[4] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
+    aff[5] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
+}
 
 __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const uint8_t* __restrict__ src,
                                                             float* __restrict__ dst) {
@@ -46,21 +75,7 @@ __global__ __launch_bounds__(kDeformThreads) void k_deform(DeformArgs a, const u
             fx[i] = rng_unit(rng_draw(key, 3ull + (uint64_t)i));
             fy[i] = rng_unit(rng_draw(key, 3ull + (uint64_t)kPix + (uint64_t)i));
         }
-        if (threadIdx.x == 0) {
-            // per-image scalars are formed in double and rounded once to float
-            const double u0 = (double)rng_unit(rng_draw(key, 0));
-            const double u1 = (double)rng_unit(rng_draw(key, 1));
-            const double u2 = (double)rng_unit(rng_draw(key, 2));
-            const double beta = a.beta_each ? (double)a.beta_each[k] : (double)a.beta_deg;
-            const double th = beta * u0 * (3.14159265358979323846 / 180.0);
-            if (a.shear) {
-                aff[0] = 1.0f; aff[1] = (float)tan(th); aff[2] = 0.0f; aff[3] = 1.0f;
-            } else {
-                aff[0] = (float)cos(th); aff[1] = (float)(-sin(th)); aff[2] = (float)sin(th); aff[3] = (float)cos(th);
-            }
-            aff[4] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
-            aff[5] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
-        }
+        if (threadIdx.x == 0) image_affine(a, key, k, aff);
         __syncthreads();
         // row pass: along c
         for (int i = threadIdx.x; i < kPix; i += kDeformThreads) {
@@ -163,21 +178,7 @@ __global__ __launch_bounds__(kDeformThreads, 4) void k_deform_taps(DeformArgs a,
             fld[0][r][R + c] = rng_unit(rng_draw(key, 3ull + (uint64_t)i));
             fld[1][r][R + c] = rng_unit(rng_draw(key, 3ull + (uint64_t)kPix + (uint64_t)i));
         }
-        if (threadIdx.x == 0) {
-            // per-image scalars are formed in double and rounded once to float
-            const double u0 = (double)rng_unit(rng_draw(key, 0));
-            const double u1 = (double)rng_unit(rng_draw(key, 1));
-            const double u2 = (double)rng_unit(rng_draw(key, 2));
-            const double beta = a.beta_each ? (double)a.beta_each[k] : (double)a.beta_deg;
-            const double th = beta * u0 * (3.14159265358979323846 / 180.0);
-            if (a.shear) {
-                aff[0] = 1.0f; aff[1] = (float)tan(th); aff[2] = 0.0f; aff[3] = 1.0f;
-            } else {
-                aff[0] = (float)cos(th); aff[1] = (float)(-sin(th)); aff[2] = (float)sin(th); aff[3] = (float)cos(th);
-            }
-            aff[4] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u1);
-            aff[5] = (float)(1.0 + ((double)a.gamma_pct / 100.0) * u2);
-        }
+        if (threadIdx.x == 0) image_affine(a, key, k, aff);
         __syncthreads();
         // row pass: outputs (line, 4 run .. 4 run + 3) of both fields; the window starts at padded index 4 run
         if (threadIdx.x < kItems) {

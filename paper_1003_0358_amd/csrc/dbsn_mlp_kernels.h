@@ -18,15 +18,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "dbsn_plan.h"
 #include "dbsn_rng.h"
 
 namespace dbsn {
 
-constexpr int kMaxLayers = 16;
-constexpr int kThreads = 512;
-constexpr int kWaves = kThreads / 64;
-constexpr int kMaxRowsPerGroup = 256;
-constexpr int kMaxClasses = 64;
 constexpr float kA = 1.7159f;  // y(a) = A tanh(B a), section "Architectures"
 constexpr float kB = 0.6666f;
 
@@ -230,7 +226,7 @@ __device__ void top_phase(const Layer& Ly, const float* __restrict__ xin, int la
             if (k == label) pl = p;
             if (publish) Ly.x[k] = p;
             dL[k] = p - (k == label ? 1.0f : 0.0f);
-            if (publish) Ly.d[k] = dL[k];
+            if (publish && do_update) Ly.d[k] = dL[k];   // (a forward-only call leaves the last step's deltas alone)
         }
         if (publish && loss_out) *loss_out = -logf(pl);
         if (publish && label_out) *label_out = best;
@@ -266,14 +262,6 @@ __device__ void top_phase(const Layer& Ly, const float* __restrict__ xin, int la
         case 16: if constexpr (MAXNCH >= 16) { constexpr int N = 16; CALL; } break;  \
         default: break;                                             \
     }
-
-__host__ inline int nch_for(int ld) {
-    const int need = (ld + 255) / 256;
-    const int opts[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
-    for (int o : opts)
-        if (o >= need) return o;
-    return -1;
-}
 
 // ---- one kernel per phase (DBSN_MODE_LAUNCHES) --------------------------------------------
 

@@ -94,13 +94,6 @@ constexpr int kProfLdsFloats = 0;
 #endif
 #define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 8 + (sub))
 
-constexpr int kPGroups = 256;        // workgroups of the persistent kernel (tile geometry is fixed for it)
-constexpr int kGR = 2;               // rows per register group
-constexpr int kNG = 14;              // register groups per wavefront
-constexpr int kSlots = kGR * kNG;    // rows a wavefront holds: 28 (a tile has at most 8 * 28 = 224 rows)
-constexpr int kMaxTileRows = kSlots * kWaves;   // 224
-constexpr int kTopWMax = 16384;      // floats of W_L kept in LDS (rows padded to a multiple of four classes)
-constexpr int kTopXMax = 2048;       // neurons of layer L-1 the output phase can take
 constexpr int kStageFloats = kWaves * kMaxTileRows;   // per-wavefront partial deltas of a tile's rows
 static_assert(kGR == 2, "the forward reduction pairs the two rows of a register group");
 static_assert(kSlots <= 32, "one lane per row slot, two blocks of 16");
@@ -124,9 +117,8 @@ struct PNet {
     unsigned spin_limit;
     int stationary;   // 1: every layer has its own register groups for the whole launch
     // pause of each (direction, layer) before its first look at the partials, in units of 64 clocks
-    // ([0]: forward, index L the output layer; [1]: backward); the adaptive mode starts from these
+    // ([0]: forward, index L the output layer; [1]: backward)
     unsigned char pace[2][kMaxLayers + 1];
-    int adapt;        // 1: every wavefront tunes its pauses while it runs (see pace_begin)
 };
 
 // Per-layer table of this workgroup (32-bit words in LDS), filled once per launch.
@@ -166,8 +158,8 @@ struct PLds {
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
     static constexpr int plan = dtop + kTopXMax;                  // [kMaxLayers + 1][kPlanInts]
     static constexpr int fail = plan + (kMaxLayers + 1) * kPlanInts;   // [1] set when a wait gave up
-    static constexpr int pace = fail + 16;                        // [kWaves][2][kMaxLayers + 1] pauses before polling
-    static constexpr int total = pace + kWaves * 2 * (kMaxLayers + 1);
+    static constexpr int pace = fail + 16;                        // [2][kMaxLayers + 1] pauses before polling
+    static constexpr int total = pace + 2 * (kMaxLayers + 1) + 14;
 };
 static_assert((PLds::total + kProfLdsFloats) * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
 static_assert(kMaxClasses * kWaves <= kWaves * 264, "partial logits do not fit");
@@ -256,7 +248,7 @@ __device__ inline float pair_sum2(float a0, float a1) {
 // sum, which adds the payloads in index order.
 template <int N>
 __device__ __forceinline__ float poll_sum_n(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
-                                            unsigned limit, bool& ok, float s, unsigned& rereads) {
+                                            unsigned limit, bool& ok, float s) {
     u64 v[N];
     unsigned spins = 0;
     for (;;) {
@@ -271,46 +263,34 @@ __device__ __forceinline__ float poll_sum_n(const u64* base, unsigned col, int P
         if (!__any(pending && DBSN_WAITING(limit))) break;
         if (++spins > limit) { ok = false; break; }
     }
-    rereads += spins;
 #pragma unroll
     for (int k = 0; k < N; ++k) s += (k < P) ? __uint_as_float((unsigned)v[k]) : 0.0f;
     return s;
 }
-// (more than 12 partials take batches of 8 one after the other); rereads counts the batches that
-// had to be read again
+// (more than 12 partials take batches of 8 one after the other)
 __device__ __forceinline__ float poll_sum(const u64* base, unsigned col, int P, unsigned stride, unsigned tag,
-                                          unsigned limit, bool& ok, unsigned& rereads) {
+                                          unsigned limit, bool& ok) {
     float s = 0.0f;
     while (P > 12 && ok) {
-        s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, s, rereads);
+        s = poll_sum_n<8>(base, col, 8, stride, tag, limit, ok, s);
         base += (size_t)(8u * stride);
         P -= 8;
     }
-    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, s, rereads);
-    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, s, rereads);
-    return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, s, rereads);
+    if (P <= 4) return poll_sum_n<4>(base, col, P, stride, tag, limit, ok, s);
+    if (P <= 8) return poll_sum_n<8>(base, col, P, stride, tag, limit, ok, s);
+    return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, s);
 }
 
 // Pacing of the polls.  A batch of loads that comes back without the data costs a full round trip
 // before the next one can be judged, so it pays to look a little later and find the data at the
-// first look.  How much later depends on the layer, the direction and the machine, so every
-// wavefront keeps one pause per (direction, layer) in LDS, in units of 64 clocks, and tunes it as
-// it goes: two units more after a wait that had to read again, one unit less after every eighth
-// step that did not.  Results do not depend on it.
+// first look.  How much later depends on the layer, the direction and the machine: one pause per
+// (direction, layer), in units of 64 clocks, set by the host (defaults, or the search of
+// dbsn_mlp_autotune).  Results do not depend on it.
 constexpr int kPaceMax = 48;
-__device__ __forceinline__ int pace_begin(const float* lds, int dir, int l) {
+__device__ __forceinline__ void pace_begin(const float* lds, int dir, int l) {
     const int* tab = reinterpret_cast<const int*>(lds + PLds::pace);
-    const int d = uniform(tab[((threadIdx.x >> 6) * 2 + dir) * (kMaxLayers + 1) + l]);
+    const int d = uniform(tab[dir * (kMaxLayers + 1) + l]);
     for (int w = 0; w < d; ++w) __builtin_amdgcn_s_sleep(1);
-    return d;
-}
-__device__ __forceinline__ void pace_end(float* lds, int dir, int l, int d, unsigned rereads, unsigned tag, int adapt) {
-    if (!adapt) return;
-    int* tab = reinterpret_cast<int*>(lds + PLds::pace);
-    int nd = d;
-    if (rereads != 0) nd = min(d + 2, kPaceMax);
-    else if ((tag & ((1u << adapt) - 1u)) == 0u && d > 0) nd = d - 1;
-    if (nd != d && (threadIdx.x & 63) == 0) tab[((threadIdx.x >> 6) * 2 + dir) * (kMaxLayers + 1) + l] = nd;
 }
 
 __device__ inline float dot4(const float4& w, const float4& x) {
@@ -343,24 +323,7 @@ __device__ __forceinline__ void for_layer_groups(int g0, int gend, F&& f) {
 // as the work of a small layer.  Networks whose layers fit a register LAYOUT fixed at compile time
 // (layer l owns the groups [g0(l), g0(l) + ngmax(l)), of which it uses its first ng) skip it: the
 // loops below then see constant group numbers, selected by one plain switch on the layer.
-// LAYOUT 0: groups packed in layer order at run time (any network);
-// LAYOUT 1: up to four hidden layers of at most 2, 3, 2, 1 groups (the paper's nets of two to four
-//           hidden layers: 1000-500, 1500-1000-500, 2000-1500-1000-500);
-// LAYOUT 2: up to five hidden layers of at most 3, 5, 3, 2, 1 groups (2500-2000-1500-1000-500);
-// LAYOUT 3: up to nine hidden layers of one group each (the paper's net of nine hidden layers of
-//           1000 units, and other deep nets of narrow layers).
-// The host takes the first layout a network fits.
-constexpr int kLayouts = 4;
-constexpr int kLayoutMaxDepth = 9;
-constexpr int kLayoutDepth[kLayouts] = {0, 5, 5, 9};
-constexpr int kLayoutG0[kLayouts][kLayoutMaxDepth] = {{0, 0, 0, 0, 0, 0, 0, 0, 0},
-                                                      {0, 2, 5, 7, 8, 8, 8, 8, 8},
-                                                      {0, 3, 8, 11, 13, 14, 14, 14, 14},
-                                                      {0, 1, 2, 3, 4, 5, 6, 7, 8}};
-constexpr int kLayoutNG[kLayouts][kLayoutMaxDepth] = {{0, 0, 0, 0, 0, 0, 0, 0, 0},
-                                                      {2, 3, 2, 1, 0, 0, 0, 0, 0},
-                                                      {3, 5, 3, 2, 1, 0, 0, 0, 0},
-                                                      {1, 1, 1, 1, 1, 1, 1, 1, 1}};
+// (the layouts are tabulated in dbsn_plan.h; the host takes the first one a network fits)
 // (All groups of the layer's static range run, used or not: an unused group holds zero weights and
 // meets zero deltas, so it publishes nothing and stays zero, and the code has no branch to merge.)
 template <int G, int GEND, class F>
@@ -536,11 +499,9 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
             const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
             const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
             const unsigned col = min(threadIdx.x, (unsigned)Ceff - 1u);
-            const int pause = pace_begin(lds, 0, l);
+            pace_begin(lds, 0, l);
             DBSN_PROF_SUB(ps, ph, 1);
-            unsigned rereads = 0;
-            const float a = poll_sum(base, col, P, stride, tag, net.spin_limit, ok, rereads);
-            pace_end(lds, 0, l, pause, rereads, tag, net.adapt);
+            const float a = poll_sum(base, col, P, stride, tag, net.spin_limit, ok);
             const float x = ((int)threadIdx.x < Ceff) ? act_fast(a) : 0.0f;
             xk[threadIdx.x] = x;
             // state read-out after the last step (dbsn_mlp_get_activations): row block 0 writes the
@@ -624,11 +585,9 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         bool ok = true;
         float part = 0.0f;
         if (Pw > 0 && 64 * (wave & ((1 << lgNR) - 1)) < Reff) {
-            const int pause = pace_begin(lds, 1, l);
-            unsigned rereads = 0;
+            pace_begin(lds, 1, l);
             part = poll_sum(src + (size_t)((unsigned)pc * (unsigned)Reff), (unsigned)min(j, Reff - 1), Pw,
-                            (unsigned)(NPC * Reff), tag, net.spin_limit, ok, rereads);
-            pace_end(lds, 1, l, pause, rereads, tag, net.adapt);
+                            (unsigned)(NPC * Reff), tag, net.spin_limit, ok);
         }
         if (j < Reff) sg[pc * kMaxTileRows + j] = part;
         DBSN_PROF_SUB(ps, ph, 1);
@@ -761,15 +720,14 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     const int P = uniform(pl[PL_PF]);
     const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
     const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
-    const int pause = pace_begin(lds, 0, L);
-    unsigned rereads = 0;
+    pace_begin(lds, 0, L);
     // One column per thread and at most 16 classes (the paper's nets): the column of W_L stays in
     // registers from the products to the update.  Otherwise the same steps with loops over the
     // thread's columns and the classes.
     const bool small = n <= kThreads && ncq <= 4;
     if (small) {
         const int i = (int)threadIdx.x, ic = min(i, n - 1);
-        const float a = poll_sum(base, (unsigned)ic, P, stride, tag, net.spin_limit, ok, rereads);
+        const float a = poll_sum(base, (unsigned)ic, P, stride, tag, net.spin_limit, ok);
         const float xi = (i < n) ? act_fast(a) : 0.0f;
         tr.xi = xi;
         DBSN_PROF_SUB(ps, ph, 2);
@@ -785,7 +743,7 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
         // thread i gathers x_{L-1}[i] (and i + 512, ...): the partial sums in index order
         for (int i0 = 0; i0 < n; i0 += kThreads) {
             const int i = i0 + (int)threadIdx.x;
-            const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok, rereads);
+            const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok);
             if (i < n) xtop[i] = act_fast(a);
         }
         DBSN_PROF_SUB(ps, ph, 2);
@@ -805,7 +763,6 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
             if (lane < 4) part[(4 * jq + lane) * kWaves + wave] = v;
         }
     }
-    pace_end(lds, 0, L, pause, rereads, tag, net.adapt);
     DBSN_PROF_SUB(ps, ph, 3);
     if (!all_ok(ok, net.err, lds)) return false;
     DBSN_PROF_SUB(ps, ph, 4);
@@ -917,8 +874,8 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
-    for (int e = threadIdx.x; e < kWaves * 2 * (kMaxLayers + 1); e += kThreads)
-        reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[(e / (kMaxLayers + 1)) & 1][e % (kMaxLayers + 1)];
+    for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1); e += kThreads)
+        reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[e / (kMaxLayers + 1)][e % (kMaxLayers + 1)];
     if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
 
     for (int l = 1; l < L; ++l) {

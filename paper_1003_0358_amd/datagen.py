@@ -55,7 +55,3 @@ def stroke_images(n, seed=0, chunk=4096):
         out[a:a + m] = np.clip(np.rint(img), 0, 255).astype(np.uint8).reshape(m, NPIX)
     return out, labels
 
-
-def to_inputs(images_u8):
-    """uint8 intensities -> network inputs intensity/127.5 - 1 as float32 (section "Data")."""
-    return (images_u8.astype(np.float32) / np.float32(127.5) - np.float32(1.0)).astype(np.float32)

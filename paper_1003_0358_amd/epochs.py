@@ -10,7 +10,7 @@
 
 Host logic only: every array operation on the data runs in the library's kernels (the un-deformed
 inputs are produced by the deformation kernel with all amplitudes at zero, which is the exact
-intensity map).
+intensity map; the angle bound per class, the error count and the mean loss are library calls).
 """
 import numpy as np
 
@@ -31,7 +31,7 @@ def eta_schedule(epochs, eta_start=1e-3, eta_end=1e-6):
 def identity_params():
     """Deformation parameters that leave the image alone: the kernel then only maps intensities to
     p / 127.5 - 1."""
-    return binding.DeformParams(0.0, 0.0, 0.0, 0.0, 1, 0)
+    return binding.DeformParams(0.0, 0.0, 0.0, 0.0, 1, 0, 0)
 
 
 def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6, params=None,
@@ -41,8 +41,9 @@ def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6
 
     train_u8: uint8 device tensor [n, 784]; train_labels: int32 device tensor [n];
     params: binding.DeformParams (default: the paper's values); beta_by_label: the bound of the
-    rotation / shear angle follows the label: the look-alike digits 1 and 7 get params.beta_deg, all
-    others twice that (7.5 and 15 degrees with the default), instead of params.beta_deg for all;
+    rotation / shear angle follows the label (dbsn_deform_batch_labels): the look-alike digits 1
+    and 7 get params.beta_deg, all others twice that (7.5 and 15 degrees with the default),
+    instead of params.beta_deg for all;
     val_u8 / val_labels: validation set (default: the un-deformed training set).
     autotune: tune the training kernel's pauses once before the first epoch (dbsn_mlp_autotune on the
     first deformed chunk; steps with eta = 0, so the weights and every result stay as they are).
@@ -56,27 +57,36 @@ def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6
     params = params or binding.default_deform_params()
     if val_u8 is None:
         val_u8, val_labels = train_u8, train_labels
-    beta = binding.beta_for_labels(train_labels, beta_similar=params.beta_deg, beta_other=2.0 * params.beta_deg) \
-        if beta_by_label else None
+    if beta_by_label:
+        # the struct carries the bound of the other classes, the call the one of the look-alikes
+        wide = binding.DeformParams(params.sigma, params.alpha, 2.0 * params.beta_deg, params.gamma_pct, params.ktaps,
+                                    params.shear, params.kernel)
+        similar = params.beta_deg
+
+    def deform(a, m, first_index):
+        if beta_by_label:
+            binding.deform_batch(train_u8[a:a + m], seed, first_index, wide, out=xbuf[:m],
+                                 labels=train_labels[a:a + m], beta_similar_deg=similar)
+        else:
+            binding.deform_batch(train_u8[a:a + m], seed, first_index, params, out=xbuf[:m])
+
     val_x = binding.deform_batch(val_u8, 0, 0, identity_params())
     xbuf = torch.empty((chunk, 784), dtype=torch.float32, device=train_u8.device)
     loss = torch.zeros(n, dtype=torch.float32, device=train_u8.device)
     history, best, best_params = [], None, None
     if autotune and min(chunk, n) >= 64:
         m0 = min(chunk, n)
-        binding.deform_batch(train_u8[:m0], seed, 0, params, out=xbuf[:m0],
-                             beta_deg=None if beta is None else beta[:m0])
+        deform(0, m0, 0)
         mlp.autotune(xbuf[:m0], train_labels[:m0])
     for e, eta in enumerate(eta_schedule(epochs, eta_start, eta_end)):
         for a in range(0, n, chunk):
             m = min(chunk, n - a)
-            binding.deform_batch(train_u8[a:a + m], seed, e * n + a, params, out=xbuf[:m],
-                                 beta_deg=None if beta is None else beta[a:a + m])
+            deform(a, m, e * n + a)
             mlp.bp_steps(xbuf[:m], train_labels[a:a + m], float(eta), loss[a:a + m])
         mlp.status()
         pred = mlp.classify(val_x)
-        errors = int((pred != val_labels).sum().item())
-        rec = {"epoch": e, "eta": float(eta), "train_loss": float(loss.mean().item()), "val_errors": errors,
+        errors = binding.count_errors(pred, val_labels)
+        rec = {"epoch": e, "eta": float(eta), "train_loss": binding.mean_loss(loss), "val_errors": errors,
                "val_n": int(val_labels.numel())}
         history.append(rec)
         if log:

@@ -68,6 +68,14 @@ def test_argument_errors_without_device(dbsn):
     q = binding.DeformParams(float("nan"), 36.0, 7.5, 15.0, 21)
     assert dbsn.deform_batch(q, None, 1, 0, 0, None) == binding.E_ARG
     assert dbsn.last_error() != ""
+    assert dbsn.deform_batch_labels(None, None, None, 0, 7.5, 1, 0, 0, None) == binding.E_ARG
+    assert dbsn.deform_batch_labels(p, None, None, 0, 7.5, 0, 0, 0, None) == binding.OK      # empty
+    assert dbsn.count_errors(None, None, -1, None) == binding.E_ARG
+    assert dbsn.count_errors(None, None, 0, None) == binding.E_ARG          # nowhere to write the count
+    assert dbsn.mean_loss(None, 0, None) == binding.E_ARG
+    assert dbsn.mlp_set_pauses(None, None, None) == binding.E_ARG
+    assert dbsn.mlp_get_pauses(None, None, None) == binding.E_ARG
+    assert dbsn.mlp_set_variant(None, 1, 1) == binding.E_ARG
 
 
 def test_missing_library_fails_loudly(tmp_path):

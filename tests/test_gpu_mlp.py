@@ -8,6 +8,7 @@ logit margin of the float64 oracle > 1e-4).
 import numpy as np
 import pytest
 
+from inputs_util import pixels_to_inputs
 from paper_1003_0358_amd import datagen
 
 pytestmark = pytest.mark.gpu
@@ -28,6 +29,7 @@ SHAPES = [
     [784, 1500, 1000, 500, 10],      # the other nets of the benchmark configurations
     [784, 2000, 1500, 1000, 500, 10],
     [784] + [1000] * 9 + [10],
+    NET4,                            # the net the throughput target is quoted on
 ]
 
 
@@ -39,7 +41,7 @@ def _torch():
 def _data(n, n0=784, seed=0):
     if n0 == 784:
         img, lab = datagen.stroke_images(n, seed=seed)
-        return datagen.to_inputs(img), lab
+        return pixels_to_inputs(img), lab
     rng = np.random.default_rng(seed)
     return rng.uniform(-1, 1, (n, n0)).astype(np.float32), rng.integers(0, 10, n).astype(np.int32)
 
@@ -176,7 +178,7 @@ def test_forward_and_classify(oracle):
     torch = _torch()
     sizes = NET0
     img, _ = datagen.stroke_images(300, seed=11)
-    X = datagen.to_inputs(img)
+    X = pixels_to_inputs(img)
     xs = torch.from_numpy(X).cuda()
     m = _mk(sizes, 1, seed=1)
     # train a little so that the outputs are not all alike
@@ -184,16 +186,9 @@ def test_forward_and_classify(oracle):
     m.bp_steps(torch.from_numpy(Xt).cuda(), torch.from_numpy(yt).cuda(), 1e-2)
     p = m.get_params()
     got = m.classify(xs).cpu().numpy()
-    ref = oracle.classify(sizes, p, X, "f64")
-    margins = []
-    for s in range(300):
-        acts, _ = oracle.forward(sizes, p, X[s], "f64")
-        top2 = np.sort(acts[-10:])[-2:]
-        margins.append(top2[1] - top2[0])
-    clear = np.array(margins) > 1e-4
-    assert clear.sum() >= 290
-    assert np.array_equal(got[clear], ref[clear])
-    assert got.min() >= 0 and got.max() <= 9
+    _check_labels(oracle, sizes, p, X, got, min_clear=290)
+    assert np.array_equal(oracle.classify(sizes, p, X[:20], "f64"),
+                          np.argmax(oracle.logits_batch(sizes, p, X[:20], "f64"), axis=1))
     probs = m.forward(xs[0]).cpu().numpy()
     _, pref = oracle.forward(sizes, p, X[0], "f64")
     assert np.abs(probs - pref).max() < 1e-5
@@ -205,14 +200,23 @@ def test_forward_and_classify(oracle):
     m.close()
 
 
-def _margins(oracle, sizes, p, X):
-    nc = sizes[-1]
-    out = []
-    for s in range(len(X)):
-        acts, _ = oracle.forward(sizes, p, X[s], "f64")
-        top2 = np.sort(acts[-nc:])[-2:]
-        out.append(top2[1] - top2[0])
-    return np.array(out)
+def _check_labels(oracle, sizes, p, X, got, min_clear):
+    """Complete validity check of a set of labels: the float64 oracle gives every sample's output
+    pre-activations; wherever the library's label differs from the oracle's argmax (lowest index on
+    ties) the two largest outputs must lie within 1e-4 of each other, i.e. the decision is within
+    float32 rounding.  No allowance by count.  Returns the number of differing labels."""
+    oracle.set_threads(min(oracle.max_threads(), 16))
+    logits = oracle.logits_batch(sizes, p, X, "f64")
+    oracle.set_threads(1)
+    ref = np.argmax(logits, axis=1)                      # first maximum = lowest index
+    assert got.shape == ref.shape
+    top2 = np.sort(logits, axis=1)[:, -2:]
+    margin = top2[:, 1] - top2[:, 0]
+    differ = got != ref
+    assert (margin[differ] < 1e-4).all(), (np.flatnonzero(differ)[:10], margin[differ][:10])
+    assert (margin > 1e-4).sum() >= min_clear, (margin > 1e-4).sum()
+    assert got.min() >= 0 and got.max() < sizes[-1]
+    return int(differ.sum())
 
 
 @pytest.mark.parametrize("sizes", [[37, 70, 33, 7], [20, 136, 260, 36, 7]], ids=["odd-widths", "multiples-of-four"])
@@ -236,11 +240,8 @@ def test_classify_batches_ragged_shapes(oracle, sizes):
     p = m.get_params()
     xs = torch.from_numpy(X).cuda()
     got = m.classify(xs).cpu().numpy()
-    ref = oracle.classify(sizes, p, X, "f64")
-    clear = _margins(oracle, sizes, p, X[:400]) > 1e-4
-    assert clear.sum() >= 380
-    assert np.array_equal(got[:400][clear], ref[:400][clear])
-    assert (got != ref).sum() <= 4            # the rest: only decisions within rounding may differ
+    # every one of the 16,492 labels: equal to the oracle's, or a decision within rounding
+    _check_labels(oracle, sizes, p, X, got, min_clear=int(0.97 * n))
     assert len(np.unique(got)) >= 5
     for s in (0, 127, 128, 16383, 16384, n - 1):   # tile and pass boundaries
         probs = m.forward(xs[s]).cpu().numpy()
@@ -252,45 +253,33 @@ def test_classify_batches_ragged_shapes(oracle, sizes):
 def test_classify_full_size_net(oracle):
     torch = _torch()
     img, _ = datagen.stroke_images(200, seed=21)
-    X = datagen.to_inputs(img)
+    X = pixels_to_inputs(img)
     m = _mk(NET4, 1, seed=4)
     Xt, yt = _data(30, seed=22)
     m.bp_steps(torch.from_numpy(Xt).cuda(), torch.from_numpy(yt).cuda(), 1e-2)
     p = m.get_params()
     got = m.classify(torch.from_numpy(X).cuda()).cpu().numpy()
-    oracle.set_threads(8)
-    ref = oracle.classify(NET4, p, X, "f64")
-    clear = _margins(oracle, NET4, p, X) > 1e-4
-    oracle.set_threads(1)
-    assert clear.sum() >= 190
-    assert np.array_equal(got[clear], ref[clear])
+    _check_labels(oracle, NET4, p, X, got, min_clear=190)
     m.close()
 
 
 def test_classify_full_size_net_in_bench_configuration(oracle):
     """The 12 M-weight net over the bench's 10,000 images (79 rows of tiles, up to seven tiles per
-    persistent workgroup, a last row of tiles with 16 samples): the oracle classifies a sample of
-    them one by one, spread over the tile rows and the ends; the whole set must also classify the
-    same way when it is cut into pieces that move every sample to another place in its tile."""
+    persistent workgroup, a last row of tiles with 16 samples): the float64 oracle propagates every
+    one of the 10,000 (its samples dealt to the host threads), and each label must equal its argmax
+    or be a decision within rounding; the whole set must also classify the same way when it is cut
+    into pieces that move every sample to another place in its tile."""
     torch = _torch()
     n = 10000
     img, _ = datagen.stroke_images(n, seed=1)
-    X = datagen.to_inputs(img)
+    X = pixels_to_inputs(img)
     m = _mk(NET4, 1, seed=4)
     Xt, yt = _data(30, seed=22)
     m.bp_steps(torch.from_numpy(Xt).cuda(), torch.from_numpy(yt).cuda(), 1e-2)
     p = m.get_params()
     xs = torch.from_numpy(X).cuda()
     got = m.classify(xs).cpu().numpy()
-    rng = np.random.default_rng(9)
-    pick = np.unique(np.concatenate([[0, 1, 127, 128, 4095, 4096, 8191, 8192, 9983, 9984, 9998, 9999],
-                                     rng.integers(0, n, 52)]))
-    oracle.set_threads(8)
-    ref = oracle.classify(NET4, p, X[pick], "f64")
-    clear = _margins(oracle, NET4, p, X[pick]) > 1e-4
-    oracle.set_threads(1)
-    assert clear.sum() >= len(pick) - 6
-    assert np.array_equal(got[pick][clear], ref[clear])
+    _check_labels(oracle, NET4, p, X, got, min_clear=int(0.97 * n))
     # the same samples at other tile positions: a shifted cut of the set
     pieces = [(0, 37), (37, 5037), (5037, 5100), (5100, n)]
     again = np.concatenate([m.classify(xs[a:b]).cpu().numpy() for a, b in pieces])
@@ -383,9 +372,12 @@ def test_wait_timeout_is_reported_not_hung():
 
 def test_random_shapes_three_steps(oracle):
     """Seeded random architectures (1 to 6 hidden layers, widths 1 to 2600, 1 to 64 classes, inputs 1
-    to 1200): three steps in one persistent launch against the float64 oracle.  Exercises ragged
-    tiles, layers narrower than a wavefront, single-row tiles, both output-layer paths, both register
-    layouts and both parities of the hand-over buffers."""
+    to 1200), three steps against the float64 oracle.  Exercises ragged tiles, layers narrower than
+    a wavefront, single-row tiles, both output-layer paths, both register layouts and both parities
+    of the hand-over buffers.  Every step is held to the one-step bar by itself: the oracle takes
+    each step from the weights the library had before it (three launches of one step; the step
+    count and with it the parity of the buffers runs on from launch to launch), and the same three
+    steps in ONE launch must then give the same floats bit for bit."""
     torch = _torch()
     rng = np.random.default_rng(1234)
     for case in range(24):
@@ -394,17 +386,26 @@ def test_random_shapes_three_steps(oracle):
         sizes = [int(rng.choice([1, 5, 64, 300, 784, 1200]))] + widths + [int(rng.choice([1, 2, 10, 17, 64]))]
         X = rng.uniform(-1, 1, (3, sizes[0])).astype(np.float32)
         y = rng.integers(0, sizes[-1], 3).astype(np.int32)
+        xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
         m = _mk(sizes, 1, seed=case)
         # somewhat larger weights than the initialisation so that narrow layers carry signal too
         p0 = (m.get_params() * 2).astype(np.float32)
         m.set_params(p0)
-        m.bp_steps(torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), 1e-3)
-        m.status()
-        got = m.get_params()
-        ref = oracle.bp_steps(sizes, p0, X, y, 1e-3, "f64")[0]
-        assert _close(got, ref, rtol=2e-5), (sizes, float(np.abs(got - ref).max()))
+        before = p0
+        for s in range(3):
+            m.bp_step(xs[s], int(y[s]), 1e-3)
+            m.status()
+            got = m.get_params()
+            ref = oracle.bp_step(sizes, before, X[s], int(y[s]), 1e-3, "f64")[0]
+            assert _close(got, ref), (sizes, s, float(np.abs(got - ref).max()))
+            before = got
         if sizes[-1] > 1:     # (a single class has probability 1 and nothing to learn)
             assert np.abs(got - p0).max() > 0
         else:
             assert np.array_equal(got, p0)
-        m.close()
+        one = _mk(sizes, 1, seed=case)
+        one.set_params(p0)
+        one.bp_steps(xs, ys, 1e-3)
+        one.status()
+        assert np.array_equal(one.get_params(), got), sizes
+        m.close(); one.close()

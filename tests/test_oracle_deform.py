@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 import scipy.ndimage as ndi
 
+from inputs_util import pixels_to_inputs
 from paper_1003_0358_amd import datagen
 
 
@@ -77,17 +78,26 @@ def test_smoothing_constant_interior(oracle):
 # ---- resampling -------------------------------------------------------------
 @pytest.mark.parametrize("mode", ["f64", "f32"])
 def test_zero_displacement_is_identity(oracle, mode):
-    img = _img()[0]
+    """With no displacement, no rotation and unit scale every output pixel is its own source pixel
+    (coordinates are exact integers, both interpolation weights exactly 0 or 1), mapped to
+    intensity / 127.5 - 1 (section "Data").  The expected values are the exact rationals
+    (2 p - 255) / 255: the result may differ from their correctly rounded value by the two roundings
+    of a division and a subtraction, and the ends of the range are exact."""
+    from fractions import Fraction
+    ulp = 2.0 ** -52 if mode == "f64" else 2.0 ** -23
+    ramp = np.arange(784, dtype=np.int64).reshape(28, 28) % 256          # every intensity 0..255
+    img = ramp.astype(np.uint8)
     z = np.zeros((28, 28))
     out = oracle.resample(img, 1.0, 0.0, 1.0, 1.0, z, z, mode)
-    want = img.astype(np.float64) / 127.5 - 1.0 if mode == "f64" else datagen.to_inputs(img)
-    assert np.array_equal(out, want)                       # exact
-    # whole pipeline with alpha = beta = gamma = 0
-    full = oracle.deform_batch(_img().reshape(4, 784), seed=5, first_index=0, alpha=0.0, beta_deg=0.0,
-                               gamma_pct=0.0, mode=mode)
+    exact = np.array([[float(Fraction(2 * int(p) - 255, 255)) for p in row] for row in ramp])
+    assert np.abs(out.astype(np.float64) - exact).max() <= 1.0 * ulp
+    assert out[0, 0] == -1.0 and out.reshape(-1)[255] == 1.0             # intensities 0 and 255
+    assert np.all(np.diff(out.reshape(-1)[:256]) > 0)                    # strictly increasing in the intensity
+    # whole pipeline with alpha = beta = gamma = 0 on stroke images: pixel for pixel the same map
     allw = _img().reshape(4, 784)
-    want = allw.astype(np.float64) / 127.5 - 1.0 if mode == "f64" else datagen.to_inputs(allw)
-    assert np.array_equal(full, want)
+    full = oracle.deform_batch(allw, seed=5, first_index=0, alpha=0.0, beta_deg=0.0, gamma_pct=0.0, mode=mode)
+    lut = out.reshape(-1)[:256]
+    assert np.array_equal(full, lut[allw])
 
 
 def test_bilinear_exact_on_affine_linear_image(oracle):
@@ -211,7 +221,7 @@ def test_chunking_and_seed(oracle):
     assert np.abs(a - c).max() > 0.1
     assert a.min() >= -1.0 and a.max() <= 1.0
     # deformation moves things but keeps most of the ink
-    ink0 = (datagen.to_inputs(imgs) + 1).sum(axis=1)
+    ink0 = (pixels_to_inputs(imgs) + 1).sum(axis=1)
     ink1 = (a + 1).sum(axis=1)
     assert np.all(ink1 > 0.5 * ink0) and np.all(ink1 < 1.6 * ink0)
 

@@ -204,11 +204,12 @@ def test_online_semantics(oracle):
 
 
 def test_f32_mode_tracks_f64(oracle):
+    from inputs_util import pixels_to_inputs
     from paper_1003_0358_amd import datagen
     sizes = [784, 100, 50, 10]
     params = oracle.init_params(sizes, seed=0)
     img, lab = datagen.stroke_images(100, seed=0)
-    X = datagen.to_inputs(img)
+    X = pixels_to_inputs(img)
     p64, l64 = oracle.bp_steps(sizes, params, X, lab, 1e-3, "f64")
     p32, l32 = oracle.bp_steps(sizes, params, X, lab, np.float32(1e-3), "f32")
     assert p32.dtype == np.float32
@@ -247,3 +248,27 @@ def test_threads_do_not_change_results(oracle):
     b, lb = oracle.bp_steps(sizes, params, X, y, np.float32(0.01), "f32")
     oracle.set_threads(1)
     assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+def test_logits_batch_matches_torch(oracle):
+    """The batch of output pre-activations the classify parity tests take their margins from:
+    against a float64 torch forward pass of the same net, with one and several threads."""
+    rng = np.random.default_rng(11)
+    sizes = [12, 9, 7, 5]
+    params = _rand_net(sizes, rng)
+    X = rng.uniform(-1, 1, (37, 12))
+    Ws, bs = unpack_params(sizes, params)
+    x = torch.tensor(X, dtype=torch.float64)
+    for l, (W, b) in enumerate(zip(Ws, bs)):
+        a = x @ torch.tensor(W).T + torch.tensor(b)
+        x = A * torch.tanh(B * a) if l < len(Ws) - 1 else a
+    want = x.numpy()
+    one = oracle.logits_batch(sizes, params, X)
+    assert one.shape == (37, 5)
+    assert np.allclose(one, want, rtol=0, atol=1e-13)
+    oracle.set_threads(4)
+    four = oracle.logits_batch(sizes, params, X)
+    oracle.set_threads(1)
+    assert np.array_equal(one, four)
+    assert list(oracle.classify(sizes, params, X)) == list(np.argmax(want, axis=1))
+    assert oracle.logits_batch(sizes, params, X[:0]).shape == (0, 5)
