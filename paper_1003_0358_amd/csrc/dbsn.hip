@@ -520,18 +520,15 @@ int32_t dbsn_forward(dbsn_mlp* m, const float* sample_dev, float* probs_dev) {
     return DBSN_OK;
 }
 
-int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t* labels_out_dev) {
-    if (check_mlp(m)) return DBSN_E_ARG;
-    if (n < 0) return fail(DBSN_E_ARG, "n is negative");
-    if (n == 0) return DBSN_OK;
-    if (!samples_dev || !labels_out_dev) return fail(DBSN_E_ARG, "null pointer");
-    if (!aligned(samples_dev, 4) || !aligned(labels_out_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
-    // the samples go through the layers in passes of kBatchSamples (what the activation buffers
-    // hold), one launch per layer
+}  // extern "C"
+
+namespace {
+
+// The batched forward pass over n samples, `per` at a time: one launch per layer, the activations
+// of a pass alternating between the two buffers act[0] and act[1] ([per][ldact] floats each).
+int32_t classify_passes(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t* labels_out_dev, float* const act[2],
+                        int64_t per) {
     const int L = m->net.L, n0 = m->sizes[0], ldact = m->plan.ldact;
-    float* act[2] = {reinterpret_cast<float*>(m->arena + m->plan.act[0]),
-                     reinterpret_cast<float*>(m->arena + m->plan.act[1])};
-    const int64_t per = kBatchSamples;
     for (int64_t at = 0; at < n; at += per) {
         const int S = (int)std::min<int64_t>(per, n - at);
         const float* X = samples_dev + at * n0;
@@ -581,6 +578,27 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     }
     HIP_TRY(hipGetLastError());
     return DBSN_OK;
+}
+
+int32_t check_classify_args(dbsn_mlp* m, const float* samples_dev, int64_t n, const int32_t* labels_out_dev) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    if (n < 0) return fail(DBSN_E_ARG, "n is negative");
+    if (n > 0 && (!samples_dev || !labels_out_dev)) return fail(DBSN_E_ARG, "null pointer");
+    if (!aligned(samples_dev, 4) || !aligned(labels_out_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    return DBSN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t* labels_out_dev) {
+    if (int32_t rc = check_classify_args(m, samples_dev, n, labels_out_dev)) return rc;
+    if (n == 0) return DBSN_OK;
+    // the samples go through the layers in passes of kBatchSamples (what the arena's buffers hold)
+    float* const act[2] = {reinterpret_cast<float*>(m->arena + m->plan.act[0]),
+                           reinterpret_cast<float*>(m->arena + m->plan.act[1])};
+    return classify_passes(m, samples_dev, n, labels_out_dev, act, kBatchSamples);
 }
 
 }  // extern "C"
