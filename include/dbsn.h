@@ -39,6 +39,7 @@ extern "C" {
 #define DBSN_MAX_WIDTH   4096   /* neurons in any layer, inputs included                              */
 #define DBSN_MAX_CLASSES 64     /* neurons in the output layer                                        */
 #define DBSN_MAX_KTAPS   63     /* taps of the 1-D Gaussian                                           */
+#define DBSN_STATIC_SCRATCH_BYTES (64u << 20)   /* device memory dbsn_classify_static stages through  */
 #define DBSN_IMG_SIDE    28
 #define DBSN_IMG_PIXELS  784
 
@@ -200,6 +201,20 @@ int32_t dbsn_forward(dbsn_mlp* mlp, const float* sample_dev, float* probs_dev);
  * samples_dev is 16-byte aligned (other shapes take a slower kernel, same results).  Asynchronous
  * on the network's stream; n == 0 is a no-op. */
 int32_t dbsn_classify(dbsn_mlp* mlp, const float* samples_dev, int64_t n, int32_t* labels_out_dev);
+
+/* dbsn_classify for callers that cannot allocate device memory or must not see a memset: code
+ * that records the stream into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.
+ * Same kernels and same labels as dbsn_classify, but the activations of the pass are staged in a
+ * static device array of DBSN_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held
+ * until the process ends) instead of the arena's buffers, all n samples in ONE pass: the call makes
+ * no hipMalloc / hipFree / memset and no allocating library call.  Limit: 2 * n * 4 * w bytes must
+ * fit the array, w = the widest layer after the input rounded up to a multiple of 4 (3355 samples
+ * for a 2500-wide net, 8388 for a 1000-wide one); a larger n is rejected with DBSN_E_SHAPE and a
+ * message that names the largest n allowed, and no work is issued.  Every call on a GPU shares that
+ * GPU's array (each call clears what it uses with a kernel first): calls that overlap on one GPU,
+ * from different streams or host threads, race; calls on one stream are ordered and safe.
+ * Asynchronous on the network's stream. */
+int32_t dbsn_classify_static(dbsn_mlp* mlp, const float* samples_dev, int64_t n, int32_t* labels_out_dev);
 
 /* Error count of a validation or test pass (section "Results"): *count_dev (int64, device, 8-byte
  * aligned) = number of s < n with predicted_dev[s] != labels_dev[s] (both [n] int32, device).

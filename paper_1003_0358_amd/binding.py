@@ -20,7 +20,7 @@ SYMBOLS = [
     "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
     "dbsn_mlp_set_pauses", "dbsn_mlp_get_pauses", "dbsn_mlp_set_variant",
     "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_deform_batch_labels",
-    "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_count_errors", "dbsn_mean_loss",
+    "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_classify_static", "dbsn_count_errors", "dbsn_mean_loss",
     "dbsn_last_error",
 ]
 DEFORM_KERNEL_AUTO, DEFORM_KERNEL_GENERAL = 0, 1
@@ -81,6 +81,7 @@ class Lib:
         c.dbsn_bp_step.argtypes = [vp, vp, i32, f32]
         c.dbsn_forward.argtypes = [vp, vp, vp]
         c.dbsn_classify.argtypes = [vp, vp, i64, vp]
+        c.dbsn_classify_static.argtypes = [vp, vp, i64, vp]
         c.dbsn_last_error.restype = C.c_char_p
         for name in SYMBOLS:
             if name not in ("dbsn_mlp_arena_bytes", "dbsn_last_error"):
@@ -173,6 +174,9 @@ class Lib:
 
     def classify(self, h, samples, n, labels_out):
         return self.c.dbsn_classify(h, _ptr(samples), n, _ptr(labels_out))
+
+    def classify_static(self, h, samples, n, labels_out):
+        return self.c.dbsn_classify_static(h, _ptr(samples), n, _ptr(labels_out))
 
 
 _lib = None

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -22,7 +23,17 @@
 
 using namespace dbsn;
 
+// Staging memory of dbsn_classify_static: the two activation buffers of one batched forward pass,
+// for callers that cannot allocate.  Every device the library runs on holds its own copy of the
+// array until the process ends; in host code the name below is only a handle for
+// hipGetSymbolAddress, the address kernels are given is the one that call returns (g_scratch_ptr).
+static __device__ __align__(256) float scratch[DBSN_STATIC_SCRATCH_BYTES / sizeof(float)];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[kMaxDevices] = {};   // per device: where `scratch` lives there (null: not asked yet)
 
 thread_local std::string g_err;
 
@@ -43,6 +54,19 @@ int32_t fail(int32_t code, const char* fmt, ...) {
     } while (0)
 
 constexpr size_t kAlign = kArenaAlign;
+
+// Looks up this device's copy of the static scratch array, once per device; `device` must be the
+// current device.
+int32_t static_scratch_setup(int device) {
+    if (device < 0 || device >= kMaxDevices) return fail(DBSN_E_HIP, "device ordinal %d not supported", device);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[device]) return DBSN_OK;
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(DBSN_E_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[device] = static_cast<float*>(p);
+    return DBSN_OK;
+}
 
 }  // namespace
 
@@ -228,6 +252,10 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     if (e != hipSuccess) {
         delete m;
         return fail(DBSN_E_HIP, "no usable HIP device: %s", hipGetErrorString(e));
+    }
+    if (int32_t rc = static_scratch_setup(m->device)) {
+        delete m;
+        return rc;
     }
     m->lds_limit = prop.sharedMemPerBlock;
     m->cus = prop.multiProcessorCount;
@@ -599,6 +627,33 @@ int32_t dbsn_classify(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t*
     float* const act[2] = {reinterpret_cast<float*>(m->arena + m->plan.act[0]),
                            reinterpret_cast<float*>(m->arena + m->plan.act[1])};
     return classify_passes(m, samples_dev, n, labels_out_dev, act, kBatchSamples);
+}
+
+int32_t dbsn_classify_static(dbsn_mlp* m, const float* samples_dev, int64_t n, int32_t* labels_out_dev) {
+    if (int32_t rc = check_classify_args(m, samples_dev, n, labels_out_dev)) return rc;
+    if (n == 0) return DBSN_OK;
+    // one pass: both activation buffers of all n samples must fit the static array
+    const size_t row = sizeof(float) * (size_t)m->plan.ldact;
+    const size_t half = DBSN_STATIC_SCRATCH_BYTES / 2;
+    if ((uint64_t)n > half / row)
+        return fail(DBSN_E_SHAPE, "n = %lld is beyond the static scratch: at most %zu samples per call for a widest "
+                                  "layer of %d neurons (2 x n x %zu bytes <= %zu)",
+                    (long long)n, half / row, m->plan.ldact, row, (size_t)DBSN_STATIC_SCRATCH_BYTES);
+    float* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        base = g_scratch_ptr[m->device];
+    }
+    if (!base) return fail(DBSN_E_HIP, "static scratch of device %d was not set up", m->device);
+    float* const act[2] = {base, base + half / sizeof(float)};
+    // The array keeps what the last call left (possibly of another network).  The kernels read a few
+    // columns past a layer's outputs against zero weights, so what they find there must be finite:
+    // both regions start at zero, by a kernel (no memset, which callers recording a graph avoid).
+    const long long n4 = (long long)((size_t)n * row / sizeof(float4));
+    const int blocks = (int)std::min<long long>((n4 + 255) / 256, 2048);
+    hipLaunchKernelGGL(k_zero, dim3(blocks), dim3(256), 0, m->stream, reinterpret_cast<float4*>(act[0]), n4);
+    hipLaunchKernelGGL(k_zero, dim3(blocks), dim3(256), 0, m->stream, reinterpret_cast<float4*>(act[1]), n4);
+    return classify_passes(m, samples_dev, n, labels_out_dev, act, n);
 }
 
 }  // extern "C"
