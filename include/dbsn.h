@@ -126,7 +126,8 @@ int32_t dbsn_mlp_get_pauses(dbsn_mlp* mlp, int32_t* fwd_host, int32_t* bwd_host)
  * layers stay in registers for the whole call when they all fit (58 MB; else as 0); 0: every phase
  * loads its tile from memory and the backward phase stores it back.  fixed_layout = 1: networks
  * that fit one of the compiled register layouts use it; 0: register groups packed at run time.
- * All variants give the same floats.  Synchronises the stream. */
+ * The variants add in the same order and agree to rounding (they are separately compiled kernels).
+ * Synchronises the stream. */
 int32_t dbsn_mlp_set_variant(dbsn_mlp* mlp, int32_t stationary, int32_t fixed_layout);
 
 /* Optional tuning of the persistent kernel for this network on this device.  Between the phases
@@ -225,6 +226,16 @@ int32_t dbsn_count_errors(const int32_t* predicted_dev, const int32_t* labels_de
 /* Mean of the per-step losses of an epoch: *mean_dev (float, device) = the sum of loss_dev[0 .. n)
  * taken in binary64 in a fixed order, divided by n, rounded to binary32.  n >= 1. */
 int32_t dbsn_mean_loss(const float* loss_dev, int64_t n, float* mean_dev, void* hip_stream);
+
+/* Measurement aid, not part of the method: the memory traffic of a streamed training step without
+ * its arithmetic.  `sweeps` times over buf_dev[0 .. n_floats): one kernel that reads every float,
+ * one that reads it and writes it back (adding 0.0f), i.e. 12 bytes per float and sweep, the mix
+ * of forward read, backward read and update write.  Timed by the caller (events on hip_stream), it
+ * gives the bandwidth this mix can reach over a footprint of 4 * n_floats bytes.  buf_dev: device,
+ * 16-byte aligned, n_floats a multiple of 4; sink_dev: [4 * workgroups] floats of device memory the
+ * read kernel leaves its sums in; workgroups of 256 threads each, 1 .. 65536. */
+int32_t dbsn_probe_stream(float* buf_dev, int64_t n_floats, int32_t workgroups, int32_t sweeps,
+                          float* sink_dev, void* hip_stream);
 
 /* Message for the last error on this host thread ("" if none). */
 const char* dbsn_last_error(void);

@@ -9,7 +9,7 @@ LIB = os.path.join(_HERE, "libdbsn.so")
 SOURCES = [os.path.join(CSRC, "dbsn.hip")]
 HEADERS = [os.path.join(CSRC, h) for h in ("dbsn_plan.h", "dbsn_rng.h", "dbsn_mlp_kernels.h", "dbsn_deform_kernels.h",
                                            "dbsn_persistent_kernel.h", "dbsn_batch_kernels.h",
-                                           "dbsn_reduce_kernels.h")] + \
+                                           "dbsn_reduce_kernels.h", "dbsn_probe_kernels.h")] + \
           [os.path.join(ROOT, "include", "dbsn.h")]
 
 

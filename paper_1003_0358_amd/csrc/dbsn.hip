@@ -20,6 +20,7 @@
 #include "dbsn_batch_kernels.h"
 #include "dbsn_persistent_kernel.h"
 #include "dbsn_reduce_kernels.h"
+#include "dbsn_probe_kernels.h"
 
 using namespace dbsn;
 
@@ -745,6 +746,24 @@ int32_t dbsn_count_errors(const int32_t* predicted_dev, const int32_t* labels_de
         return fail(DBSN_E_SHAPE, "misaligned pointer");
     hipLaunchKernelGGL(k_count_errors, dim3(1), dim3(kReduceThreads), 0, static_cast<hipStream_t>(hip_stream),
                        predicted_dev, labels_dev, (long long)n, reinterpret_cast<long long*>(count_dev));
+    HIP_TRY(hipGetLastError());
+    return DBSN_OK;
+}
+
+int32_t dbsn_probe_stream(float* buf_dev, int64_t n_floats, int32_t workgroups, int32_t sweeps, float* sink_dev,
+                          void* hip_stream) {
+    if (!buf_dev || !sink_dev) return fail(DBSN_E_ARG, "null pointer");
+    if (n_floats < 4 || n_floats % 4 != 0) return fail(DBSN_E_ARG, "n_floats must be a positive multiple of 4");
+    if (workgroups < 1 || workgroups > 65536) return fail(DBSN_E_ARG, "workgroups must be in 1..65536");
+    if (sweeps < 0) return fail(DBSN_E_ARG, "sweeps is negative");
+    if (!aligned(buf_dev, 16) || !aligned(sink_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (int r = 0; r < sweeps; ++r) {
+        hipLaunchKernelGGL(k_probe_read, dim3(workgroups), dim3(kProbeThreads), 0, st,
+                           reinterpret_cast<const float4*>(buf_dev), (long long)(n_floats / 4), sink_dev);
+        hipLaunchKernelGGL(k_probe_update, dim3(workgroups), dim3(kProbeThreads), 0, st,
+                           reinterpret_cast<float4*>(buf_dev), (long long)(n_floats / 4), 0.0f);
+    }
     HIP_TRY(hipGetLastError());
     return DBSN_OK;
 }

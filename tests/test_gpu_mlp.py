@@ -30,6 +30,7 @@ SHAPES = [
     [784, 2000, 1500, 1000, 500, 10],
     [784] + [1000] * 9 + [10],
     NET4,                            # the net the throughput target is quoted on
+    [784, 3584, 3584, 3584, 1000, 10],   # 128 MB of hidden weights: the streamed net bench.py times
 ]
 
 
@@ -409,3 +410,37 @@ def test_random_shapes_three_steps(oracle):
         one.status()
         assert np.array_equal(one.get_params(), got), sizes
         m.close(); one.close()
+
+
+@pytest.mark.parametrize("sizes", [NET0, [784, 1500, 1000, 500, 10], [784] + [300] * 9 + [10]])
+def test_kernel_variants_agree_bit_for_bit(sizes):
+    """The persistent kernel with its weights held in registers in a compile-time layout (the
+    default for these nets), with register groups packed at run time, and with the weights streamed
+    from memory in every phase: the same sums in the same order, in three separately compiled
+    kernels (the compiler may fuse a multiply and an add in one and not in another), so they agree
+    to rounding; the pauses before polling change nothing at all."""
+    torch = _torch()
+    X, y = _data(40, seed=9)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    out = []
+    for stationary, fixed, pauses in ((True, True, None), (True, False, None), (False, True, None), (True, True, 3)):
+        m = _mk(sizes, 1, seed=2)
+        m.set_variant(stationary=stationary, fixed_layout=fixed)
+        if pauses is not None:
+            L = len(sizes) - 1
+            m.set_pauses([pauses] * L, [2 * pauses] * L)
+            f, b = m.get_pauses()
+            assert list(f) == [pauses] * L and list(b) == [2 * pauses] * L
+        loss = torch.zeros(40, dtype=torch.float32, device="cuda")
+        m.bp_steps(xs[:7], ys[:7], 1e-3, loss[:7])
+        m.bp_steps(xs[7:], ys[7:], 1e-3, loss[7:])
+        m.status()
+        out.append((m.get_params(), loss.cpu().numpy()))
+        assert m.lib.mlp_set_pauses(m.h, np.array([49] * (len(sizes) - 1), np.int32), None) != 0   # out of range
+        m.close()
+    diffs = [float(np.abs(p - out[0][0]).max()) for p, _ in out]
+    print("variants, max weight difference from the default:", diffs)
+    assert np.array_equal(out[3][0], out[0][0]) and np.array_equal(out[3][1], out[0][1])    # same kernel, other pauses
+    for (p, l), d in zip(out[1:3], diffs[1:3]):
+        assert d <= 1e-7, diffs
+        assert np.abs(l - out[0][1]).max() <= 1e-5
