@@ -122,13 +122,21 @@ int32_t dbsn_mlp_set_pauses(dbsn_mlp* mlp, const int32_t* fwd_host, const int32_
 int32_t dbsn_mlp_get_pauses(dbsn_mlp* mlp, int32_t* fwd_host, int32_t* bwd_host);
 
 /* Variant of the persistent kernel, for measurements and tests (the default, chosen at
- * dbsn_mlp_init, is the fastest the network allows).  stationary = 1: the weights of the hidden
- * layers stay in registers for the whole call when they all fit (58 MB; else as 0); 0: every phase
- * loads its tile from memory and the backward phase stores it back.  fixed_layout = 1: networks
- * that fit one of the compiled register layouts use it; 0: register groups packed at run time.
- * The variants add in the same order and agree to rounding (they are separately compiled kernels).
- * Synchronises the stream. */
-int32_t dbsn_mlp_set_variant(dbsn_mlp* mlp, int32_t stationary, int32_t fixed_layout);
+ * dbsn_mlp_init, is the fastest the network and the device allow).  stationary = 1: the weights of
+ * the hidden layers stay in registers for the whole call when they all fit (58 MB; else as 0); 0:
+ * every phase loads its tile from memory and the backward phase stores it back.  fixed_layout = 1:
+ * networks that fit one of the compiled register layouts use it; 0: registers packed at run time.
+ * banded = 1: where two hidden layers follow each other, the neurons between them are split into
+ * eight bands, one per die of the chip, so that the partial sums those two layers exchange never
+ * leave a die (used when the device places workgroup g on die g % 8, which dbsn_mlp_init probes,
+ * and the banded tiles fit the registers); 0: every layer cut the same way, all hand-overs across
+ * the chip.  stationary and fixed_layout do not change the order of any sum: those variants agree
+ * to rounding (they are separately compiled kernels); banded changes how partial sums are grouped,
+ * like DBSN_MODE_LAUNCHES does.  Synchronises the stream.
+ * dbsn_mlp_get_variant reports what is in force: stationary (0/1), the register layout (0: packed
+ * at run time) and the number of banded pairs of layers (0: the plain cut); pointers may be NULL. */
+int32_t dbsn_mlp_set_variant(dbsn_mlp* mlp, int32_t stationary, int32_t fixed_layout, int32_t banded);
+int32_t dbsn_mlp_get_variant(dbsn_mlp* mlp, int32_t* stationary, int32_t* layout, int32_t* banded_pairs);
 
 /* Optional tuning of the persistent kernel for this network on this device.  Between the phases
  * of a step a workgroup pauses before it first looks for the partial sums of the phase before (a

@@ -18,7 +18,7 @@ MODE_LAUNCHES, MODE_PERSISTENT = 0, 1
 SYMBOLS = [
     "dbsn_mlp_arena_bytes", "dbsn_mlp_init", "dbsn_mlp_free", "dbsn_mlp_set_weights", "dbsn_mlp_get_weights",
     "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
-    "dbsn_mlp_set_pauses", "dbsn_mlp_get_pauses", "dbsn_mlp_set_variant",
+    "dbsn_mlp_set_pauses", "dbsn_mlp_get_pauses", "dbsn_mlp_set_variant", "dbsn_mlp_get_variant",
     "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_deform_batch_labels",
     "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_classify_static", "dbsn_count_errors", "dbsn_mean_loss", "dbsn_probe_stream",
     "dbsn_last_error",
@@ -69,7 +69,8 @@ class Lib:
         c.dbsn_mlp_set_spin_limit.argtypes = [vp, C.c_uint32]
         c.dbsn_mlp_set_pauses.argtypes = [vp, vp, vp]
         c.dbsn_mlp_get_pauses.argtypes = [vp, vp, vp]
-        c.dbsn_mlp_set_variant.argtypes = [vp, i32, i32]
+        c.dbsn_mlp_set_variant.argtypes = [vp, i32, i32, i32]
+        c.dbsn_mlp_get_variant.argtypes = [vp, vp, vp, vp]
         c.dbsn_mlp_status.argtypes = [vp]
         c.dbsn_mlp_autotune.argtypes = [vp, vp, vp, i64]
         c.dbsn_deform_batch.argtypes = [C.POINTER(DeformParams), vp, i64, u64, u64, vp, vp]
@@ -138,8 +139,11 @@ class Lib:
     def mlp_get_pauses(self, h, fwd_host, bwd_host):
         return self.c.dbsn_mlp_get_pauses(h, _ptr(fwd_host), _ptr(bwd_host))
 
-    def mlp_set_variant(self, h, stationary, fixed_layout):
-        return self.c.dbsn_mlp_set_variant(h, stationary, fixed_layout)
+    def mlp_set_variant(self, h, stationary, fixed_layout, banded):
+        return self.c.dbsn_mlp_set_variant(h, stationary, fixed_layout, banded)
+
+    def mlp_get_variant(self, h, stationary, layout, banded_pairs):
+        return self.c.dbsn_mlp_get_variant(h, _ptr(stationary), _ptr(layout), _ptr(banded_pairs))
 
     def mlp_autotune(self, h, samples, labels, n):
         return self.c.dbsn_mlp_autotune(h, _ptr(samples), _ptr(labels), n)
@@ -237,8 +241,14 @@ class Mlp:
     def status(self):
         self.lib.check(self.lib.mlp_status(self.h))
 
-    def set_variant(self, stationary=True, fixed_layout=True):
-        self.lib.check(self.lib.mlp_set_variant(self.h, int(stationary), int(fixed_layout)))
+    def set_variant(self, stationary=True, fixed_layout=True, banded=True):
+        self.lib.check(self.lib.mlp_set_variant(self.h, int(stationary), int(fixed_layout), int(banded)))
+
+    def get_variant(self):
+        """-> (stationary, layout, banded_pairs) in force"""
+        v = [np.zeros(1, np.int32) for _ in range(3)]
+        self.lib.check(self.lib.mlp_get_variant(self.h, v[0], v[1], v[2]))
+        return int(v[0][0]), int(v[1][0]), int(v[2][0])
 
     def get_pauses(self):
         f = np.zeros(self.L, np.int32)

@@ -85,6 +85,8 @@ struct dbsn_mlp {
     size_t lds_limit = 0;
     bool persistent_ready = false;   // LDS size and residency of the selected persistent kernel checked
     int layout = 0;            // register layout of the persistent kernel (0: packed at run time)
+    int tiles = 0;             // which of plan.tiles the persistent kernel uses (1: the banded cut)
+    bool dies_ok = false;      // workgroup g of a launch runs on die g % 8 on this device (probed)
     int* err = nullptr;
 };
 
@@ -187,33 +189,75 @@ int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, i
 }
 
 // Fills the persistent kernel's view of the network for the chosen variant: weights stationary in
-// registers or streamed per phase; register groups in a compile-time layout or packed at run time.
-void configure_persistent(dbsn_mlp* m, bool stationary, bool fixed_layout) {
+// registers or streamed per phase; row slots in a compile-time layout or packed at run time; tiles
+// in the banded cut (hand-overs inside a die where the layers pair up) or the plain one.
+void configure_persistent(dbsn_mlp* m, bool stationary, bool fixed_layout, bool banded) {
     const ArenaPlan& plan = m->plan;
     const Net& net = m->net;
     PNet& pn = m->pnet;
-    pn.stationary = (stationary && plan.stationary) ? 1 : 0;
-    m->layout = (pn.stationary && fixed_layout) ? choose_layout(plan, net.L) : 0;
+    m->tiles = (banded && plan.banded && m->dies_ok) ? 1 : 0;
+    const TilePlan& tp = plan.tiles[m->tiles];
+    pn.stationary = (stationary && tp.stationary) ? 1 : 0;
+    m->layout = (pn.stationary && fixed_layout) ? choose_layout(tp, net.L) : 0;
+    pn.any_local = 0;
     for (int l = 1; l <= net.L; ++l) {
         PLayer& P = pn.lay[l];
         const Layer& Ly = net.lay[l];
+        P = PLayer{};
         P.W = Ly.W; P.b = Ly.b; P.x = Ly.x; P.d = Ly.d;
         P.n_in = Ly.n_in; P.n_out = Ly.n_out; P.ld = Ly.ld;
-        if (l < net.L && plan.persistent_ok) {
-            P.nCB = plan.nCB[l]; P.nRB = plan.nRB[l]; P.C = plan.C[l]; P.R = plan.R[l];
-            P.g0 = m->layout ? kLayoutG0[m->layout][l - 1] : (pn.stationary ? plan.g0[l] : 0);
-            P.ng = plan.ng[l];
+        if (l < net.L && tp.ok) {
+            P.shape = tp.shape[l];
+            P.s0 = m->layout ? kLayoutS0[m->layout][l - 1] : (pn.stationary ? tp.s0[l] : 0);
+            P.ns = tp.ns[l];
+            P.fwd_local = tp.fwd_local[l] ? 1 : 0;
+            P.bwd_local = tp.bwd_local[l] ? 1 : 0;
+            pn.any_local |= P.fwd_local | P.bwd_local;
             P.yp = reinterpret_cast<u64*>(m->arena + plan.yp[l]);
             if (l <= net.L - 2) {
                 P.gp = reinterpret_cast<u64*>(m->arena + plan.gp[l]);
-                P.gP = plan.nRB[l + 1];
+                P.gP = tp.gP[l];
             }
         }
     }
     m->persistent_ready = false;
 }
 
+// Does workgroup g of a launch of kPGroups workgroups run on die g % 8?  Asked once per device: a
+// small kernel notes the die every workgroup finds itself on (in the static scratch array).
+std::mutex g_dies_mu;
+int g_dies_state[kMaxDevices] = {};   // 0: not probed, 1: yes, 2: no
+bool dies_follow_workgroup_index(int device, hipStream_t stream) {
+    std::lock_guard<std::mutex> lock(g_dies_mu);
+    if (device < 0 || device >= kMaxDevices) return false;
+    if (g_dies_state[device] == 0) {
+        g_dies_state[device] = 2;
+        int* ids = nullptr;
+        {
+            std::lock_guard<std::mutex> lk(g_scratch_mu);
+            ids = reinterpret_cast<int*>(g_scratch_ptr[device]);
+        }
+        int host[kPGroups];
+        if (ids) {
+            const size_t lds = sizeof(float) * (size_t)(PLds::total + kProfLdsFloats);   // the training kernel's footprint: one workgroup per CU
+            const void* fn = reinterpret_cast<const void*>(&k_die_probe);
+            void* args[] = {&ids};
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+                hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, stream) == hipSuccess &&
+                hipStreamSynchronize(stream) == hipSuccess &&
+                hipMemcpy(host, ids, sizeof host, hipMemcpyDeviceToHost) == hipSuccess) {
+                bool ok = true;
+                for (int g = 0; g < kPGroups; ++g) ok = ok && host[g] == g % kXcds;
+                if (ok) g_dies_state[device] = 1;
+            }
+            (void)hipGetLastError();
+        }
+    }
+    return g_dies_state[device] == 1;
+}
+
 bool use_persistent(const dbsn_mlp* m) { return m->mode == DBSN_MODE_PERSISTENT && m->plan.persistent_ok; }
+
 
 int32_t check_mlp(dbsn_mlp* m) { return m ? DBSN_OK : fail(DBSN_E_ARG, "null network handle"); }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -298,7 +342,8 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         pn.pace[0][l] = 17;
         pn.pace[1][l] = 0;
     }
-    configure_persistent(m, true, true);
+    m->dies_ok = plan.banded && prop.multiProcessorCount == kPGroups && dies_follow_workgroup_index(m->device, m->stream);
+    configure_persistent(m, true, true, true);
     // kernels that need more LDS than the default limit say so once, here
     {
         int32_t rc = DBSN_OK;
@@ -387,12 +432,20 @@ int32_t dbsn_mlp_get_pauses(dbsn_mlp* m, int32_t* fwd_host, int32_t* bwd_host) {
     return DBSN_OK;
 }
 
-int32_t dbsn_mlp_set_variant(dbsn_mlp* m, int32_t stationary, int32_t fixed_layout) {
+int32_t dbsn_mlp_set_variant(dbsn_mlp* m, int32_t stationary, int32_t fixed_layout, int32_t banded) {
     if (check_mlp(m)) return DBSN_E_ARG;
-    if ((stationary != 0 && stationary != 1) || (fixed_layout != 0 && fixed_layout != 1))
-        return fail(DBSN_E_ARG, "stationary and fixed_layout must be 0 or 1");
+    if ((stationary != 0 && stationary != 1) || (fixed_layout != 0 && fixed_layout != 1) || (banded != 0 && banded != 1))
+        return fail(DBSN_E_ARG, "stationary, fixed_layout and banded must be 0 or 1");
     HIP_TRY(hipStreamSynchronize(m->stream));
-    configure_persistent(m, stationary != 0, fixed_layout != 0);
+    configure_persistent(m, stationary != 0, fixed_layout != 0, banded != 0);
+    return DBSN_OK;
+}
+
+int32_t dbsn_mlp_get_variant(dbsn_mlp* m, int32_t* stationary, int32_t* layout, int32_t* banded_pairs) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    if (stationary) *stationary = m->pnet.stationary;
+    if (layout) *layout = m->layout;
+    if (banded_pairs) *banded_pairs = m->tiles ? m->plan.tiles[1].pairs : 0;
     return DBSN_OK;
 }
 
@@ -401,6 +454,14 @@ int32_t dbsn_mlp_status(dbsn_mlp* m) {
     HIP_TRY(hipStreamSynchronize(m->stream));
     int err = 0;
     HIP_TRY(hipMemcpy(&err, m->err, sizeof err, hipMemcpyDeviceToHost));
+    if (err == 2) {
+        HIP_TRY(hipMemset(m->err, 0, sizeof(int)));
+        m->epoch += (uint64_t)1 << 20;
+        m->dies_ok = false;   // fall back to the plain cut from here on
+        configure_persistent(m, m->pnet.stationary != 0, m->layout != 0, false);
+        return fail(DBSN_E_HIP, "workgroups were not placed on the dies as probed; the banded tiles are switched off, "
+                                "the weights are undefined");
+    }
     if (err) {
         HIP_TRY(hipMemset(m->err, 0, sizeof(int)));
         // stale partial sums of the abandoned steps must never match a later step's tag

@@ -105,9 +105,11 @@ struct PLayer {
                       //                            chunk rb holds, for p < gP (row blocks of layer l+1), the Reff(rb)
                       //                            rows of the block side by side; chunks are gP * R words apart
     int n_in, n_out, ld;
-    int nCB, nRB, C, R;
-    int gP;           // number of partial rows in gp = nRB of layer l+1
-    int g0, ng;       // register groups [g0, g0 + ng) hold this layer's tile
+    TileShape shape;  // how the layer is cut into tiles (dbsn_plan.h)
+    int gP;           // number of partial rows in gp = row blocks of layer l+1
+    int s0, ns;       // row slots [s0, s0 + ns) of a wavefront hold this layer's tile
+    int fwd_local;    // 1: the forward partial sums this layer publishes are read on the publisher's die only
+    int bwd_local;    // 1: the backward partial sums this layer publishes (for the layer below) likewise
 };
 
 struct PNet {
@@ -115,7 +117,8 @@ struct PNet {
     int* err;
     int L;
     unsigned spin_limit;
-    int stationary;   // 1: every layer has its own register groups for the whole launch
+    int stationary;   // 1: every layer has its own register slots for the whole launch
+    int any_local;    // 1: some hand-over stays inside a die, which relies on workgroup g running on die g % 8
     // pause of each (direction, layer) before its first look at the partials, in units of 64 clocks
     // ([0]: forward, index L the output layer; [1]: backward)
     unsigned char pace[2][kMaxLayers + 1];
@@ -125,7 +128,7 @@ struct PNet {
 constexpr int kPlanInts = 32;
 enum : int {
     PL_FLAGS = 0,   // bit 0: the workgroup has a tile of this layer; bit 1: column block 0; bit 2: row block 0
-    PL_CEFF, PL_REFF, PL_R0, PL_C0, PL_G0, PL_GEND,
+    PL_CEFF, PL_REFF, PL_R0, PL_C0, PL_S0, PL_SEND,   // (slots [S0, SEND) of a wavefront hold the tile's rows)
     PL_PF,          // forward: partials per input column = nCB of the layer below
     PL_FSTRIDE,     // forward: words between two partials of one column = n of the layer below
     PL_FPAR,        // forward source: words between the two parity buffers
@@ -134,10 +137,8 @@ enum : int {
     PL_NW,          // backward: words of this tile's chunk = gP * Reff
     PL_BPAR,        // backward source: words between the parity buffers
     PL_BDPAR,       // backward destination (gp of the layer below): words between the parity buffers
-    PL_RPREV,       // rows per row block of the layer below
-    PL_M20,         // ceil(2^20 / RPREV): c / RPREV == (c * M20) >> 20 for c < 4096, RPREV <= 224
-    PL_NPREV,       // neurons of the layer below
-    PL_CHUNKPREV,   // words between two chunks of the layer below's gp
+    PL_FLOCAL,      // forward: 1 when every reader of the words published here runs on this die
+    PL_BLOCAL,      // backward: likewise for the words published for the layer below
     PL_RB,          // row block of this tile
     PL_FSRC = 20,   // (2 words each) pointers: forward source of parity 0 at this tile's first column,
     PL_FDST = 22,   //   forward destination at this tile's first row,
@@ -159,7 +160,9 @@ struct PLds {
     static constexpr int plan = dtop + kTopXMax;                  // [kMaxLayers + 1][kPlanInts]
     static constexpr int fail = plan + (kMaxLayers + 1) * kPlanInts;   // [1] set when a wait gave up
     static constexpr int pace = fail + 16;                        // [2][kMaxLayers + 1] pauses before polling
-    static constexpr int total = pace + 2 * (kMaxLayers + 1) + 14;
+    static constexpr int bdst = pace + 2 * (kMaxLayers + 1) + 14; // [kMaxLayers + 1][256] where column i of the layer's tile
+                                                                  //   publishes its backward partial sum (word offset in gp)
+    static constexpr int total = bdst + (kMaxLayers + 1) * 256;
 };
 static_assert((PLds::total + kProfLdsFloats) * 4 <= 160 * 1024, "LDS map exceeds 160 KB");
 static_assert(kMaxClasses * kWaves <= kWaves * 264, "partial logits do not fit");
@@ -173,6 +176,14 @@ __device__ inline u64 ld_tagged(const u64* p) {
 }
 __device__ inline void st_tagged(u64* p, float v, unsigned tag) {
     __hip_atomic_store((global_u64*)p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The same for words whose readers all run on the publisher's die (`local`, uniform): the store
+// then stops at the die's L2, where the readers' device-scope loads find it, in half the time of a
+// store that has to become visible to the other dies.  (Were the word ever evicted, it would reach
+// memory, where those loads look next: visibility never depends on luck, only speed does.)
+__device__ inline void st_tagged(u64* p, float v, unsigned tag, bool local) {
+    if (local) __hip_atomic_store((global_u64*)p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    else __hip_atomic_store((global_u64*)p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -335,59 +346,65 @@ __device__ __forceinline__ void run_groups(F&& f) {
 }
 // POS = 0: the layer is known at run time only (LAYOUT 0); POS = 1 .. kLayoutDepth[LAYOUT]: the
 // phase is compiled for hidden layer POS of that layout.
+// (s0, send: the layer's slots; the groups that hold any of them run.  A group shared with a
+// neighbouring layer runs for both: the foreign row's dot product is never published, and in the
+// backward sweep it meets a zero delta.)
 template <int LAYOUT, int POS, class F>
-__device__ __forceinline__ void layer_groups(int g0, int gend, F&& f) {
-    if constexpr (POS == 0) for_layer_groups(g0, gend, f);
+__device__ __forceinline__ void layer_groups(int s0, int send, F&& f) {
+    if constexpr (POS == 0) for_layer_groups(s0 / kGR, (send + kGR - 1) / kGR, f);
     else {
-        static_assert(POS <= kLayoutDepth[LAYOUT] && kLayoutG0[LAYOUT][POS - 1] + kLayoutNG[LAYOUT][POS - 1] <= kNG,
-                      "the layout has this layer and its groups exist");
-        run_groups<kLayoutG0[LAYOUT][POS - 1], kLayoutG0[LAYOUT][POS - 1] + kLayoutNG[LAYOUT][POS - 1]>(f);
+        static_assert(POS <= kLayoutDepth[LAYOUT] && kLayoutS0[LAYOUT][POS - 1] + kLayoutNS[LAYOUT][POS - 1] <= kSlots,
+                      "the layout has this layer and its slots exist");
+        run_groups<kLayoutS0[LAYOUT][POS - 1] / kGR,
+                   (kLayoutS0[LAYOUT][POS - 1] + kLayoutNS[LAYOUT][POS - 1] + kGR - 1) / kGR>(f);
     }
 }
 
-// Register slot a = kGR * G + q of group G holds tile row wave + 8 * (a - kGR * g0) of the layer
-// whose groups start at g0 ("absolute" slot a, the same index in every per-slot register).
+// Register slot a of a wavefront holds tile row wave + 8 * (a - s0) of the layer whose slots start
+// at s0 ("absolute" slot a, the same index in every per-slot register; group G = slots 2 G, 2 G + 1).
 struct TileGeom {
     float* wbase;   // &W[r0][c0 + 4 * lane]
-    int ld, Reff, g0, gend;
+    int ld, Reff, s0, send;
     bool lane_on;
 };
-__device__ inline TileGeom tile_geom(const PLayer& Ly, int g) {
-    TileGeom t;
+__device__ inline bool tile_geom(const PLayer& Ly, int g, TileGeom& t) {
+    TileAt at;
+    if (!tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at)) return false;
     const int lane = threadIdx.x & 63;
-    const int cb = g % Ly.nCB, rb = g / Ly.nCB;
-    const int c0 = cb * Ly.C, r0 = rb * Ly.R;
     t.ld = Ly.ld;
-    t.Reff = min(Ly.R, Ly.n_out - r0);
-    t.g0 = Ly.g0;
-    t.gend = Ly.g0 + Ly.ng;
-    t.lane_on = (4 * lane < Ly.C) && (c0 + 4 * lane < Ly.ld);
-    t.wbase = Ly.W + (size_t)r0 * Ly.ld + c0 + 4 * lane;
-    return t;
+    t.Reff = at.Reff;
+    t.s0 = Ly.s0;
+    t.send = Ly.s0 + Ly.ns;
+    t.lane_on = (4 * lane < at.Ceff);   // (row pitch and column starts are multiples of 4: a float4 never leaves the row)
+    t.wbase = Ly.W + (size_t)at.r0 * Ly.ld + at.c0 + 4 * lane;
+    return true;
 }
-__device__ inline bool has_tile(const PLayer& Ly, int g) { return g < Ly.nCB * Ly.nRB; }
 
+// (slots outside [s0, send) belong to other layers and are left alone)
 __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const TileGeom& t) {
     const int wave = threadIdx.x >> 6;
-    for_layer_groups(t.g0, t.gend, [&](auto Gc) {
+    for_layer_groups(t.s0 / kGR, (t.send + kGR - 1) / kGR, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
 #pragma unroll
         for (int q = 0; q < kGR; ++q) {
-            const int rl = wave + kWaves * (kGR * (G - t.g0) + q);
-            wr[kGR * G + q] = (rl < t.Reff && t.lane_on)
-                                  ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * t.ld)
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int a = kGR * G + q;
+            const int rl = wave + kWaves * (a - t.s0);
+            if (a >= t.s0 && a < t.send)
+                wr[a] = (rl < t.Reff && t.lane_on) ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * t.ld)
+                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     });
 }
 __device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const TileGeom& t) {
     const int wave = threadIdx.x >> 6;
-    for_layer_groups(t.g0, t.gend, [&](auto Gc) {
+    for_layer_groups(t.s0 / kGR, (t.send + kGR - 1) / kGR, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
 #pragma unroll
         for (int q = 0; q < kGR; ++q) {
-            const int rl = wave + kWaves * (kGR * (G - t.g0) + q);
-            if (rl < t.Reff && t.lane_on) *reinterpret_cast<float4*>(t.wbase + (size_t)rl * t.ld) = wr[kGR * G + q];
+            const int a = kGR * G + q;
+            const int rl = wave + kWaves * (a - t.s0);
+            if (a >= t.s0 && a < t.send && rl < t.Reff && t.lane_on)
+                *reinterpret_cast<float4*>(t.wbase + (size_t)rl * t.ld) = wr[a];
         }
     });
 }
@@ -430,45 +447,56 @@ __device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
     if (l == L) {   // output layer: only the gathering of x_{L-1}
         const PLayer& Lp = net.lay[L - 1];
         pl[PL_FLAGS] = 1;
-        pl[PL_PF] = Lp.nCB;
+        pl[PL_PF] = Lp.shape.nCB;
         pl[PL_FSTRIDE] = Lp.n_out;
-        pl[PL_FPAR] = Lp.nCB * Lp.n_out;
+        pl[PL_FPAR] = Lp.shape.nCB * Lp.n_out;
         put_ptr(PL_FSRC, Lp.yp);
         return;
     }
-    if (!has_tile(Ly, g)) return;
-    const int cb = g % Ly.nCB, rb = g / Ly.nCB;
-    const int c0 = cb * Ly.C, r0 = rb * Ly.R;
-    const int Reff = min(Ly.R, Ly.n_out - r0);
-    pl[PL_FLAGS] = 1 | (cb == 0 ? 2 : 0) | (rb == 0 ? 4 : 0);
-    pl[PL_CEFF] = min(Ly.C, Ly.n_in - c0);
-    pl[PL_REFF] = Reff;
-    pl[PL_R0] = r0;
-    pl[PL_C0] = c0;
-    pl[PL_G0] = Ly.g0;
-    pl[PL_GEND] = Ly.g0 + Ly.ng;
-    pl[PL_RB] = rb;
-    pl[PL_FDPAR] = Ly.nCB * Ly.n_out;
-    put_ptr(PL_FDST, Ly.yp + (size_t)cb * Ly.n_out + r0);
+    TileAt at;
+    if (!tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at)) return;
+    pl[PL_FLAGS] = 1 | (at.cb == 0 ? 2 : 0) | (at.rb == 0 ? 4 : 0);
+    pl[PL_CEFF] = at.Ceff;
+    pl[PL_REFF] = at.Reff;
+    pl[PL_R0] = at.r0;
+    pl[PL_C0] = at.c0;
+    pl[PL_S0] = Ly.s0;
+    pl[PL_SEND] = Ly.s0 + Ly.ns;
+    pl[PL_RB] = at.rb;
+    pl[PL_FLOCAL] = Ly.fwd_local;
+    pl[PL_BLOCAL] = Ly.bwd_local;
+    pl[PL_FDPAR] = Ly.shape.nCB * Ly.n_out;
+    put_ptr(PL_FDST, Ly.yp + (size_t)at.cb * Ly.n_out + at.r0);
     if (l > 1) {
         const PLayer& Lp = net.lay[l - 1];
-        pl[PL_PF] = Lp.nCB;
+        pl[PL_PF] = Lp.shape.nCB;
         pl[PL_FSTRIDE] = Lp.n_out;
-        pl[PL_FPAR] = Lp.nCB * Lp.n_out;
-        put_ptr(PL_FSRC, Lp.yp + c0);
-        pl[PL_BDPAR] = Lp.nRB * Lp.R * Lp.gP;
-        pl[PL_RPREV] = Lp.R;
-        pl[PL_M20] = ((1 << 20) + Lp.R - 1) / Lp.R;
-        pl[PL_NPREV] = Lp.n_out;
-        pl[PL_CHUNKPREV] = Lp.gP * Lp.R;
+        pl[PL_FPAR] = Lp.shape.nCB * Lp.n_out;
+        put_ptr(PL_FSRC, Lp.yp + at.c0);
+        pl[PL_BDPAR] = Lp.shape.nRB * Lp.shape.R * Lp.gP;
         put_ptr(PL_BDST, Lp.gp);
     }
     if (l < L - 1) {
         pl[PL_GP] = Ly.gP;
-        pl[PL_NW] = Ly.gP * Reff;
-        pl[PL_BPAR] = Ly.nRB * Ly.R * Ly.gP;
-        put_ptr(PL_BSRC, Ly.gp + (size_t)rb * Ly.gP * Ly.R);
+        pl[PL_NW] = Ly.gP * at.Reff;
+        pl[PL_BPAR] = Ly.shape.nRB * Ly.shape.R * Ly.gP;
+        put_ptr(PL_BSRC, Ly.gp + (size_t)at.rb * Ly.gP * Ly.shape.R);
     }
+}
+
+// Where column i of this workgroup's tile of layer l publishes its backward partial sum: neuron
+// c = c0 + i of layer l-1 belongs to that layer's row block rb', whose chunk of gp keeps one run of
+// its Reff' rows per row block of layer l.  Worked out once per launch (thread i of the workgroup).
+__device__ inline void make_bdst(const PNet& net, int l, int g, int i, float* lds) {
+    int* tab = reinterpret_cast<int*>(lds + PLds::bdst) + l * 256;
+    tab[i] = 0;
+    if (l < 2 || l >= net.L) return;
+    TileAt at;
+    if (!tile_at(net.lay[l].shape, net.lay[l].n_in, net.lay[l].n_out, g, at) || i >= at.Ceff) return;
+    const PLayer& Lp = net.lay[l - 1];
+    int rbp, jp, reffp;
+    row_block_at(Lp.shape, Lp.n_out, at.c0 + i, rbp, jp, reffp);
+    tab[i] = rbp * (Lp.gP * Lp.shape.R) + at.rb * reffp + jp;
 }
 
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
@@ -481,9 +509,12 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
     const int Ceff = uniform(pl[PL_CEFF]), Reff = uniform(pl[PL_REFF]);
-    const int g0 = uniform(pl[PL_G0]), gend = uniform(pl[PL_GEND]);
+    const int s0 = uniform(pl[PL_S0]), send = uniform(pl[PL_SEND]);
     DBSN_PROF_SUB(ps, ph, 0);
-    if (!ST) load_tile(wr, tile_geom(net.lay[l], g));  // in flight while the inputs are awaited
+    if (!ST) {   // in flight while the inputs are awaited
+        TileGeom tg;
+        if (tile_geom(net.lay[l], g, tg)) load_tile(wr, tg);
+    }
 
     float* xk = lds + PLds::xkeep + l * 256;
     if (l == 1) {
@@ -514,25 +545,25 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 3);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     // the lane that will publish absolute slot a = lane (lanes 0 .. 31): tile row and bias
-    const int myrow = wave + kWaves * (lane - kGR * g0);
-    const bool pub = lane >= kGR * g0 && lane < kGR * gend && myrow < Reff;
+    const int myrow = wave + kWaves * (lane - s0);
+    const bool pub = lane >= s0 && lane < send && myrow < Reff;
     const float mybias = (pub && (flags & 2)) ? lds[PLds::bias + l * kMaxTileRows + myrow] : 0.0f;
     // per group: the two row sums transposed onto the even and odd lanes and reduced inside each row
     // of 16 lanes; lane 16 r + (a & 15) keeps the sum of slot a over lane row r
     float res0 = 0.0f, res1 = 0.0f;
     const int lane14 = lane & 14;
-    layer_groups<LAYOUT, POS>(g0, gend, [&](auto Gc) {
+    layer_groups<LAYOUT, POS>(s0, send, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
         const float v2 = pair_sum2(dot4(wr[kGR * G + 0], x4), dot4(wr[kGR * G + 1], x4));
         if (kGR * G < 16) res0 = (lane14 == ((kGR * G) & 14)) ? v2 : res0;
         else res1 = (lane14 == ((kGR * G) & 14)) ? v2 : res1;
     });
     res0 = rows_sum(res0);
-    if (gend > 8) res1 = rows_sum(res1);
+    if (send > 16) res1 = rows_sum(res1);
     DBSN_PROF_SUB(ps, ph, 4);
     if (pub) {
         u64* dst = plan_ptr(pl, PL_FDST) + (size_t)(par * (unsigned)uniform(pl[PL_FDPAR]));
-        st_tagged(dst + myrow, ((lane < 16) ? res0 : res1) + mybias, tag);
+        st_tagged(dst + myrow, ((lane < 16) ? res0 : res1) + mybias, tag, uniform(pl[PL_FLOCAL]) != 0);
     }
     DBSN_PROF_SUB(ps, ph, 7);
     return true;
@@ -551,10 +582,10 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned par = tag & 1u;
     const int Ceff = uniform(pl[PL_CEFF]), Reff = uniform(pl[PL_REFF]);
-    const int g0 = uniform(pl[PL_G0]), gend = uniform(pl[PL_GEND]);
+    const int s0 = uniform(pl[PL_S0]), send = uniform(pl[PL_SEND]);
     DBSN_PROF_SUB(ps, ph, 0);
     TileGeom tg;
-    if (!ST) { tg = tile_geom(net.lay[l], g); load_tile(wr, tg); }
+    if (!ST) { tile_geom(net.lay[l], g, tg); load_tile(wr, tg); }   // (flags & 1: the tile exists)
     // the tile's inputs, kept since the forward sweep (read before this phase's first barrier: the
     // next step's forward sweep overwrites them after it)
     const float* xk = lds + PLds::xkeep + l * 256;
@@ -567,9 +598,9 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     // partials to classes p mod NPC; wavefront w takes rows 64 (w mod NR) ... and class w / NR,
     // adds its partials in index order and leaves the sum in LDS; then lane a adds the NPC sums of
     // its row in class order.
-    const int srel = lane - kGR * g0;   // slot of this lane within the layer
+    const int srel = lane - s0;   // slot of this lane within the layer
     const int myrow = wave + kWaves * srel;
-    const bool rowon = srel >= 0 && lane < kGR * gend && myrow < Reff;
+    const bool rowon = srel >= 0 && lane < send && myrow < Reff;
     float dlane = 0.0f;
     if (l == net.L - 1) {
         if (rowon) dlane = lds[PLds::dtop + uniform(pl[PL_R0]) + myrow];
@@ -604,7 +635,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 3);
     if (l > 1) {
         float4 gacc = make_float4(0.f, 0.f, 0.f, 0.f);
-        layer_groups<LAYOUT, POS>(g0, gend, [&](auto Gc) {
+        layer_groups<LAYOUT, POS>(s0, send, [&](auto Gc) {
             constexpr int G = decltype(Gc)::value;
 #pragma unroll
             for (int q = 0; q < kGR; ++q) {
@@ -630,24 +661,18 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
             float s8 = 0.0f;
 #pragma unroll
             for (int k = 0; k < kWaves; ++k) s8 += v8[k];
-            // where the word goes: neuron c of the layer below belongs to that layer's row block
-            // c / R', whose chunk keeps this tile's row block rb at offset rb * Reff'
-            const unsigned c = (unsigned)uniform(pl[PL_C0]) + (unsigned)i;
-            const unsigned Rp = (unsigned)uniform(pl[PL_RPREV]);
-            const unsigned rbq = (c * (unsigned)uniform(pl[PL_M20])) >> 20;
-            const unsigned jp = c - rbq * Rp;
-            const unsigned Reffp = min(Rp, (unsigned)uniform(pl[PL_NPREV]) - rbq * Rp);
+            // where the word goes (see make_bdst)
+            const unsigned at = (unsigned)reinterpret_cast<const int*>(lds + PLds::bdst)[l * 256 + i];
             u64* dst = plan_ptr(pl, PL_BDST) + (size_t)(par * (unsigned)uniform(pl[PL_BDPAR]));
             // this tile's columns are neurons of layer l-1 whose outputs it holds: fold f' in here,
             // so that the consumer's sum over row blocks is delta_{l-1} itself
-            st_tagged(dst + (rbq * (unsigned)uniform(pl[PL_CHUNKPREV]) + (unsigned)uniform(pl[PL_RB]) * Reffp + jp),
-                      s8 * dact_from_y(xi), tag);
+            st_tagged(dst + at, s8 * dact_from_y(xi), tag, uniform(pl[PL_BLOCAL]) != 0);
         }
     }
     DBSN_PROF_SUB(ps, ph, 6);
     // rank-1 update of the tile held in registers, w[j][i] -= eta * delta_j * x_i; rows beyond the
     // tile hold zeros and get a zero delta, so they stay zero
-    layer_groups<LAYOUT, POS>(g0, gend, [&](auto Gc) {
+    layer_groups<LAYOUT, POS>(s0, send, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
 #pragma unroll
         for (int q = 0; q < kGR; ++q) {
@@ -853,6 +878,14 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     return true;
 }
 
+// The die (XCD) this wavefront runs on: bits 3:0 of the hardware register XCC_ID.
+__device__ inline int die_id() { return (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u); }
+
+// Notes, for every workgroup of a launch shaped like the training kernel's, the die it runs on.
+__global__ __launch_bounds__(kThreads) void k_die_probe(int* ids) {
+    if (threadIdx.x == 0) ids[blockIdx.x] = die_id();
+}
+
 template <bool ST, int LAYOUT>
 __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float* samples, const int* labels,
                                                            int label_val, long long n, float eta, float* loss_out,
@@ -874,23 +907,31 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
+    // hand-overs inside a die assume that workgroup g runs on die g % 8: say so if it does not (the
+    // waits of the workgroups concerned then give up by themselves)
+    if (net.any_local && threadIdx.x == 0 && die_id() != g % kXcds)
+        __hip_atomic_store(net.err, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1); e += kThreads)
         reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[e / (kMaxLayers + 1)][e % (kMaxLayers + 1)];
     if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
+    for (int l = 1; l <= kMaxLayers; ++l)
+        if (threadIdx.x < 256) make_bdst(net, l, g, threadIdx.x, lds);
 
     for (int l = 1; l < L; ++l) {
         const PLayer& Ly = net.lay[l];
-        if (has_tile(Ly, g) && g % Ly.nCB == 0) {
-            const int r0 = (g / Ly.nCB) * Ly.R, Reff = min(Ly.R, Ly.n_out - r0);
-            for (int j = threadIdx.x; j < Reff; j += kThreads) lds[PLds::bias + l * kMaxTileRows + j] = Ly.b[r0 + j];
+        TileAt at;
+        if (tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at) && at.cb == 0) {
+            for (int j = threadIdx.x; j < at.Reff; j += kThreads) lds[PLds::bias + l * kMaxTileRows + j] = Ly.b[at.r0 + j];
         }
     }
     float4 wr[kSlots];
 #pragma unroll
     for (int s = 0; s < kSlots; ++s) wr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ST) {
-        for (int l = 1; l < L; ++l)
-            if (has_tile(net.lay[l], g)) load_tile(wr, tile_geom(net.lay[l], g));
+        for (int l = 1; l < L; ++l) {
+            TileGeom tg;
+            if (tile_geom(net.lay[l], g, tg)) load_tile(wr, tg);
+        }
     }
     __syncthreads();
 
@@ -978,15 +1019,17 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
 #undef DBSN_BWD
     }
     if (ST) {
-        for (int l = 1; l < L; ++l)
-            if (has_tile(net.lay[l], g)) store_tile(wr, tile_geom(net.lay[l], g));
+        for (int l = 1; l < L; ++l) {
+            TileGeom tg;
+            if (tile_geom(net.lay[l], g, tg)) store_tile(wr, tg);
+        }
     }
     __syncthreads();
     for (int l = 1; l < L; ++l) {
         const PLayer& Ly = net.lay[l];
-        if (has_tile(Ly, g) && g % Ly.nCB == 0) {
-            const int r0 = (g / Ly.nCB) * Ly.R, Reff = min(Ly.R, Ly.n_out - r0);
-            for (int j = threadIdx.x; j < Reff; j += kThreads) Ly.b[r0 + j] = lds[PLds::bias + l * kMaxTileRows + j];
+        TileAt at;
+        if (tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at) && at.cb == 0) {
+            for (int j = threadIdx.x; j < at.Reff; j += kThreads) Ly.b[at.r0 + j] = lds[PLds::bias + l * kMaxTileRows + j];
         }
     }
     DBSN_PROF_FLUSH();

@@ -75,7 +75,8 @@ def test_argument_errors_without_device(dbsn):
     assert dbsn.mean_loss(None, 0, None) == binding.E_ARG
     assert dbsn.mlp_set_pauses(None, None, None) == binding.E_ARG
     assert dbsn.mlp_get_pauses(None, None, None) == binding.E_ARG
-    assert dbsn.mlp_set_variant(None, 1, 1) == binding.E_ARG
+    assert dbsn.mlp_set_variant(None, 1, 1, 1) == binding.E_ARG
+    assert dbsn.mlp_get_variant(None, None, None, None) == binding.E_ARG
 
 
 def test_missing_library_fails_loudly(tmp_path):

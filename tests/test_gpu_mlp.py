@@ -412,20 +412,25 @@ def test_random_shapes_three_steps(oracle):
         m.close(); one.close()
 
 
-@pytest.mark.parametrize("sizes", [NET0, [784, 1500, 1000, 500, 10], [784] + [300] * 9 + [10]])
-def test_kernel_variants_agree_bit_for_bit(sizes):
+@pytest.mark.parametrize("sizes", [NET0, [784, 1500, 1000, 500, 10], [784] + [300] * 9 + [10], NET4])
+def test_kernel_variants_agree(sizes):
     """The persistent kernel with its weights held in registers in a compile-time layout (the
-    default for these nets), with register groups packed at run time, and with the weights streamed
+    default for these nets), with registers packed at run time, and with the weights streamed
     from memory in every phase: the same sums in the same order, in three separately compiled
     kernels (the compiler may fuse a multiply and an add in one and not in another), so they agree
-    to rounding; the pauses before polling change nothing at all."""
+    to rounding; the pauses before polling change nothing at all.  The plain cut of the layers
+    instead of the banded one groups the partial sums differently, like the launch-per-phase mode."""
     torch = _torch()
     X, y = _data(40, seed=9)
     xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     out = []
-    for stationary, fixed, pauses in ((True, True, None), (True, False, None), (False, True, None), (True, True, 3)):
+    for stationary, fixed, banded, pauses in ((True, True, True, None), (True, False, True, None), (False, True, True, None),
+                                              (True, True, True, 3), (True, True, False, None), (False, False, False, None)):
         m = _mk(sizes, 1, seed=2)
-        m.set_variant(stationary=stationary, fixed_layout=fixed)
+        m.set_variant(stationary=stationary, fixed_layout=fixed, banded=banded)
+        st, lay, pairs = m.get_variant()
+        assert st == int(stationary) and (lay > 0) == (stationary and fixed)
+        assert pairs == 0 if not banded else pairs >= 1       # (every net of this test has layers to pair)
         if pauses is not None:
             L = len(sizes) - 1
             m.set_pauses([pauses] * L, [2 * pauses] * L)
@@ -443,4 +448,7 @@ def test_kernel_variants_agree_bit_for_bit(sizes):
     assert np.array_equal(out[3][0], out[0][0]) and np.array_equal(out[3][1], out[0][1])    # same kernel, other pauses
     for (p, l), d in zip(out[1:3], diffs[1:3]):
         assert d <= 1e-7, diffs
+        assert np.abs(l - out[0][1]).max() <= 1e-5
+    for (p, l), d in zip(out[4:], diffs[4:]):
+        assert d <= 2e-6, diffs
         assert np.abs(l - out[0][1]).max() <= 1e-5

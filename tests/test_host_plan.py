@@ -1,6 +1,6 @@
 """The pure-host part of libdbsn (arena layout, tile geometry of the persistent kernel, choice of
 the register layout, shape checks: csrc/dbsn_plan.h) compiled with g++ under AddressSanitizer and
-UndefinedBehaviorSanitizer and run over 20,000 random layer shapes, no GPU involved."""
+UndefinedBehaviorSanitizer and run over 2,000 random layer shapes (every weight of every layer counted into its tile), no GPU involved."""
 import os
 import subprocess
 
@@ -15,6 +15,6 @@ def test_host_planning_under_sanitizers(tmp_path):
            os.path.join(ROOT, "tests", "host_plan_check.cpp"), "-o", exe]
     subprocess.run(cmd, check=True)
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
-    r = subprocess.run([exe, "20000"], capture_output=True, text=True, env=env, timeout=300)
+    r = subprocess.run([exe, "2000"], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0, r.stdout + r.stderr
-    assert r.stdout.strip() == "ok 20000", r.stdout + r.stderr
+    assert r.stdout.strip() == "ok 2000", r.stdout + r.stderr
