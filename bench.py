@@ -110,7 +110,7 @@ def main():
                     help="which of BASELINE.json's nets the headline runs (default 3, the benchmark)")
     ap.add_argument("--net", type=str, default=None,
                     help="layer sizes a-b-...-c of the headline run instead of a config's net (context runs)")
-    ap.add_argument("--variant", choices=["default", "streaming", "runtime-layout"], default="default",
+    ap.add_argument("--variant", choices=["default", "streaming", "runtime-layout", "plain-tiles"], default="default",
                     help="persistent-kernel variant of the headline run (see dbsn_mlp_set_variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-classify", action="store_true")
@@ -155,6 +155,8 @@ def main():
             m.set_variant(stationary=False)
         elif variant == "runtime-layout":
             m.set_variant(fixed_layout=False)
+        elif variant == "plain-tiles":
+            m.set_variant(banded=False)
         if not deform:   # the same un-deformed chunk every step
             lib.check(lib.deform_batch(identity, src[:chunk], chunk, 0, 0, xbuf, stream))
 
@@ -195,8 +197,9 @@ def main():
         final_loss = float(loss.mean())
         assert np.isfinite(final_loss)
         bp_ms = [a.elapsed_time(b) for a, b in events]
+        f, b = m.get_pauses()
         return {"mlp": m, "dt": dt, "bp_avg_s": sum(bp_ms) / len(bp_ms) / 1e3, "final_loss": final_loss,
-                "autotune_s": tune_s}
+                "autotune_s": tune_s, "variant": m.get_variant(), "pauses": [f.tolist(), b.tolist()]}
 
     def summary(sizes, r, extra=None):
         nw = n_weights(sizes)
@@ -204,7 +207,8 @@ def main():
         d = {"net": "-".join(map(str, sizes)), "weights": nw, "us_per_sample": per * 1e6,
              "samples_per_s_bp_steps_alone": 1.0 / per,
              "algorithmic_GBps": 12.0 * nw / per / 1e9, "frac": 12.0 * nw / per / 1e9 / HBM_PEAK_GBS,
-             "us_per_phase": per * 1e6 / (2 * (len(sizes) - 1)), "phases_per_step": 2 * (len(sizes) - 1)}
+             "us_per_phase": per * 1e6 / (2 * (len(sizes) - 1)), "phases_per_step": 2 * (len(sizes) - 1),
+             "stationary_layout_bandedpairs": list(r["variant"]), "pauses_fwd_bwd": r["pauses"]}
         if extra:
             d.update(extra)
         return d
@@ -243,6 +247,8 @@ def main():
             "samples_per_step": chunk,
             "mode": "persistent" if args.mode == 1 else "launch-per-phase",
             "variant": args.variant,
+            "stationary_layout_bandedpairs": list(head["variant"]),
+            "pauses_fwd_bwd": head["pauses"],
             "autotune_s": head["autotune_s"],
         },
         "roofline": {

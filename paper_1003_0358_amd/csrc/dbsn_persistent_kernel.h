@@ -292,6 +292,34 @@ __device__ __forceinline__ float poll_sum(const u64* base, unsigned col, int P, 
     return poll_sum_n<12>(base, col, P, stride, tag, limit, ok, s);
 }
 
+// Two columns at once (col0, col1 of the same rows): all 2 N loads in flight together, one wait for
+// both.  P <= N.
+template <int N>
+__device__ __forceinline__ void poll_sum_pair(const u64* base, unsigned col0, unsigned col1, int P, unsigned stride,
+                                              unsigned tag, unsigned limit, bool& ok, float& s0, float& s1) {
+    u64 v0[N], v1[N];
+    unsigned spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const u64* row = base + (size_t)((unsigned)min(k, P - 1) * stride);
+            v0[k] = ld_tagged(row + col0);
+            v1[k] = ld_tagged(row + col1);
+        }
+        bool pending = false;
+#pragma unroll
+        for (int k = 0; k < N; ++k) pending |= ((unsigned)(v0[k] >> 32) != tag) | ((unsigned)(v1[k] >> 32) != tag);
+        if (!__any(pending && DBSN_WAITING(limit))) break;
+        if (++spins > limit) { ok = false; break; }
+    }
+    s0 = 0.0f; s1 = 0.0f;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        s0 += (k < P) ? __uint_as_float((unsigned)v0[k]) : 0.0f;
+        s1 += (k < P) ? __uint_as_float((unsigned)v1[k]) : 0.0f;
+    }
+}
+
 // Pacing of the polls.  A batch of loads that comes back without the data costs a full round trip
 // before the next one can be judged, so it pays to look a little later and find the data at the
 // first look.  How much later depends on the layer, the direction and the machine: one pause per
@@ -699,23 +727,29 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     return true;
 }
 
-// Registers of the output phase when a thread owns one column of W_L and there are at most 16
-// classes (the paper's nets): the column itself, for the whole launch, and what its update needs,
-// which is applied after the backward phase that follows has published its partial sums.
+// Registers of the output phase when a thread owns TC columns of W_L (i, i + 512, ...) and there
+// are at most 16 classes (the paper's nets): the columns themselves, for the whole launch, and what
+// their update needs, which is applied after the backward phase that follows has published its
+// partial sums.  TC = 1 covers last hidden layers of up to 512 neurons, TC = 2 up to 1024.
+template <int TC>
 struct TopRegs {
-    float w[16];    // W_L[c][i] of this thread's column i, classes padded with zeros
-    float xi;       // x_{L-1}[i] of the step in flight
+    float w[TC][16];    // W_L[c][i] of this thread's columns, classes padded with zeros
+    float xi[TC];       // x_{L-1}[i] of the step in flight
 };
 // (delta_L of the step is still in LDS, padded with zeros up to 16 classes)
-__device__ __forceinline__ void top_update(TopRegs& tr, float eta, const float* lds) {
+template <int TC>
+__device__ __forceinline__ void top_update(TopRegs<TC>& tr, float eta, const float* lds) {
     const float4* dL = reinterpret_cast<const float4*>(lds + PLds::dLp);
 #pragma unroll
     for (int jq = 0; jq < 4; ++jq) {
         const float4 d4 = dL[jq];
-        tr.w[4 * jq + 0] = fmaf(-(eta * d4.x), tr.xi, tr.w[4 * jq + 0]);
-        tr.w[4 * jq + 1] = fmaf(-(eta * d4.y), tr.xi, tr.w[4 * jq + 1]);
-        tr.w[4 * jq + 2] = fmaf(-(eta * d4.z), tr.xi, tr.w[4 * jq + 2]);
-        tr.w[4 * jq + 3] = fmaf(-(eta * d4.w), tr.xi, tr.w[4 * jq + 3]);
+#pragma unroll
+        for (int c = 0; c < TC; ++c) {
+            tr.w[c][4 * jq + 0] = fmaf(-(eta * d4.x), tr.xi[c], tr.w[c][4 * jq + 0]);
+            tr.w[c][4 * jq + 1] = fmaf(-(eta * d4.y), tr.xi[c], tr.w[c][4 * jq + 1]);
+            tr.w[c][4 * jq + 2] = fmaf(-(eta * d4.z), tr.xi[c], tr.w[c][4 * jq + 2]);
+            tr.w[c][4 * jq + 3] = fmaf(-(eta * d4.w), tr.xi[c], tr.w[c][4 * jq + 3]);
+        }
     }
 }
 
@@ -725,8 +759,9 @@ __device__ __forceinline__ void top_update(TopRegs& tr, float eta, const float* 
 // (and i + 512, ...): it gathers x_i and forms the products W_L[j][i] x_i; the workgroup adds them
 // per class (quads -> rows of 16 lanes on the vector ALU, then 32 partial sums per class through
 // LDS); wavefront 0 does the softmax, and each thread back-propagates through and updates its columns.
+template <int TC>
 __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float eta, unsigned tag, float* loss_out,
-                                      bool last, float* lds, const PlanRow& pl, TopRegs& tr, long long ps,
+                                      bool last, float* lds, const PlanRow& pl, TopRegs<TC>& tr, long long ps,
                                       int ph DBSN_PROF_ARGS) {
     const int L = net.L;
     const PLayer& Ly = net.lay[L];
@@ -746,20 +781,43 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     const unsigned stride = (unsigned)uniform(pl[PL_FSTRIDE]);
     const u64* base = plan_ptr(pl, PL_FSRC) + (size_t)(par * (unsigned)uniform(pl[PL_FPAR]));
     pace_begin(lds, 0, L);
-    // One column per thread and at most 16 classes (the paper's nets): the column of W_L stays in
-    // registers from the products to the update.  Otherwise the same steps with loops over the
+    // At most TC columns per thread and at most 16 classes (the paper's nets): the columns of W_L stay
+    // in registers from the products to the update.  Otherwise the same steps with loops over the
     // thread's columns and the classes.
-    const bool small = n <= kThreads && ncq <= 4;
+    const bool small = n <= TC * kThreads && ncq <= 4;
     if (small) {
-        const int i = (int)threadIdx.x, ic = min(i, n - 1);
-        const float a = poll_sum(base, (unsigned)ic, P, stride, tag, net.spin_limit, ok);
-        const float xi = (i < n) ? act_fast(a) : 0.0f;
-        tr.xi = xi;
+        const int i = (int)threadIdx.x;
+        if constexpr (TC == 1) {
+            const float a = poll_sum(base, (unsigned)min(i, n - 1), P, stride, tag, net.spin_limit, ok);
+            tr.xi[0] = (i < n) ? act_fast(a) : 0.0f;
+        } else {
+            static_assert(TC == 2, "one or two columns per thread");
+            const unsigned c0 = (unsigned)min(i, n - 1), c1 = (unsigned)min(i + kThreads, n - 1);
+            float a0, a1;
+            if (n <= kThreads) {   // (a narrow layer under a kernel compiled for two columns: the second is not there)
+                a0 = poll_sum(base, c0, P, stride, tag, net.spin_limit, ok);
+                a1 = 0.0f;
+            } else if (P <= 4) {
+                poll_sum_pair<4>(base, c0, c1, P, stride, tag, net.spin_limit, ok, a0, a1);
+            } else {   // (more words per column than registers for both columns at once: one after the other)
+                a0 = poll_sum(base, c0, P, stride, tag, net.spin_limit, ok);
+                a1 = poll_sum(base, c1, P, stride, tag, net.spin_limit, ok);
+            }
+            tr.xi[0] = (i < n) ? act_fast(a0) : 0.0f;
+            tr.xi[1] = (i + kThreads < n) ? act_fast(a1) : 0.0f;
+        }
         DBSN_PROF_SUB(ps, ph, 2);
 #pragma unroll
         for (int jq = 0; jq < 4; ++jq) {
             if (jq < ncq) {
-                float v = quad_sum4(tr.w[4 * jq] * xi, tr.w[4 * jq + 1] * xi, tr.w[4 * jq + 2] * xi, tr.w[4 * jq + 3] * xi);
+                float p4[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    p4[e] = tr.w[0][4 * jq + e] * tr.xi[0];
+#pragma unroll
+                    for (int c = 1; c < TC; ++c) p4[e] = fmaf(tr.w[c][4 * jq + e], tr.xi[c], p4[e]);
+                }
+                float v = quad_sum4(p4[0], p4[1], p4[2], p4[3]);
                 v = rows_sum(v);   // lanes 0 .. 3 hold the wavefront's sums of classes 4 jq .. 4 jq + 3
                 if (lane < 4) part[(4 * jq + lane) * kWaves + wave] = v;
             }
@@ -835,21 +893,24 @@ __device__ __forceinline__ bool p_top(const PNet& net, int g, int label, float e
     }
     // deltas of layer L-1 (and, with many columns per thread, the update of the private W_L)
     if (small) {
-        const int i = (int)threadIdx.x;
-        float gs = 0.0f;
 #pragma unroll
-        for (int jq = 0; jq < 4; ++jq) {
-            if (jq < ncq) {
-                const float4 d4 = *reinterpret_cast<const float4*>(dL + 4 * jq);
-                gs = fmaf(tr.w[4 * jq + 0], d4.x, gs);
-                gs = fmaf(tr.w[4 * jq + 1], d4.y, gs);
-                gs = fmaf(tr.w[4 * jq + 2], d4.z, gs);
-                gs = fmaf(tr.w[4 * jq + 3], d4.w, gs);
+        for (int c = 0; c < TC; ++c) {
+            const int i = (int)threadIdx.x + c * kThreads;
+            float gs = 0.0f;
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) {
+                if (jq < ncq) {
+                    const float4 d4 = *reinterpret_cast<const float4*>(dL + 4 * jq);
+                    gs = fmaf(tr.w[c][4 * jq + 0], d4.x, gs);
+                    gs = fmaf(tr.w[c][4 * jq + 1], d4.y, gs);
+                    gs = fmaf(tr.w[c][4 * jq + 2], d4.z, gs);
+                    gs = fmaf(tr.w[c][4 * jq + 3], d4.w, gs);
+                }
             }
-        }
-        if (i < n) {
-            dtop[i] = gs * dact_from_y(tr.xi);
-            if (last && g == 0) net.lay[L - 1].x[i] = tr.xi;   // x_{L-1} for the host
+            if (i < n) {
+                dtop[i] = gs * dact_from_y(tr.xi[c]);
+                if (last && g == 0) net.lay[L - 1].x[i] = tr.xi[c];   // x_{L-1} for the host
+            }
         }
     } else {
         for (int i = threadIdx.x; i < n; i += kThreads) {
@@ -942,14 +1003,20 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     float x0pre = (has1 && n > 0) ? samples[c01 + threadIdx.x] : 0.0f;
     int labpre = (labels && n > 0) ? labels[0] : label_val;
 
-    // this thread's column of the output layer, when it lives in registers (see TopRegs)
-    TopRegs tr;
-    const bool top_small = LyL.n_in <= kThreads && LyL.n_out <= 16;
+    // this thread's columns of the output layer, when they live in registers (see TopRegs): two per
+    // thread in the kernels for deep narrow nets and for any net, one in those of the paper's nets of
+    // up to five hidden layers, whose last hidden layer has 500 neurons
+    constexpr int TC = (LAYOUT == 0 || LAYOUT == 3) ? 2 : 1;
+    TopRegs<TC> tr;
+    const bool top_small = LyL.n_in <= TC * kThreads && LyL.n_out <= 16;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        tr.w[c] = (top_small && (int)threadIdx.x < LyL.n_in && c < LyL.n_out) ? lds[PLds::WL + c * LyL.n_in + threadIdx.x] : 0.0f;
+    for (int k = 0; k < TC; ++k) {
+        const int i = (int)threadIdx.x + k * kThreads;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+            tr.w[k][c] = (top_small && i < LyL.n_in && c < LyL.n_out) ? lds[PLds::WL + c * LyL.n_in + i] : 0.0f;
+        tr.xi[k] = 0.0f;
     }
-    tr.xi = 0.0f;
     // the table rows of the layers: fetched once here when the layout is fixed at compile time
     const PlanRow rowL = load_plan(lds, L);
     const PlanRow row1 = load_plan(lds, 1), row2 = load_plan(lds, LAYOUT ? min(2, L) : 1),
@@ -1034,10 +1101,14 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     DBSN_PROF_FLUSH();
     if (g == 0) {
-        if (top_small && (int)threadIdx.x < LyL.n_in) {
+        if (top_small) {
 #pragma unroll
-            for (int c = 0; c < 16; ++c)
-                if (c < LyL.n_out) lds[PLds::WL + c * LyL.n_in + threadIdx.x] = tr.w[c];
+            for (int k = 0; k < TC; ++k) {
+                const int i = (int)threadIdx.x + k * kThreads;
+#pragma unroll
+                for (int c = 0; c < 16; ++c)
+                    if (i < LyL.n_in && c < LyL.n_out) lds[PLds::WL + c * LyL.n_in + i] = tr.w[k][c];
+            }
         }
         __syncthreads();
         for (int e = threadIdx.x; e < LyL.n_out * LyL.n_in; e += kThreads) {
