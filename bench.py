@@ -357,6 +357,20 @@ def main():
         out["roofline"]["frac_of_measured_stream_48MB"] = achieved / ceil["48MB"]["GBps"]
         out["roofline"]["frac_of_measured_stream_1GB"] = achieved / ceil["1GB"]["GBps"]
         out["ceilings"] = {"kernel": "k_probe_read + k_probe_update (2 reads : 1 write, 12 B per float and sweep)", **ceil}
+        # the bare hand-over among the 256 workgroups, across the chip and inside a die (dbsn_probe_handover)
+        hbuf = torch.zeros(2 * 256 * 64, dtype=torch.int64, device=dev)
+        gave = torch.zeros(1, dtype=torch.int32, device=dev)
+        hand = {}
+        for label, within in (("across_dies", 0), ("within_die", 1)):
+            lib.check(lib.probe_handover(within, 200, hbuf, gave, stream))
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lib.check(lib.probe_handover(within, 4000, hbuf, gave, stream))
+            e1.record()
+            torch.cuda.synchronize()
+            hand[label] = {"us_per_hand_over": e0.elapsed_time(e1) * 1e3 / 4000, "workgroups_gave_up": int(gave.item())}
+        out["hand_over"] = hand
         if "streaming" in out:
             for row in out["streaming"]:
                 fp = 4 * row["weights"]

@@ -245,6 +245,17 @@ int32_t dbsn_mean_loss(const float* loss_dev, int64_t n, float* mean_dev, void* 
 int32_t dbsn_probe_stream(float* buf_dev, int64_t n_floats, int32_t workgroups, int32_t sweeps,
                           float* sink_dev, void* hip_stream);
 
+/* Measurement aid, not part of the method: the bare hand-over of the persistent training kernel.
+ * 256 workgroups; in each of `rounds` rounds every workgroup publishes 64 tagged words and polls 8
+ * words of 8 others until they carry the round's number.  within_die = 0: partners all over the
+ * chip, device-scope stores; 1: partners on the same die (workgroup g runs on die g % 8),
+ * workgroup-scope stores that stop in the die's L2.  Timed by the caller, time / rounds is the cost
+ * of one hand-over.  buf_dev: 2 * 256 * 64 uint64 of device memory (the call clears it);
+ * *gave_up_dev (int32, device) receives the number of workgroups whose polls gave up (0 when the
+ * assumption about the dies holds).  One cooperative launch on hip_stream. */
+int32_t dbsn_probe_handover(int32_t within_die, int32_t rounds, uint64_t* buf_dev, int32_t* gave_up_dev,
+                            void* hip_stream);
+
 /* Message for the last error on this host thread ("" if none). */
 const char* dbsn_last_error(void);
 

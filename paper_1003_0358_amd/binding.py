@@ -20,7 +20,7 @@ SYMBOLS = [
     "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
     "dbsn_mlp_set_pauses", "dbsn_mlp_get_pauses", "dbsn_mlp_set_variant", "dbsn_mlp_get_variant",
     "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_deform_batch_labels",
-    "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_classify_static", "dbsn_count_errors", "dbsn_mean_loss", "dbsn_probe_stream",
+    "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_classify_static", "dbsn_count_errors", "dbsn_mean_loss", "dbsn_probe_stream", "dbsn_probe_handover",
     "dbsn_last_error",
 ]
 DEFORM_KERNEL_AUTO, DEFORM_KERNEL_GENERAL = 0, 1
@@ -79,6 +79,7 @@ class Lib:
         c.dbsn_count_errors.argtypes = [vp, vp, i64, vp, vp]
         c.dbsn_mean_loss.argtypes = [vp, i64, vp, vp]
         c.dbsn_probe_stream.argtypes = [vp, i64, i32, i32, vp, vp]
+        c.dbsn_probe_handover.argtypes = [i32, i32, vp, vp, vp]
         c.dbsn_bp_steps.argtypes = [vp, vp, vp, i64, f32, vp]
         c.dbsn_bp_step.argtypes = [vp, vp, i32, f32]
         c.dbsn_forward.argtypes = [vp, vp, vp]
@@ -170,6 +171,9 @@ class Lib:
 
     def probe_stream(self, buf, n_floats, workgroups, sweeps, sink, stream=0):
         return self.c.dbsn_probe_stream(_ptr(buf), n_floats, workgroups, sweeps, _ptr(sink), C.c_void_p(stream))
+
+    def probe_handover(self, within_die, rounds, buf, gave_up, stream=0):
+        return self.c.dbsn_probe_handover(int(within_die), rounds, _ptr(buf), _ptr(gave_up), C.c_void_p(stream))
 
     def bp_steps(self, h, samples, labels, n, eta, loss=None):
         return self.c.dbsn_bp_steps(h, _ptr(samples), _ptr(labels), n, eta, _ptr(loss))

@@ -832,6 +832,25 @@ int32_t dbsn_probe_stream(float* buf_dev, int64_t n_floats, int32_t workgroups, 
     return DBSN_OK;
 }
 
+int32_t dbsn_probe_handover(int32_t within_die, int32_t rounds, uint64_t* buf_dev, int32_t* gave_up_dev, void* hip_stream) {
+    if (!buf_dev || !gave_up_dev) return fail(DBSN_E_ARG, "null pointer");
+    if (within_die != 0 && within_die != 1) return fail(DBSN_E_ARG, "within_die must be 0 or 1");
+    if (rounds < 0 || rounds > (1 << 24)) return fail(DBSN_E_ARG, "rounds must be in 0..2^24");
+    if (!aligned(buf_dev, 8) || !aligned(gave_up_dev, 4)) return fail(DBSN_E_SHAPE, "misaligned pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    unsigned long long* buf = reinterpret_cast<unsigned long long*>(buf_dev);
+    unsigned limit = 1u << 16;
+    // the buffer and the counter start at zero (by a kernel: callers may be recording a graph)
+    const long long n4 = (long long)(2 * kHandoverGroups * kHandoverWords * sizeof(uint64_t) / sizeof(float4));
+    hipLaunchKernelGGL(k_zero, dim3(64), dim3(256), 0, st, reinterpret_cast<float4*>(buf_dev), n4);
+    hipLaunchKernelGGL(k_zero_int, dim3(1), dim3(64), 0, st, gave_up_dev, 1);
+    const void* fn = within_die ? reinterpret_cast<const void*>(&k_probe_handover<true>)
+                                : reinterpret_cast<const void*>(&k_probe_handover<false>);
+    void* args[] = {&buf, &rounds, &limit, &gave_up_dev};
+    HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(kHandoverGroups), dim3(64), args, 0, st));
+    return DBSN_OK;
+}
+
 int32_t dbsn_mean_loss(const float* loss_dev, int64_t n, float* mean_dev, void* hip_stream) {
     if (n < 1) return fail(DBSN_E_ARG, "n must be at least 1");
     if (!loss_dev || !mean_dev) return fail(DBSN_E_ARG, "null pointer");

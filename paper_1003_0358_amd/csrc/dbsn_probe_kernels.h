@@ -63,4 +63,41 @@ __global__ __launch_bounds__(kProbeThreads) void k_probe_update(float4* __restri
     }
 }
 
+// The bare hand-over of the persistent training kernel, without its arithmetic: in every round each
+// of the 256 workgroups publishes 64 tagged 64-bit words and then polls 8 words of 8 other
+// workgroups until they carry the round's number.  ACROSS: the partners are spread over the chip,
+// stores and loads of device scope.  WITHIN_DIE: the partners are the workgroups of the same die
+// (workgroup g runs on die g % 8), the stores of workgroup scope, which stop in the die's L2, where
+// the device-scope loads of the pollers find them.  A poll gives up after `limit` rounds of loads
+// and counts itself in *gave_up (so a wrong assumption about the dies ends, it does not hang).
+constexpr int kHandoverGroups = 256, kHandoverWords = 64, kHandoverFan = 8;
+template <bool WITHIN_DIE>
+__global__ __launch_bounds__(64) void k_probe_handover(unsigned long long* buf, int rounds, unsigned limit, int* gave_up) {
+    typedef __attribute__((address_space(1))) unsigned long long gu64;
+    constexpr int ngroups = WITHIN_DIE ? 8 : 1;
+    const int grp = blockIdx.x % ngroups, me = blockIdx.x / ngroups, gsz = kHandoverGroups / ngroups;
+    const int lane = threadIdx.x;
+    bool ok = true;
+    for (int it = 1; it <= rounds && ok; ++it) {
+        unsigned long long* cur = buf + (size_t)(it & 1) * kHandoverGroups * kHandoverWords;
+        const unsigned long long word = ((unsigned long long)(unsigned)it << 32) | (unsigned)lane;
+        if (WITHIN_DIE) __hip_atomic_store((gu64*)(cur + (size_t)blockIdx.x * kHandoverWords + lane), word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else __hip_atomic_store((gu64*)(cur + (size_t)blockIdx.x * kHandoverWords + lane), word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        for (;;) {
+            bool pending = false;
+#pragma unroll
+            for (int k = 0; k < kHandoverFan; ++k) {
+                const int prod = ((me + 1 + k * (gsz / kHandoverFan)) % gsz) * ngroups + grp;
+                const unsigned long long v = __hip_atomic_load((const gu64*)(cur + (size_t)prod * kHandoverWords + lane),
+                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pending |= (int)((unsigned)(v >> 32) - (unsigned)it) < 0;   // (a partner may be a round ahead)
+            }
+            if (!__any(pending)) break;
+            if (++spins > limit) { ok = false; break; }
+        }
+    }
+    if (!ok && lane == 0) atomicAdd(gave_up, 1);
+}
+
 }  // namespace dbsn

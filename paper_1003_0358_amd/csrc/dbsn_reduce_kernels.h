@@ -47,4 +47,8 @@ __global__ void k_zero(float4* __restrict__ p, long long n4) {
         p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
+__global__ void k_zero_int(int* __restrict__ p, int n) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
 }  // namespace dbsn

@@ -63,13 +63,19 @@ def test_init_matches_oracle_bit_for_bit(oracle, sizes):
     m.close()
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, "plain-tiles"])
 @pytest.mark.parametrize("sizes", SHAPES)
 def test_single_step(oracle, sizes, mode):
+    """One step against the oracle in the launch-per-phase mode (0), in the persistent kernel as the
+    library configures it (1: tiles in bands per die wherever two hidden layers pair up) and in the
+    persistent kernel with every layer cut the plain way."""
     torch = _torch()
     X, y = _data(3, sizes[0], seed=1)
     y = (y % sizes[-1]).astype(np.int32)
-    m = _mk(sizes, mode, seed=3)
+    m = _mk(sizes, 1 if mode == "plain-tiles" else mode, seed=3)
+    if mode == "plain-tiles":
+        m.set_variant(banded=False)
+        assert m.get_variant()[2] == 0
     p0 = m.get_params()
     eta = np.float32(1e-3)
     xs = torch.from_numpy(X).cuda()

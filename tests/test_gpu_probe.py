@@ -23,3 +23,23 @@ def test_probe_stream_reads_everything_and_changes_nothing():
     assert lib.probe_stream(None, 4, 1, 1, sink) == binding.E_ARG
     assert lib.probe_stream(buf, 4, 0, 1, sink) == binding.E_ARG
     assert lib.probe_stream(buf, 4, 1, 0, sink) == binding.OK             # no sweeps: nothing to do
+
+
+def test_probe_handover_ends_and_nobody_gives_up():
+    """The bare hand-over across the chip and inside a die: every poll finds its words (on a device
+    whose workgroup g runs on die g % 8 the workgroup-scope stores reach the same die's pollers)."""
+    import torch
+    from paper_1003_0358_amd import binding
+    lib = binding.load()
+    buf = torch.ones(2 * 256 * 64, dtype=torch.int64, device="cuda")     # dirty on purpose: the call clears it
+    gave = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    for within in (0, 1):
+        lib.check(lib.probe_handover(within, 300, buf, gave))
+        torch.cuda.synchronize()
+        assert int(gave.item()) == 0
+        words = buf.cpu().numpy().view(np.uint64).reshape(2, 256, 64)
+        assert (words[0] >> np.uint64(32) == 300).all() and (words[1] >> np.uint64(32) == 299).all()   # last two rounds
+        assert ((words & np.uint64(0xFFFFFFFF)) == np.arange(64, dtype=np.uint64)).all()
+    assert lib.probe_handover(2, 10, buf, gave) == binding.E_ARG
+    assert lib.probe_handover(0, -1, buf, gave) == binding.E_ARG
+    assert lib.probe_handover(0, 10, None, gave) == binding.E_ARG
