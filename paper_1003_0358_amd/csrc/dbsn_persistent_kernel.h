@@ -408,7 +408,11 @@ __device__ inline bool tile_geom(const PLayer& Ly, int g, TileGeom& t) {
     return true;
 }
 
-// (slots outside [s0, send) belong to other layers and are left alone)
+// KEEP = true (weights stationary: the layers share the registers for the whole launch): slots
+// outside [s0, send) belong to other layers and are left alone.  KEEP = false (streaming: the phase
+// has the registers to itself, s0 = 0): every slot of the groups is assigned, rows past the tile
+// get zeros, and the loads carry no condition that would keep them from being in flight together.
+template <bool KEEP>
 __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const TileGeom& t) {
     const int wave = threadIdx.x >> 6;
     for_layer_groups(t.s0 / kGR, (t.send + kGR - 1) / kGR, [&](auto Gc) {
@@ -417,7 +421,7 @@ __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const TileGeom& 
         for (int q = 0; q < kGR; ++q) {
             const int a = kGR * G + q;
             const int rl = wave + kWaves * (a - t.s0);
-            if (a >= t.s0 && a < t.send)
+            if (!KEEP || (a >= t.s0 && a < t.send))
                 wr[a] = (rl < t.Reff && t.lane_on) ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * t.ld)
                                                    : make_float4(0.f, 0.f, 0.f, 0.f);
         }
@@ -541,7 +545,7 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 0);
     if (!ST) {   // in flight while the inputs are awaited
         TileGeom tg;
-        if (tile_geom(net.lay[l], g, tg)) load_tile(wr, tg);
+        if (tile_geom(net.lay[l], g, tg)) load_tile<false>(wr, tg);
     }
 
     float* xk = lds + PLds::xkeep + l * 256;
@@ -613,7 +617,7 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     const int s0 = uniform(pl[PL_S0]), send = uniform(pl[PL_SEND]);
     DBSN_PROF_SUB(ps, ph, 0);
     TileGeom tg;
-    if (!ST) { tile_geom(net.lay[l], g, tg); load_tile(wr, tg); }   // (flags & 1: the tile exists)
+    if (!ST) { tile_geom(net.lay[l], g, tg); load_tile<false>(wr, tg); }   // (flags & 1: the tile exists)
     // the tile's inputs, kept since the forward sweep (read before this phase's first barrier: the
     // next step's forward sweep overwrites them after it)
     const float* xk = lds + PLds::xkeep + l * 256;
@@ -991,7 +995,7 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     if (ST) {
         for (int l = 1; l < L; ++l) {
             TileGeom tg;
-            if (tile_geom(net.lay[l], g, tg)) load_tile(wr, tg);
+            if (tile_geom(net.lay[l], g, tg)) load_tile<true>(wr, tg);
         }
     }
     __syncthreads();
