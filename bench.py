@@ -269,6 +269,10 @@ def main():
             "avg_launch_ms": head["bp_avg_s"] * 1e3,
             "us_per_sample": head["bp_avg_s"] / chunk * 1e6,
         },
+        # the pair the measurement plan asks for: the whole step (deformation of the chunk + training) is
+        # `value`; training alone, from the events around dbsn_bp_steps; the deformation is not put on
+        # a side stream because it is 0.1 % of the step (deform_batch_images_per_s below)
+        "bp_steps_alone_samples_per_s": chunk / head["bp_avg_s"],
         "final_chunk_mean_loss": head["final_loss"],
         "paper_context": "GTX 280 (2010): up to 5e9 weight updates/s, i.e. about 413 samples/s on this net "
                          "(derived from the paper's figure; different hardware, not a target)",
