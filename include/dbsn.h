@@ -128,9 +128,10 @@ int32_t dbsn_mlp_get_pauses(dbsn_mlp* mlp, int32_t* fwd_host, int32_t* bwd_host)
  * networks that fit one of the compiled register layouts use it; 0: registers packed at run time.
  * banded = 1: where two hidden layers follow each other, the neurons between them are split into
  * eight bands, one per die of the chip, so that the partial sums those two layers exchange never
- * leave a die (used when the device places workgroup g on die g % 8, which dbsn_mlp_init probes,
- * and the banded tiles fit the registers); 0: every layer cut the same way, all hand-overs across
- * the chip.  stationary and fixed_layout do not change the order of any sum: those variants agree
+ * leave a die (used when the device is eight dies of 32 compute units, which dbsn_mlp_init probes,
+ * and the banded tiles fit the registers; the workgroups of a launch number themselves by the die
+ * they find themselves on, so nothing is assumed about where the hardware puts them); 0: every
+ * layer cut the same way, all hand-overs across the chip.  stationary and fixed_layout do not change the order of any sum: those variants agree
  * to rounding (they are separately compiled kernels); banded changes how partial sums are grouped,
  * like DBSN_MODE_LAUNCHES does.  Synchronises the stream.
  * dbsn_mlp_get_variant reports what is in force: stationary (0/1), the register layout (0: packed

@@ -86,7 +86,8 @@ struct dbsn_mlp {
     bool persistent_ready = false;   // LDS size and residency of the selected persistent kernel checked
     int layout = 0;            // register layout of the persistent kernel (0: packed at run time)
     int tiles = 0;             // which of plan.tiles the persistent kernel uses (1: the banded cut)
-    bool dies_ok = false;      // workgroup g of a launch runs on die g % 8 on this device (probed)
+    bool dies_ok = false;      // the device is eight dies of 32 compute units (probed)
+    unsigned die_launches = 0; // launches so far that took tickets from the per-die counters
     int* err = nullptr;
 };
 
@@ -182,7 +183,9 @@ int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, i
     PNet net = m->pnet;
     long long nn = n;
     unsigned base = (unsigned)m->epoch;
-    void* args[] = {&net, &samples, &labels, &label_val, &nn, &eta, &loss, &base};
+    unsigned seq = m->die_launches;
+    if (net.any_local) ++m->die_launches;
+    void* args[] = {&net, &samples, &labels, &label_val, &nn, &eta, &loss, &base, &seq};
     HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, m->stream));
     m->epoch += (uint64_t)n;
     return DBSN_OK;
@@ -223,11 +226,12 @@ void configure_persistent(dbsn_mlp* m, bool stationary, bool fixed_layout, bool 
     m->persistent_ready = false;
 }
 
-// Does workgroup g of a launch of kPGroups workgroups run on die g % 8?  Asked once per device: a
-// small kernel notes the die every workgroup finds itself on (in the static scratch array).
+// Is the device eight dies that take 32 workgroups of the training kernel each?  Asked once per
+// device: a small kernel of the same launch shape notes the die every workgroup finds itself on
+// (in the static scratch array).
 std::mutex g_dies_mu;
 int g_dies_state[kMaxDevices] = {};   // 0: not probed, 1: yes, 2: no
-bool dies_follow_workgroup_index(int device, hipStream_t stream) {
+bool device_has_eight_dies(int device, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(g_dies_mu);
     if (device < 0 || device >= kMaxDevices) return false;
     if (g_dies_state[device] == 0) {
@@ -246,8 +250,13 @@ bool dies_follow_workgroup_index(int device, hipStream_t stream) {
                 hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, stream) == hipSuccess &&
                 hipStreamSynchronize(stream) == hipSuccess &&
                 hipMemcpy(host, ids, sizeof host, hipMemcpyDeviceToHost) == hipSuccess) {
+                int per_die[kXcds] = {};
                 bool ok = true;
-                for (int g = 0; g < kPGroups; ++g) ok = ok && host[g] == g % kXcds;
+                for (int g = 0; g < kPGroups; ++g) {
+                    ok = ok && host[g] >= 0 && host[g] < kXcds;
+                    if (ok) ++per_die[host[g]];
+                }
+                for (int k = 0; k < kXcds; ++k) ok = ok && per_die[k] == kPGroups / kXcds;
                 if (ok) g_dies_state[device] = 1;
             }
             (void)hipGetLastError();
@@ -342,11 +351,11 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
         pn.pace[0][l] = 17;
         pn.pace[1][l] = 0;
     }
-    m->dies_ok = plan.banded && prop.multiProcessorCount == kPGroups && dies_follow_workgroup_index(m->device, m->stream);
+    m->dies_ok = plan.banded && prop.multiProcessorCount == kPGroups && device_has_eight_dies(m->device, m->stream);
     configure_persistent(m, true, true, true);
     // (a hand-over inside a die is there sooner: the layers that read one look earlier)
     for (int l = 2; l < net.L; ++l)
-        if (pn.lay[l].bwd_local) pn.pace[0][l] = 10;
+        if (pn.lay[l].bwd_local) pn.pace[0][l] = 5;
     // kernels that need more LDS than the default limit say so once, here
     {
         int32_t rc = DBSN_OK;
@@ -462,7 +471,7 @@ int32_t dbsn_mlp_status(dbsn_mlp* m) {
         m->epoch += (uint64_t)1 << 20;
         m->dies_ok = false;   // fall back to the plain cut from here on
         configure_persistent(m, m->pnet.stationary != 0, m->layout != 0, false);
-        return fail(DBSN_E_HIP, "workgroups were not placed on the dies as probed; the banded tiles are switched off, "
+        return fail(DBSN_E_HIP, "the workgroups of a launch did not come 32 to a die; the banded tiles are switched off, "
                                 "the weights are undefined");
     }
     if (err) {

@@ -118,7 +118,7 @@ struct PNet {
     int L;
     unsigned spin_limit;
     int stationary;   // 1: every layer has its own register slots for the whole launch
-    int any_local;    // 1: some hand-over stays inside a die, which relies on workgroup g running on die g % 8
+    int any_local;    // 1: some hand-over stays inside a die: workgroups number themselves by the die they run on
     // pause of each (direction, layer) before its first look at the partials, in units of 64 clocks
     // ([0]: forward, index L the output layer; [1]: backward)
     unsigned char pace[2][kMaxLayers + 1];
@@ -954,10 +954,33 @@ __global__ __launch_bounds__(kThreads) void k_die_probe(int* ids) {
 template <bool ST, int LAYOUT>
 __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float* samples, const int* labels,
                                                            int label_val, long long n, float eta, float* loss_out,
-                                                           unsigned tag_base) {
+                                                           unsigned tag_base, unsigned launch_seq) {
     extern __shared__ float lds[];
     DBSN_PROF_DECL;
-    const int g = blockIdx.x, L = net.L;
+    const int L = net.L;
+    // Which tiles this workgroup owns follows from its number g.  With hand-overs inside a die, g
+    // must say where the workgroup really runs: die g % 8.  The hardware deals workgroups to the
+    // dies in turn only while nothing else occupies the chip (a kernel on another stream moves
+    // them), so the workgroup asks: it reads the die it is on and takes the next free rank among the
+    // workgroups of that die (one counter per die in the network's flag block, 32 tickets per die
+    // and launch since every compute unit holds exactly one workgroup of this kernel), g = die + 8
+    // rank.  Which workgroup gets which number varies from launch to launch; what number g
+    // computes does not, so results do not depend on it.
+    if (threadIdx.x == 0) {
+        int v = blockIdx.x;
+        if (net.any_local) {
+            const int die = die_id();
+            unsigned rank = kPGroups;
+            if (die < kXcds)
+                rank = __hip_atomic_fetch_add(reinterpret_cast<unsigned*>(net.err) + kDieTicketsAt + die, 1u, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT) - (unsigned)(kPGroups / kXcds) * launch_seq;
+            if (rank < (unsigned)(kPGroups / kXcds)) v = die + kXcds * (int)rank;
+            else __hip_atomic_store(net.err, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not eight dies of 32: the waits will give up
+        }
+        *reinterpret_cast<int*>(lds + PLds::fail + 1) = v;
+    }
+    __syncthreads();
+    const int g = uniform(*reinterpret_cast<const int*>(lds + PLds::fail + 1));
     const PLayer& LyL = net.lay[L];
     const int n0 = net.lay[1].n_in;
     // private copy of the output layer, classes padded to a multiple of four with zero rows
@@ -972,10 +995,6 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
     for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
     if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
-    // hand-overs inside a die assume that workgroup g runs on die g % 8: say so if it does not (the
-    // waits of the workgroups concerned then give up by themselves)
-    if (net.any_local && threadIdx.x == 0 && die_id() != g % kXcds)
-        __hip_atomic_store(net.err, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1); e += kThreads)
         reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[e / (kMaxLayers + 1)][e % (kMaxLayers + 1)];
     if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);

@@ -17,6 +17,7 @@ constexpr int kMaxRowsPerGroup = 256;             // rows a workgroup of the lau
 constexpr int kMaxClasses = DBSN_MAX_CLASSES;
 constexpr int kArenaGroups = 512;                 // partial-sum rows the arena is sized for (>= workgroups launched)
 constexpr int kZerosAt = 16;                      // four ints of the flag block that stay zero (a float4 of zeros)
+constexpr int kDieTicketsAt = 32;                 // eight ints of the flag block: workgroups of the persistent kernel per die so far
 constexpr int kBatchSamples = 16384;              // samples per pass of the batched classification (sizes its buffers)
 
 // persistent kernel
@@ -55,9 +56,9 @@ constexpr int kLayoutNS[kLayouts][kLayoutMaxDepth] = {{0, 0, 0, 0, 0, 0, 0, 0, 0
 
 // ---- tiles of the persistent kernel ------------------------------------------------------------
 // The weight matrix [n_out][n_in] of a hidden layer is cut into at most kPGroups tiles of at most
-// kMaxTileRows x kMaxTileCols, tile <-> workgroup for the life of the network.  The chip is eight
-// dies (XCDs) with an L2 each, and workgroup g of a launch runs on die g % 8; a hand-over between
-// workgroups of one die costs half of one across dies.  So besides the PLAIN cut (column blocks x
+// kMaxTileRows x kMaxTileCols, tile <-> workgroup number g for the life of the network.  The chip is
+// eight dies (XCDs) with an L2 each, and the training kernel numbers its workgroups so that g runs
+// on die g % 8; a hand-over between workgroups of one die costs half of one across dies.  So besides the PLAIN cut (column blocks x
 // row blocks, tile (cb, rb) on workgroup rb * nCB + cb) two layers that follow each other can be cut
 // in BANDS: the neurons between them (rows of the lower layer = columns of the upper) are split
 // into eight bands of B, band k living on die k on both sides: the lower layer ROW-banded (its tiles

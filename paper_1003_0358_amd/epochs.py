@@ -2,7 +2,8 @@
 "Architectures", "Deforming images ...", "Results"):
 
 * at the beginning of every epoch the whole training set is deformed anew (dbsn_deform_batch with
-  first_index = epoch * n, so every epoch sees different deformations of every image);
+  first_index = epoch * n, so every epoch sees different deformations of every image); chunk by
+  chunk, on a side stream, while the network trains on the chunk before;
 * one on-line back-propagation pass over it (dbsn_bp_steps), with a learning rate that shrinks by
   a constant factor after each epoch, from eta_start down to eta_end;
 * validation on the UN-deformed training set (or a set the caller gives), forward only
@@ -63,36 +64,61 @@ def run_epochs(mlp, train_u8, train_labels, epochs, eta_start=1e-3, eta_end=1e-6
                                     params.shear, params.kernel)
         similar = params.beta_deg
 
-    def deform(a, m, first_index):
+    def deform(a, m, first_index, out, stream=None):
         if beta_by_label:
-            binding.deform_batch(train_u8[a:a + m], seed, first_index, wide, out=xbuf[:m],
+            binding.deform_batch(train_u8[a:a + m], seed, first_index, wide, out=out[:m], stream=stream,
                                  labels=train_labels[a:a + m], beta_similar_deg=similar)
         else:
-            binding.deform_batch(train_u8[a:a + m], seed, first_index, params, out=xbuf[:m])
+            binding.deform_batch(train_u8[a:a + m], seed, first_index, params, out=out[:m], stream=stream)
 
+    dev = train_u8.device
+    main = torch.cuda.current_stream(dev)
+    assert main.cuda_stream == mlp.stream, "run_epochs must run on the stream the network was created on"
     val_x = binding.deform_batch(val_u8, 0, 0, identity_params())
-    xbuf = torch.empty((chunk, 784), dtype=torch.float32, device=train_u8.device)
-    loss = torch.zeros(n, dtype=torch.float32, device=train_u8.device)
+    # two input buffers: while the network trains on one chunk, the next one is deformed on a side
+    # stream (default priority); `ready` says a buffer holds its chunk, `spent` that training is done with it
+    xbuf = [torch.empty((chunk, 784), dtype=torch.float32, device=dev) for _ in range(2)]
+    side = torch.cuda.Stream(dev)
+    ready = [torch.cuda.Event() for _ in range(2)]
+    spent = [torch.cuda.Event() for _ in range(2)]
+    loss = torch.zeros(n, dtype=torch.float32, device=dev)
     history, best, best_params = [], None, None
     if autotune and min(chunk, n) >= 64:
         m0 = min(chunk, n)
-        deform(0, m0, 0)
-        mlp.autotune(xbuf[:m0], train_labels[:m0])
-    for e, eta in enumerate(eta_schedule(epochs, eta_start, eta_end)):
-        for a in range(0, n, chunk):
-            m = min(chunk, n - a)
-            deform(a, m, e * n + a)
-            mlp.bp_steps(xbuf[:m], train_labels[a:a + m], float(eta), loss[a:a + m])
+        deform(0, m0, 0, xbuf[0])
+        mlp.autotune(xbuf[0][:m0], train_labels[:m0])
+    etas = eta_schedule(epochs, eta_start, eta_end)
+    work = [(e, a, min(chunk, n - a)) for e in range(len(etas)) for a in range(0, n, chunk)]
+
+    def start_deform(k):
+        e, a, m = work[k]
+        side.wait_event(spent[k % 2])       # (an event never recorded yet holds nobody up)
+        deform(a, m, e * n + a, xbuf[k % 2], stream=side.cuda_stream)
+        ready[k % 2].record(side)
+
+    side.wait_stream(main)                  # the buffers exist and the tuning run is over
+    if work:
+        start_deform(0)
+    for k, (e, a, m) in enumerate(work):
+        if k + 1 < len(work):
+            start_deform(k + 1)
+        main.wait_event(ready[k % 2])
+        mlp.bp_steps(xbuf[k % 2][:m], train_labels[a:a + m], float(etas[e]), loss[a:a + m])
+        spent[k % 2].record(main)
+        if a + m < n:
+            continue
+        # the epoch is complete: validate on the un-deformed set
         mlp.status()
         pred = mlp.classify(val_x)
         errors = binding.count_errors(pred, val_labels)
-        rec = {"epoch": e, "eta": float(eta), "train_loss": binding.mean_loss(loss), "val_errors": errors,
+        rec = {"epoch": e, "eta": float(etas[e]), "train_loss": binding.mean_loss(loss), "val_errors": errors,
                "val_n": int(val_labels.numel())}
         history.append(rec)
         if log:
             log(rec)
         if keep_best and (best is None or errors < best):
             best, best_params = errors, mlp.get_params()
+    main.wait_stream(side)
     if keep_best and best_params is not None and history[-1]["val_errors"] != best:
         mlp.set_params(best_params)
     return history

@@ -458,3 +458,36 @@ def test_kernel_variants_agree(sizes):
     for (p, l), d in zip(out[4:], diffs[4:]):
         assert d <= 2e-6, diffs
         assert np.abs(l - out[0][1]).max() <= 1e-5
+
+
+def test_training_beside_a_kernel_on_another_stream():
+    """While another kernel occupies part of the chip, the hardware places the training kernel's
+    workgroups differently; the kernel numbers them by the die they really run on, so the
+    hand-overs inside a die still find their readers.  Calls launched while a big deformation runs
+    on a side stream must give the same floats as the same calls on a quiet chip."""
+    torch = _torch()
+    from paper_1003_0358_amd import binding
+    sizes = [784, 1500, 1000, 500, 10]
+    X, y = _data(64, seed=13)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    quiet = _mk(sizes, 1, seed=4)
+    assert quiet.get_variant()[2] >= 1
+    for a in range(0, 64, 8):
+        quiet.bp_steps(xs[a:a + 8], ys[a:a + 8], 1e-3)
+    quiet.status()
+    want = quiet.get_params()
+    quiet.close()
+
+    img, _ = datagen.stroke_images(60000, seed=3)
+    src = torch.from_numpy(img).cuda()
+    out = torch.empty((60000, 784), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    busy = _mk(sizes, 1, seed=4)
+    torch.cuda.synchronize()
+    for a in range(0, 64, 8):
+        binding.deform_batch(src, 1, a, out=out, stream=side.cuda_stream)     # about 0.4 ms of other work
+        busy.bp_steps(xs[a:a + 8], ys[a:a + 8], 1e-3)                          # launched while it runs
+    busy.status()
+    torch.cuda.synchronize()
+    assert np.array_equal(busy.get_params(), want)
+    busy.close()
