@@ -5,9 +5,12 @@
 // of 2L dependent mat-vec phases; on this chip a kernel boundary or a grid-wide barrier costs
 // 2-4 us, as much as streaming a whole layer.  So the phases are connected by DATAFLOW instead:
 //
-//  * Every hidden layer l is cut into tiles of R_l rows x C_l <= 256 columns; tile (cb, rb)
-//    belongs to workgroup g = rb * nCB_l + cb for the whole life of the network, forward and
-//    backward, so a weight is only ever touched by one workgroup.
+//  * Every hidden layer l is cut into tiles of R_l rows x C_l <= 256 columns (dbsn_plan.h); a tile
+//    belongs to one workgroup number g for the whole life of the network, forward and backward,
+//    so a weight is only ever touched by one workgroup.  Where two hidden layers follow each
+//    other the cut goes in bands per die of the chip, so that what those two layers hand to each
+//    other never leaves a die's L2 (stores of workgroup scope there, which cost half); the
+//    workgroups take their numbers g by the die they find themselves on.
 //  * What crosses workgroups is small: forward, a tile publishes its R partial dot products
 //    yp_l[cb][rows]; backward, its C partial sums of W^T delta.  Each value travels as ONE 64-bit
 //    word {step tag, float} written with a device-scope atomic store, and a consumer polls the
@@ -21,8 +24,8 @@
 //    and applies the same update to its private copy (same code, same inputs, same bits), so the
 //    deltas of the last hidden layer are available everywhere without communication.
 //  * Weights live in REGISTERS.  A wavefront owns rows wave, wave+8, ... of a tile, one 128-bit
-//    register quadruple per row and lane (a lane holds four consecutive columns), in groups of
-//    kGR rows.  The 256 workgroups x 8 wavefronts x kSlots quadruples hold 58 MB: when all tiles
+//    register quadruple ("slot") per row and lane (a lane holds four consecutive columns),
+//    processed in groups of kGR slots.  The 256 workgroups x 8 wavefronts x kSlots quadruples hold 58 MB: when all tiles
 //    of a workgroup fit (they do for every net of the paper, 48 MB at most) the weights are
 //    loaded once per launch, updated in place for n steps and written back at the end
 //    ("stationary"); the memory system then carries only the small tagged words, and a step
@@ -134,7 +137,6 @@ enum : int {
     PL_FPAR,        // forward source: words between the two parity buffers
     PL_FDPAR,       // forward destination: words between the two parity buffers
     PL_GP,          // backward: partials per row
-    PL_NW,          // backward: words of this tile's chunk = gP * Reff
     PL_BPAR,        // backward source: words between the parity buffers
     PL_BDPAR,       // backward destination (gp of the layer below): words between the parity buffers
     PL_FLOCAL,      // forward: 1 when every reader of the words published here runs on this die
@@ -510,7 +512,6 @@ __device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
     }
     if (l < L - 1) {
         pl[PL_GP] = Ly.gP;
-        pl[PL_NW] = Ly.gP * at.Reff;
         pl[PL_BPAR] = Ly.shape.nRB * Ly.shape.R * Ly.gP;
         put_ptr(PL_BSRC, Ly.gp + (size_t)at.rb * Ly.gP * Ly.shape.R);
     }
