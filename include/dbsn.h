@@ -87,7 +87,9 @@ size_t dbsn_mlp_arena_bytes(const int32_t* sizes_host, int32_t n_sizes);
  * dbsn_mlp_arena_bytes() long, owned by the caller and kept alive until dbsn_mlp_free) and fill
  * it (section "Architectures"): every weight and bias uniform in [-0.05, 0.05), drawn from the
  * library's counter generator so that the result depends on `seed` alone.  The bias is the weight
- * of a constant-1 input, as in the appendix's kernels.  *out receives the handle. */
+ * of a constant-1 input, as in the appendix's kernels.  *out receives the handle.  The first call
+ * on a device also runs a short probe kernel and waits for it (is the chip eight dies of 32 compute
+ * units, see dbsn_mlp_set_variant); later calls only enqueue work on hip_stream. */
 int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes_host, int32_t n_sizes, uint64_t seed,
                       void* arena_dev, size_t arena_bytes, void* hip_stream);
 
