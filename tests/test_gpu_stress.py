@@ -48,3 +48,33 @@ def test_ten_thousand_steps(oracle):
     assert d_oracle <= 1e-5, d_oracle
     assert d_loss <= 1e-4, d_loss
     assert np.abs(res[0][0] - p0).max() > 1e-2          # the weights did move
+
+
+def test_five_thousand_steps_on_the_full_size_net_in_both_cuts():
+    """The 12 M-weight net, whose banded tiles use every register slot: 5,000 steps in five launches,
+    twice with the banded cut (bit-identical: a hand-over inside a die that came late or stale would
+    show) and once with the plain cut (same step, partial sums grouped differently)."""
+    import torch
+    from paper_1003_0358_amd import binding
+    sizes = [784, 2500, 2000, 1500, 1000, 500, 10]
+    n = 5000
+    img, lab = datagen.stroke_images(n, seed=78)
+    xs, ys = torch.from_numpy(pixels_to_inputs(img)).cuda(), torch.from_numpy(lab).cuda()
+    res = []
+    for banded in (True, True, False):
+        m = binding.Mlp(sizes, seed=9)
+        m.set_variant(banded=banded)
+        assert (m.get_variant()[2] > 0) == banded
+        p0 = m.get_params()
+        loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+        for a in range(0, n, 1000):
+            m.bp_steps(xs[a:a + 1000], ys[a:a + 1000], 1e-3, loss[a:a + 1000])
+        m.status()
+        res.append((m.get_params(), loss.cpu().numpy()))
+        m.close()
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+    d = float(np.abs(res[0][0] - res[2][0]).max())
+    print("5000 steps on the full-size net: banded vs plain cut %.3g" % d)
+    assert d <= 1e-5, d
+    assert np.abs(res[0][1] - res[2][1]).max() <= 1e-4
+    assert np.abs(res[0][0] - p0).max() > 1e-3
