@@ -128,6 +128,10 @@ DBSN_HD inline void row_block_at(const TileShape& s, int n_out, int r, int& rb, 
 }
 
 inline int round_up4(int v) { return (v + 3) / 4 * 4; }
+// Rows of a tile are dealt to the kWaves wavefronts of its workgroup, so a tile costs as much as the
+// next multiple of kWaves rows would: take that many, and the layer has fewer row blocks, hence
+// fewer partial sums for the layer below to gather.
+inline int whole_slots(int rows) { return (rows + kWaves - 1) / kWaves * kWaves; }
 
 // PLAIN cut: as few column blocks as the 256-column limit allows, as many row blocks as fill the workgroups.
 inline TileShape plain_shape(int n_in, int n_out) {
@@ -137,7 +141,7 @@ inline TileShape plain_shape(int n_in, int n_out) {
     s.C = round_up4((n_in + s.nCBq - 1) / s.nCBq);
     s.nCBq = (n_in + s.C - 1) / s.C;
     const int rb_max = kPGroups / s.nCBq;
-    s.R = (n_out + rb_max - 1) / rb_max;
+    s.R = whole_slots((n_out + rb_max - 1) / rb_max);
     s.nRBq = (n_out + s.R - 1) / s.R;
     s.nCB = s.nCBq; s.nRB = s.nRBq;
     return s;
@@ -161,7 +165,7 @@ inline TileShape rowband_shape(int n_in, int n_out) {
     s.nCBq = (n_in + s.C - 1) / s.C;
     const int per_die = kPGroups / kXcds;
     const int rb_max = per_die / s.nCBq > 0 ? per_die / s.nCBq : 1;
-    s.R = (s.B + rb_max - 1) / rb_max;
+    s.R = whole_slots((s.B + rb_max - 1) / rb_max);
     s.nRBq = (s.B + s.R - 1) / s.R;
     s.nCB = s.nCBq;
     s.nRB = bands_blocks(n_out, s.B, s.R);
@@ -176,7 +180,7 @@ inline TileShape colband_shape(int n_in, int n_out) {
     s.nCBq = (s.B + s.C - 1) / s.C;
     const int per_die = kPGroups / kXcds;
     const int rb_max = per_die / s.nCBq > 0 ? per_die / s.nCBq : 1;
-    s.R = (n_out + rb_max - 1) / rb_max;
+    s.R = whole_slots((n_out + rb_max - 1) / rb_max);
     s.nRBq = (n_out + s.R - 1) / s.R;
     s.nRB = s.nRBq;
     s.nCB = bands_blocks(n_in, s.B, s.C);

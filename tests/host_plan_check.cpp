@@ -105,7 +105,7 @@ static int check(const std::vector<int32_t>& sizes) {
             CHECK(tiles == s.nCB * s.nRB && tiles <= kPGroups);
             for (int c = 0, at = 0; c < s.nCB; ++c) { CHECK(cb_c0[c] == at); at += cb_ce[c]; if (c == s.nCB - 1) CHECK(at == nin); }
             for (int r = 0, at = 0; r < s.nRB; ++r) { CHECK(rb_r0[r] == at); at += rb_re[r]; if (r == s.nRB - 1) CHECK(at == nout); }
-            CHECK(t.ns[l] * kWaves >= s.R && (t.ns[l] - 1) * kWaves < s.R);
+            CHECK(t.ns[l] * kWaves == s.R);   // tiles take whole slots
             if (s.R > kMaxTileRows || s.C > kMaxTileCols || t.ns[l] > kSlots) fits = false;
             slots += t.ns[l];
             CHECK(t.yp_words[l] == 2 * (size_t)s.nCB * nout);
