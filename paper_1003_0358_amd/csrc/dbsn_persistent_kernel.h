@@ -982,6 +982,22 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     __syncthreads();
     const int g = uniform(*reinterpret_cast<const int*>(lds + PLds::fail + 1));
+    // A workgroup that owns no tile of any layer leaves at once.  It has nothing to contribute (every
+    // workgroup that owns one evaluates the output layer for itself), and nobody would ever wait
+    // for it: left in, it could fall two steps behind the others (it may start late, when another
+    // kernel still holds its compute unit) and then look for tags that have been overwritten.  An
+    // owner cannot be left behind: every output of the last hidden layer depends on every tile of
+    // every layer, so no workgroup passes the output phase of a step before all owners have
+    // published in it.  (Workgroup 0, which reports losses and the final state, owns the first
+    // tile of every layer.)
+    {
+        bool owns = false;
+        for (int l = 1; l < L; ++l) {
+            TileAt at;
+            owns = owns || tile_at(net.lay[l].shape, net.lay[l].n_in, net.lay[l].n_out, g, at);
+        }
+        if (!owns) return;
+    }
     const PLayer& LyL = net.lay[L];
     const int n0 = net.lay[1].n_in;
     // private copy of the output layer, classes padded to a multiple of four with zero rows

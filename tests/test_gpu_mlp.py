@@ -460,18 +460,21 @@ def test_kernel_variants_agree(sizes):
         assert np.abs(l - out[0][1]).max() <= 1e-5
 
 
-def test_training_beside_a_kernel_on_another_stream():
+@pytest.mark.parametrize("sizes", [[784, 1500, 1000, 500, 10], [784, 64, 10], [784, 300, 10]],
+                         ids=["banded", "32-tiles", "152-tiles"])
+def test_training_beside_a_kernel_on_another_stream(sizes):
     """While another kernel occupies part of the chip, the hardware places the training kernel's
-    workgroups differently; the kernel numbers them by the die they really run on, so the
-    hand-overs inside a die still find their readers.  Calls launched while a big deformation runs
-    on a side stream must give the same floats as the same calls on a quiet chip."""
+    workgroups differently and starts some of them late.  The kernel numbers its workgroups by the
+    die they really run on, so the hand-overs inside a die still find their readers; and workgroups
+    that own no tile (small nets leave most of the 256 without one) leave at once instead of
+    trailing behind steps nobody waits for them in.  Calls launched while a big deformation runs on a
+    side stream must give the same floats as the same calls on a quiet chip."""
     torch = _torch()
     from paper_1003_0358_amd import binding
-    sizes = [784, 1500, 1000, 500, 10]
     X, y = _data(64, seed=13)
     xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     quiet = _mk(sizes, 1, seed=4)
-    assert quiet.get_variant()[2] >= 1
+    assert (quiet.get_variant()[2] >= 1) == (len(sizes) > 3)
     for a in range(0, 64, 8):
         quiet.bp_steps(xs[a:a + 8], ys[a:a + 8], 1e-3)
     quiet.status()
