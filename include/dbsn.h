@@ -251,8 +251,9 @@ int32_t dbsn_probe_stream(float* buf_dev, int64_t n_floats, int32_t workgroups, 
 /* Measurement aid, not part of the method: the bare hand-over of the persistent training kernel.
  * 256 workgroups; in each of `rounds` rounds every workgroup publishes 64 tagged words and polls 8
  * words of 8 others until they carry the round's number.  within_die = 0: partners all over the
- * chip, device-scope stores; 1: partners on the same die (workgroup g runs on die g % 8),
- * workgroup-scope stores that stop in the die's L2.  Timed by the caller, time / rounds is the cost
+ * chip, device-scope stores; 1: partners on the same die, taking workgroup g to run on die g % 8
+ * (true of a launch on an otherwise idle chip, which is how this probe is meant to be run; the
+ * training kernel does not rely on it), workgroup-scope stores that stop in the die's L2.  Timed by the caller, time / rounds is the cost
  * of one hand-over.  buf_dev: 2 * 256 * 64 uint64 of device memory (the call clears it);
  * *gave_up_dev (int32, device) receives the number of workgroups whose polls gave up (0 when the
  * assumption about the dies holds).  One cooperative launch on hip_stream. */
