@@ -355,7 +355,7 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
     configure_persistent(m, true, true, true);
     // (a hand-over inside a die is there sooner: the layers that read one look earlier)
     for (int l = 2; l < net.L; ++l)
-        if (pn.lay[l].bwd_local) pn.pace[0][l] = 5;
+        if (pn.lay[l].bwd_local) pn.pace[0][l] = 2;
     // kernels that need more LDS than the default limit say so once, here
     {
         int32_t rc = DBSN_OK;
