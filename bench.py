@@ -413,6 +413,22 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(sizes, img, lab, eta)
+        if "other_configs" in out:
+            # the oracle on all threads on 200 consecutive samples of the other configs too (a second or two in all)
+            from oracle import Oracle
+            o = Oracle()
+            cores = out["cpu_baseline"]["cores"]
+            o.set_threads(cores)
+            for row in out["other_configs"]:
+                net = CONFIG_NETS[row["config"]]
+                p = o.init_params(net, 0)
+                t0 = time.perf_counter()
+                x = o.deform_batch(img[:200], 0, 0, mode="f32") if row["deformation"] else \
+                    o.deform_batch(img[:200], 0, 0, alpha=0.0, beta_deg=0.0, gamma_pct=0.0, mode="f32")
+                o.bp_steps(net, p, x, lab[:200], np.float32(eta), "f32")
+                row["cpu_oracle_samples_per_s"] = 200 / (time.perf_counter() - t0)
+                row["cpu_oracle_cores"] = cores
+            o.set_threads(1)
 
     print(json.dumps(out))
 
