@@ -183,10 +183,10 @@ int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, i
     PNet net = m->pnet;
     long long nn = n;
     unsigned base = (unsigned)m->epoch;
-    unsigned seq = m->die_launches;
-    if (net.any_local) ++m->die_launches;
+    unsigned seq = m->die_launches;   // launches that took tickets so far: this one's tickets start at 32 * seq per die
     void* args[] = {&net, &samples, &labels, &label_val, &nn, &eta, &loss, &base, &seq};
     HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, m->stream));
+    if (net.any_local) ++m->die_launches;
     m->epoch += (uint64_t)n;
     return DBSN_OK;
 }
