@@ -324,9 +324,17 @@ inline ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
     const int L = n_sizes - 1;
     p.tiles[0] = plan_tiles(sizes, n_sizes, 0);
     p.tiles[1] = p.tiles[0];
+    // more banded pairs first; between equals the cut that fits a compile-time register layout, then
+    // the one whose last pair ends at the last hidden layer (measured a little faster)
+    bool has_layout = false;
     for (int first = 1; first <= 2; ++first) {
         const TilePlan t = plan_tiles(sizes, n_sizes, first);
-        if (t.ok && t.stationary && t.pairs > p.tiles[1].pairs) p.tiles[1] = t;
+        if (!t.ok || !t.stationary || t.pairs == 0) continue;
+        const bool lay = choose_layout(t, L) != 0;
+        if (t.pairs > p.tiles[1].pairs || (t.pairs == p.tiles[1].pairs && lay >= has_layout)) {
+            p.tiles[1] = t;
+            has_layout = lay;
+        }
     }
     p.banded = p.tiles[1].pairs > 0;
     p.persistent_ok = p.tiles[0].ok;
