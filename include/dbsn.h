@@ -198,7 +198,10 @@ int32_t dbsn_deform_batch_labels(const dbsn_deform_params* params_host, const ui
 int32_t dbsn_bp_steps(dbsn_mlp* mlp, const float* samples_dev, const int32_t* labels_dev, int64_t n,
                       float eta, float* loss_dev);
 
-/* One step on one sample with a host-side label: dbsn_bp_steps with n = 1. */
+/* One step on one sample with a host-side label: dbsn_bp_steps with n = 1.  (A call of the
+ * persistent kernel brings the weights into registers at its start and writes them back at its
+ * end, tens of microseconds on the big nets: train through dbsn_bp_steps with as many samples per
+ * call as are at hand, one by one only where a sample depends on the step before.) */
 int32_t dbsn_bp_step(dbsn_mlp* mlp, const float* sample_dev, int32_t label, float eta);
 
 /* Forward propagation of one sample; probs_dev: [classes] float softmax outputs. */
