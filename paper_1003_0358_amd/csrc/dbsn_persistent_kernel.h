@@ -23,7 +23,7 @@
 //  * The 10 x n_{L-1} output layer lives in every workgroup's LDS; each workgroup evaluates it
 //    and applies the same update to its private copy (same code, same inputs, same bits), so the
 //    deltas of the last hidden layer are available everywhere without communication.
-//  * Weights live in REGISTERS.  A wavefront owns rows wave, wave+8, ... of a tile, one 128-bit
+//  * Weights live in REGISTERS.  A wavefront owns ns consecutive rows of a tile, one 128-bit
 //    register quadruple ("slot") per row and lane (a lane holds four consecutive columns),
 //    processed in groups of kGR slots.  The 256 workgroups x 8 wavefronts x kSlots quadruples hold 58 MB: when all tiles
 //    of a workgroup fit (they do for every net of the paper, 48 MB at most) the weights are
@@ -97,16 +97,15 @@ constexpr int kProfLdsFloats = 0;
 #endif
 #define DBSN_PROF_SUB(step, phase, sub) DBSN_PROF(step, (phase) * 8 + (sub))
 
-constexpr int kStageFloats = kWaves * kMaxTileRows;   // per-wavefront partial deltas of a tile's rows
 static_assert(kGR == 2, "the forward reduction pairs the two rows of a register group");
 static_assert(kSlots <= 32, "one lane per row slot, two blocks of 16");
 
 struct PLayer {
     float* W; float* b; float* x; float* d;
     u64* yp;          // [2][nCB][n_out]            forward partial sums of this layer's rows
-    u64* gp;          // [2][nRB][gP][rows of rb]   partial delta of this layer's neurons, one chunk per row block:
-                      //                            chunk rb holds, for p < gP (row blocks of layer l+1), the Reff(rb)
-                      //                            rows of the block side by side; chunks are gP * R words apart
+    u64* gp;          // [2][nRB] chunks            partial delta of this layer's neurons, one chunk per row block: for
+                      //                            every row of the block gP words (one per row block of layer l+1),
+                      //                            arranged by the consumer's wavefronts (gp_word_in_chunk)
     int n_in, n_out, ld;
     TileShape shape;  // how the layer is cut into tiles (dbsn_plan.h)
     int gP;           // number of partial rows in gp = row blocks of layer l+1
@@ -152,12 +151,12 @@ enum : int {
 struct PLds {
     static constexpr int WL = 0;                                  // [kTopWMax]  private copy of W_L, [padded classes][n]
     static constexpr int bL = WL + kTopWMax;                      // [kMaxClasses]
-    static constexpr int xkeep = bL + kMaxClasses;                // [kMaxLayers + 1][256] inputs of each tile
+    static constexpr int xkeep = bL + kMaxClasses;                // [kMaxLayers + 1][256] inputs of each tile (rows 0 and 1:
+                                                                  //   the first layer's, by the parity of the step)
     static constexpr int bias = xkeep + (kMaxLayers + 1) * 256;   // [kMaxLayers + 1][kMaxTileRows] (column block 0)
-    static constexpr int stage = bias + (kMaxLayers + 1) * kMaxTileRows;  // [kWaves][kMaxTileRows]
-    static constexpr int dLp = stage + kStageFloats;              // [2][kMaxClasses] delta_L (padded with zeros), probabilities
-    static constexpr int gred = dLp + 2 * kMaxClasses;            // [kWaves][264]; [class][33] partial logits
-    static constexpr int xtop = gred + kWaves * 264;              // [kTopXMax]
+    static constexpr int dLp = bias + (kMaxLayers + 1) * kMaxTileRows;   // [2][kMaxClasses] delta_L (padded with zeros), probabilities
+    static constexpr int gred = dLp + 2 * kMaxClasses;            // [2][kWaves][264] (by the parity of the layer); [class][8] partial logits
+    static constexpr int xtop = gred + 2 * kWaves * 264;          // [kTopXMax]
     static constexpr int dtop = xtop + kTopXMax;                  // [kTopXMax]
     static constexpr int plan = dtop + kTopXMax;                  // [kMaxLayers + 1][kPlanInts]
     static constexpr int fail = plan + (kMaxLayers + 1) * kPlanInts;   // [1] set when a wait gave up
@@ -205,7 +204,7 @@ __device__ inline bool all_ok(bool ok, int* err, float* lds) {
     if (!ok) *fail = 1;
     lds_barrier();
     const bool bad = *fail != 0;
-    if (bad && threadIdx.x == 0) __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (bad && threadIdx.x == 0) __hip_atomic_fetch_max(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // (keeps a 2)
     return !bad;
 }
 
@@ -322,6 +321,59 @@ __device__ __forceinline__ void poll_sum_pair(const u64* base, unsigned col0, un
     }
 }
 
+// Gathering a wavefront's own share of a chunk of backward partial sums (layout: dbsn_plan.h): lane
+// t reads the words p[64 k], k < K (K uniform), of which its first Pl (0 for a lane with no row)
+// belong to its row; all loads of a batch are in flight together, the batch is read again until the
+// lane's words carry the tag, and the payloads are added in index order.
+template <int N>
+__device__ __forceinline__ float poll_lanes_n(const u64* p, int Pl, int K, unsigned tag, unsigned limit, bool& ok, float s) {
+    u64 v[N];
+    unsigned spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) v[k] = ld_tagged(p + 64 * min(k, K - 1));
+        bool pending = false;
+#pragma unroll
+        for (int k = 0; k < N; ++k) pending |= (k < Pl) && ((unsigned)(v[k] >> 32) != tag);
+        if (!__any(pending && DBSN_WAITING(limit))) break;
+        if (++spins > limit) { ok = false; break; }
+    }
+#pragma unroll
+    for (int k = 0; k < N; ++k) s += (k < Pl) ? __uint_as_float((unsigned)v[k]) : 0.0f;
+    return s;
+}
+// (the last of the K loads may run past the wavefront's share, by less than 64 words: the buffer ends
+// with kGpTailWords spare ones; more than 12 words per lane take batches of 8 one after the other)
+__device__ __forceinline__ float poll_lanes(const u64* p, int Pl, int K, unsigned tag, unsigned limit, bool& ok) {
+    float s = 0.0f;
+    while (K > 12 && ok) {
+        s = poll_lanes_n<8>(p, Pl, 8, tag, limit, ok, s);
+        p += 8 * 64;
+        Pl -= 8;
+        K -= 8;
+    }
+    if (K <= 2) return poll_lanes_n<2>(p, Pl, K, tag, limit, ok, s);
+    if (K <= 4) return poll_lanes_n<4>(p, Pl, K, tag, limit, ok, s);
+    if (K <= 8) return poll_lanes_n<8>(p, Pl, K, tag, limit, ok, s);
+    return poll_lanes_n<12>(p, Pl, K, tag, limit, ok, s);
+}
+// Sum over the lanes t, t + span, t + 2 span, ... of the wavefront (span a power of two up to 32,
+// uniform), left in every one of them: fixed tree, vector ALU only.
+__device__ __forceinline__ float span_sum(float v, int span) {
+    if (span <= 1) v += dpp_mov<kDppXor1>(v);
+    if (span <= 2) v += dpp_mov<kDppXor2>(v);
+    if (span <= 4) v += dpp_mov<kDppRor4>(v);
+    if (span <= 8) v += dpp_mov<kDppRor8>(v);
+    if (span <= 16) {
+        const unsigned a = __float_as_uint(v);
+        const auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+        v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    const unsigned b = __float_as_uint(v);
+    const auto q = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
 // Pacing of the polls.  A batch of loads that comes back without the data costs a full round trip
 // before the next one can be judged, so it pays to look a little later and find the data at the
 // first look.  How much later depends on the layer, the direction and the machine: one pause per
@@ -390,7 +442,7 @@ __device__ __forceinline__ void layer_groups(int s0, int send, F&& f) {
     }
 }
 
-// Register slot a of a wavefront holds tile row wave + 8 * (a - s0) of the layer whose slots start
+// Register slot a of a wavefront holds tile row wave * ns + (a - s0) of the layer whose ns slots start
 // at s0 ("absolute" slot a, the same index in every per-slot register; group G = slots 2 G, 2 G + 1).
 struct TileGeom {
     float* wbase;   // &W[r0][c0 + 4 * lane]
@@ -417,15 +469,19 @@ __device__ inline bool tile_geom(const PLayer& Ly, int g, TileGeom& t) {
 template <bool KEEP>
 __device__ __forceinline__ void load_tile(float4 (&wr)[kSlots], const TileGeom& t) {
     const int wave = threadIdx.x >> 6;
+    // (the wavefront's rows end where the next wavefront's begin, or with the tile: one bound per
+    // wavefront, so that a slot past the layer's last one - the second of an odd layer's last group -
+    // reads as a row past the tile)
+    const int lim = min(t.Reff, (wave + 1) * (t.send - t.s0));
     for_layer_groups(t.s0 / kGR, (t.send + kGR - 1) / kGR, [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
 #pragma unroll
         for (int q = 0; q < kGR; ++q) {
             const int a = kGR * G + q;
-            const int rl = wave + kWaves * (a - t.s0);
+            const int rl = wave * (t.send - t.s0) + (a - t.s0);
             if (!KEEP || (a >= t.s0 && a < t.send))
-                wr[a] = (rl < t.Reff && t.lane_on) ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * t.ld)
-                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+                wr[a] = (rl < lim && t.lane_on) ? *reinterpret_cast<const float4*>(t.wbase + (size_t)rl * t.ld)
+                                                : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     });
 }
@@ -436,7 +492,7 @@ __device__ __forceinline__ void store_tile(const float4 (&wr)[kSlots], const Til
 #pragma unroll
         for (int q = 0; q < kGR; ++q) {
             const int a = kGR * G + q;
-            const int rl = wave + kWaves * (a - t.s0);
+            const int rl = wave * (t.send - t.s0) + (a - t.s0);
             if (a >= t.s0 && a < t.send && rl < t.Reff && t.lane_on)
                 *reinterpret_cast<float4*>(t.wbase + (size_t)rl * t.ld) = wr[a];
         }
@@ -507,19 +563,20 @@ __device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
         pl[PL_FSTRIDE] = Lp.n_out;
         pl[PL_FPAR] = Lp.shape.nCB * Lp.n_out;
         put_ptr(PL_FSRC, Lp.yp + at.c0);
-        pl[PL_BDPAR] = Lp.shape.nRB * Lp.shape.R * Lp.gP;
+        pl[PL_BDPAR] = Lp.shape.nRB * gp_chunk_words(Lp.ns, Lp.gP);
         put_ptr(PL_BDST, Lp.gp);
     }
     if (l < L - 1) {
         pl[PL_GP] = Ly.gP;
-        pl[PL_BPAR] = Ly.shape.nRB * Ly.shape.R * Ly.gP;
-        put_ptr(PL_BSRC, Ly.gp + (size_t)at.rb * Ly.gP * Ly.shape.R);
+        pl[PL_BPAR] = Ly.shape.nRB * gp_chunk_words(Ly.ns, Ly.gP);
+        put_ptr(PL_BSRC, Ly.gp + (size_t)at.rb * gp_chunk_words(Ly.ns, Ly.gP));
     }
 }
 
 // Where column i of this workgroup's tile of layer l publishes its backward partial sum: neuron
-// c = c0 + i of layer l-1 belongs to that layer's row block rb', whose chunk of gp keeps one run of
-// its Reff' rows per row block of layer l.  Worked out once per launch (thread i of the workgroup).
+// c = c0 + i of layer l-1 is row j' of that layer's row block rb', and the word is the one of this
+// tile's row block in row j' of chunk rb' (gp_word_in_chunk).  Worked out once per launch (thread i
+// of the workgroup).
 __device__ inline void make_bdst(const PNet& net, int l, int g, int i, float* lds) {
     int* tab = reinterpret_cast<int*>(lds + PLds::bdst) + l * 256;
     tab[i] = 0;
@@ -529,7 +586,7 @@ __device__ inline void make_bdst(const PNet& net, int l, int g, int i, float* ld
     const PLayer& Lp = net.lay[l - 1];
     int rbp, jp, reffp;
     row_block_at(Lp.shape, Lp.n_out, at.c0 + i, rbp, jp, reffp);
-    tab[i] = rbp * (Lp.gP * Lp.shape.R) + at.rb * reffp + jp;
+    tab[i] = rbp * gp_chunk_words(Lp.ns, Lp.gP) + gp_word_in_chunk(Lp.ns, Lp.gP, jp, at.rb);
 }
 
 // Forward propagation of this workgroup's tile of layer l (appendix "Forward propagation"):
@@ -549,7 +606,9 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
         if (tile_geom(net.lay[l], g, tg)) load_tile<false>(wr, tg);
     }
 
-    float* xk = lds + PLds::xkeep + l * 256;
+    // (the first layer keeps its inputs by the parity of the step: its backward phase has no barrier
+    // between reading them and the next step's forward phase, which writes the other copy)
+    float* xk = lds + PLds::xkeep + (l == 1 ? (int)par : l) * 256;
     if (l == 1) {
         // the caller fetched this thread's input pixel ahead of time
         if (threadIdx.x < 256) xk[threadIdx.x] = ((int)threadIdx.x < Ceff) ? x0pre : 0.0f;
@@ -578,7 +637,7 @@ __device__ __forceinline__ bool p_fwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 3);
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
     // the lane that will publish absolute slot a = lane (lanes 0 .. 31): tile row and bias
-    const int myrow = wave + kWaves * (lane - s0);
+    const int myrow = wave * (send - s0) + (lane - s0);
     const bool pub = lane >= s0 && lane < send && myrow < Reff;
     const float mybias = (pub && (flags & 2)) ? lds[PLds::bias + l * kMaxTileRows + myrow] : 0.0f;
     // per group: the two row sums transposed onto the even and odd lanes and reduced inside each row
@@ -619,51 +678,47 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
     DBSN_PROF_SUB(ps, ph, 0);
     TileGeom tg;
     if (!ST) { tile_geom(net.lay[l], g, tg); load_tile<false>(wr, tg); }   // (flags & 1: the tile exists)
-    // the tile's inputs, kept since the forward sweep (read before this phase's first barrier: the
-    // next step's forward sweep overwrites them after it)
-    const float* xk = lds + PLds::xkeep + l * 256;
+    // the tile's inputs, kept since the forward sweep
+    const float* xk = lds + PLds::xkeep + (l == 1 ? (int)par : l) * 256;
     const float4 x4 = *reinterpret_cast<const float4*>(xk + 4 * lane);
 
     // Deltas of the wavefront's rows, lane a <-> absolute slot a.  For the last hidden layer they
-    // are in LDS already (the output layer was evaluated in this workgroup).  Otherwise the
-    // workgroup gathers its chunk of partials: gP per row, which the producers have multiplied by
-    // f'(x_l) already (see below).  The rows are dealt to the lanes (64 at a time) and the
-    // partials to classes p mod NPC; wavefront w takes rows 64 (w mod NR) ... and class w / NR,
-    // adds its partials in index order and leaves the sum in LDS; then lane a adds the NPC sums of
-    // its row in class order.
+    // are in LDS already (the output layer was evaluated in this workgroup).  Otherwise every
+    // wavefront gathers the partial sums of its own rows, gP per row, which the producers have
+    // multiplied by f'(x_l) already (see below): its share of the tile's chunk is one run of words
+    // that the 64 lanes read side by side, lane t the words of slot (t - s0) mod span and of the
+    // partial sums p = t / span, t / span + 64 / span, ...; a lane adds its words in index order, and
+    // the lanes of a slot are added by a fixed tree, which leaves the row's delta in the lane of its
+    // absolute slot.  No LDS, no barrier: a wavefront goes on as soon as its own rows are there.
+    const int ns = send - s0;
     const int srel = lane - s0;   // slot of this lane within the layer
-    const int myrow = wave + kWaves * srel;
+    const int myrow = wave * ns + srel;
     const bool rowon = srel >= 0 && lane < send && myrow < Reff;
     float dlane = 0.0f;
     if (l == net.L - 1) {
         if (rowon) dlane = lds[PLds::dtop + uniform(pl[PL_R0]) + myrow];
     } else {
-        float* sg = lds + PLds::stage;
         const int gP = uniform(pl[PL_GP]);
-        const u64* src = plan_ptr(pl, PL_BSRC) + (size_t)(par * (unsigned)uniform(pl[PL_BPAR]));
-        const int lgNR = Reff > 128 ? 2 : (Reff > 64 ? 1 : 0);   // rounds of 64 rows: 1, 2 or 4
-        const int NPC = kWaves >> lgNR;
-        const int pc = wave >> lgNR;
-        const int j = 64 * (wave & ((1 << lgNR) - 1)) + lane;
-        const int Pw = (gP - pc + NPC - 1) / NPC;               // partials of this wavefront's class
+        const int span = slot_span(ns), nc = 64 / span;   // lanes per partial sum, partial sums per load
+        const int arel = srel & (span - 1), c = lane / span;
+        const int wv = uniform(wave);
+        const bool mine = arel < ns && wv * ns + arel < Reff;
+        const int Pl = (mine && c < gP) ? (gP - c + nc - 1) / nc : 0;
+        const int K = (gP + nc - 1) / nc;
+        const u64* src = plan_ptr(pl, PL_BSRC) + (size_t)(par * (unsigned)uniform(pl[PL_BPAR])) +
+                         (size_t)(unsigned)(wv * gP * span);
         bool ok = true;
         float part = 0.0f;
-        if (Pw > 0 && 64 * (wave & ((1 << lgNR) - 1)) < Reff) {
+        if (wv * ns < Reff) {   // (a wavefront past the tile's last row has nothing to wait for)
             pace_begin(lds, 1, l);
-            part = poll_sum(src + (size_t)((unsigned)pc * (unsigned)Reff), (unsigned)min(j, Reff - 1), Pw,
-                            (unsigned)(NPC * Reff), tag, net.spin_limit, ok);
+            part = poll_lanes(src + (c * span + arel), Pl, K, tag, net.spin_limit, ok);
         }
-        if (j < Reff) sg[pc * kMaxTileRows + j] = part;
         DBSN_PROF_SUB(ps, ph, 1);
-        if (!all_ok(ok, net.err, lds)) return false;
+        // (a wait that gave up: the next agreement of the workgroup, or the end of the launch, reports it)
+        if (!ok) *reinterpret_cast<int*>(lds + PLds::fail) = 1;
+        part = span_sum(part, span);
+        dlane = rowon ? part : 0.0f;
         DBSN_PROF_SUB(ps, ph, 2);
-        if (rowon) {
-            float pv[kWaves];
-#pragma unroll
-            for (int k = 0; k < kWaves; ++k) pv[k] = (k < NPC) ? sg[k * kMaxTileRows + myrow] : 0.0f;
-#pragma unroll
-            for (int k = 0; k < kWaves; ++k) dlane += pv[k];
-        }
     }
     DBSN_PROF_SUB(ps, ph, 3);
     if (l > 1) {
@@ -680,7 +735,9 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
                 gacc.w = fmaf(w4.w, d, gacc.w);
             }
         });
-        float* gred = lds + PLds::gred;
+        // (two copies used in turn by the layers: this phase's only barrier lies between writing and
+        // reading, so the next phase's writes must not land where this one's readers still look)
+        float* gred = lds + PLds::gred + (l & 1) * (kWaves * 264);
         *reinterpret_cast<float4*>(gred + wave * 264 + 4 * lane) = gacc;
         DBSN_PROF_SUB(ps, ph, 4);
         lds_barrier();
@@ -725,9 +782,6 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
         lds[PLds::bias + l * kMaxTileRows + myrow] -= eta * dlane;
         if (last) net.lay[l].d[uniform(pl[PL_R0]) + myrow] = dlane;
     }
-    // with a single hidden layer this phase has no barrier of its own between reading the inputs
-    // and the next step's forward sweep, which overwrites them
-    if (l == 1 && net.L == 2) lds_barrier();
     DBSN_PROF_SUB(ps, ph, 7);
     return true;
 }
@@ -1132,6 +1186,9 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
         }
     }
     __syncthreads();
+    // (a backward wait that gave up in the last steps has met no agreement of the workgroup yet)
+    if (threadIdx.x == 0 && *reinterpret_cast<const int*>(lds + PLds::fail) != 0)
+        __hip_atomic_fetch_max(net.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int l = 1; l < L; ++l) {
         const PLayer& Ly = net.lay[l];
         TileAt at;

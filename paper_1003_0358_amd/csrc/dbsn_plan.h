@@ -187,6 +187,28 @@ inline TileShape colband_shape(int n_in, int n_out) {
     return s;
 }
 
+// ---- backward hand-over of the persistent kernel ------------------------------------------------
+// A wavefront w of a tile's workgroup owns the ns consecutive tile rows [w ns, (w + 1) ns), one per
+// register slot.  The partial deltas that the tiles of layer l + 1 publish for the rows of one tile
+// of layer l (a "chunk": one per row block of layer l, gP = row blocks of layer l + 1 partial sums
+// per row) are laid out so that each wavefront of the consumer finds its own rows' words side by
+// side and reads them with whole-wavefront loads, no word twice and none for another wavefront:
+//     word(w, p, a) = (w gP + p) span + a,    span = the power of two >= ns, a < ns the slot.
+// Lane t of the wavefront then takes slot t % span and the partial sums p = t / span, t / span +
+// 64 / span, ...: its k-th word is word 64 k + t of the wavefront's gP span words.
+DBSN_HD inline int slot_span(int ns) {
+    int a = 1;
+    while (a < ns) a <<= 1;
+    return a;
+}
+DBSN_HD inline int gp_chunk_words(int ns, int gP) { return kWaves * gP * slot_span(ns); }
+// j: row within the tile (row block), p: row block of layer l + 1 that publishes
+DBSN_HD inline int gp_word_in_chunk(int ns, int gP, int j, int p) {
+    const int w = j / ns, a = j - w * ns;
+    return (w * gP + p) * slot_span(ns) + a;
+}
+constexpr int kGpTailWords = 64;   // a wavefront's last load may run up to 63 words past its share: the buffer ends with spare words
+
 constexpr size_t kArenaAlign = 256;
 inline size_t align_up(size_t v, size_t a = kArenaAlign) { return (v + a - 1) / a * a; }
 
@@ -254,7 +276,7 @@ inline TilePlan plan_tiles(const int32_t* sizes, int32_t n_sizes, int first_pair
         t.yp_words[l] = 2 * (size_t)t.shape[l].nCB * sizes[l];
         if (l <= L - 2) {
             t.gP[l] = t.shape[l + 1].nRB;
-            t.gp_words[l] = 2 * (size_t)t.shape[l].nRB * t.shape[l].R * t.gP[l];   // one chunk of gP x R words per row block
+            t.gp_words[l] = 2 * (size_t)t.shape[l].nRB * gp_chunk_words(t.ns[l], t.gP[l]) + kGpTailWords;   // one chunk per row block
         }
     }
     if (L >= 2) {
@@ -320,7 +342,7 @@ inline ArenaPlan plan_arena(const int32_t* sizes, int32_t n_sizes) {
     }
 
     // Persistent kernel: yp_l holds the forward partial sums [2][nCB_l][n_l], gp_l the backward ones
-    // [2][nRB_l][nRB_{l+1}][R_l], as 64-bit {tag, float} words.
+    // [2][nRB_l] chunks (see gp_word_in_chunk), as 64-bit {tag, float} words.
     const int L = n_sizes - 1;
     p.tiles[0] = plan_tiles(sizes, n_sizes, 0);
     p.tiles[1] = p.tiles[0];

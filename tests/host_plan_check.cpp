@@ -109,7 +109,28 @@ static int check(const std::vector<int32_t>& sizes) {
             if (s.R > kMaxTileRows || s.C > kMaxTileCols || t.ns[l] > kSlots) fits = false;
             slots += t.ns[l];
             CHECK(t.yp_words[l] == 2 * (size_t)s.nCB * nout);
-            if (l <= L - 2) CHECK(t.gP[l] == t.shape[l + 1].nRB && t.gp_words[l] == 2 * (size_t)s.nRB * s.R * t.gP[l]);
+            if (l <= L - 2) {
+                const int gP = t.gP[l], ns = t.ns[l], span = slot_span(ns), chunk = gp_chunk_words(ns, gP);
+                CHECK(gP == t.shape[l + 1].nRB && t.gp_words[l] == 2 * (size_t)s.nRB * chunk + kGpTailWords);
+                CHECK(span >= ns && span < 2 * ns + 1 && (span & (span - 1)) == 0 && 64 % span == 0 && chunk == kWaves * gP * span);
+                // backward hand-over: every (row of a tile, publishing row block) has a word of its own in the
+                // chunk, inside the share of the wavefront that owns the row, and a wavefront that reads its
+                // share 64 words at a time stays within the spare words behind the last chunk
+                std::vector<char> used(chunk, 0);
+                for (int j = 0; j < s.R; ++j)
+                    for (int q = 0; q < gP; ++q) {
+                        const int wd = gp_word_in_chunk(ns, gP, j, q);
+                        CHECK(wd >= 0 && wd < chunk && !used[wd]);
+                        used[wd] = 1;
+                        const int w = j / ns;
+                        CHECK(w < kWaves && wd >= w * gP * span && wd < (w + 1) * gP * span);
+                        // the lane and load that read it: lane t = (p % nc) span + a, load k = p / nc
+                        const int nc = 64 / span, a = j - w * ns;
+                        CHECK(wd == w * gP * span + 64 * (q / nc) + (q % nc) * span + a);
+                    }
+                const int nc = 64 / span, K = (gP + nc - 1) / nc;
+                CHECK((kWaves - 1) * gP * span + 64 * K <= chunk + kGpTailWords);
+            }
             // a banded pair: the lower layer row-banded, the upper column-banded with the same bands
             if (t.fwd_local[l]) {
                 CHECK(l + 1 < L && s.kind == TILE_ROWBAND && t.shape[l + 1].kind == TILE_COLBAND && t.bwd_local[l + 1]);

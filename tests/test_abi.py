@@ -33,7 +33,7 @@ def test_arena_bytes(dbsn):
     assert nw == 11972510
     # weights, a few MB of vectors and partial sums, and two activation buffers of 16384 samples x 2500
     # for the batched classification pass
-    assert 4 * nw + 2 * 16384 * 2500 * 4 < nb < 4 * nw + 2 * 16384 * 2500 * 4 + 16 * 2 ** 20
+    assert 4 * nw + 2 * 16384 * 2500 * 4 < nb < 4 * nw + 2 * 16384 * 2500 * 4 + 20 * 2 ** 20
     assert nb % 256 == 0
     assert dbsn.mlp_arena_bytes([784, 10]) > 4 * 7850
     # unsupported shapes
