@@ -73,7 +73,9 @@ typedef struct {
  * different (each fixed) orders, so results agree to rounding, and each mode is bit-reproducible
  * from run to run.  Shapes the persistent kernel does not hold (no hidden layer; an output layer of
  * more than 16384 weights, counting its classes rounded up to a multiple of 4, or of more than 2048
- * inputs; a layer whose 256 tiles would exceed 224 rows each) run in mode 0 whatever is selected. */
+ * inputs; a layer whose 256 tiles would exceed 224 rows each) run in mode 0 whatever is selected,
+ * and so does every shape on a device with fewer than 256 compute units, which cannot hold the
+ * persistent kernel's 256 workgroups at once. */
 #define DBSN_MODE_LAUNCHES   0
 #define DBSN_MODE_PERSISTENT 1
 

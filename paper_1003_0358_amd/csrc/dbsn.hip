@@ -265,7 +265,10 @@ bool device_has_eight_dies(int device, hipStream_t stream) {
     return g_dies_state[device] == 1;
 }
 
-bool use_persistent(const dbsn_mlp* m) { return m->mode == DBSN_MODE_PERSISTENT && m->plan.persistent_ok; }
+// (the persistent kernel needs all its workgroups resident at once, one per compute unit)
+bool use_persistent(const dbsn_mlp* m) {
+    return m->mode == DBSN_MODE_PERSISTENT && m->plan.persistent_ok && m->cus >= kPGroups;
+}
 
 
 int32_t check_mlp(dbsn_mlp* m) { return m ? DBSN_OK : fail(DBSN_E_ARG, "null network handle"); }
