@@ -31,6 +31,8 @@ SHAPES = [
     [784] + [1000] * 9 + [10],
     NET4,                            # the net the throughput target is quoted on
     [784, 3584, 3584, 3584, 1000, 10],   # 128 MB of hidden weights: the streamed net bench.py times
+    [1200, 3600, 2300, 1000, 10],    # 15 column blocks and 25 row blocks: more partial sums per neuron, forward and
+                                     # backward, than one batch of polling loads takes (two batches one after the other)
 ]
 
 
@@ -102,7 +104,7 @@ def test_single_step(oracle, sizes, mode):
 
 
 @pytest.mark.parametrize("sizes", [NET0, [784, 1000, 1000, 1000, 1000, 10], [30, 17, 9, 5],
-                                   [784] + [300] * 9 + [10], [784, 300, 700, 10]])
+                                   [784] + [300] * 9 + [10], [784, 300, 700, 10], [1200, 3600, 2300, 1000, 10]])
 def test_hundred_steps(oracle, sizes):
     torch = _torch()
     X, y = _data(100, sizes[0], seed=0)
