@@ -25,8 +25,8 @@
 //    deltas of the last hidden layer are available everywhere without communication.
 //  * Weights live in REGISTERS.  A wavefront owns ns consecutive rows of a tile, one 128-bit
 //    register quadruple ("slot") per row and lane (a lane holds four consecutive columns),
-//    processed in groups of kGR slots.  The 256 workgroups x 8 wavefronts x kSlots quadruples hold 58 MB: when all tiles
-//    of a workgroup fit (they do for every net of the paper, 48 MB at most) the weights are
+//    processed in groups of kGR slots.  The 256 workgroups x 8 wavefronts x kSlots quadruples hold
+//    58 MB: when all tiles of a workgroup fit (they do for every net of the paper, 48 MB at most) the weights are
 //    loaded once per launch, updated in place for n steps and written back at the end
 //    ("stationary"); the memory system then carries only the small tagged words, and a step
 //    costs its chain of hand-overs, not its bytes.  Otherwise each phase loads its tile into the
@@ -37,6 +37,9 @@
 //    group ranges) is worked out once per launch into a small per-layer table in LDS, the
 //    register groups of a layer are entered by one switch instead of a test per group, and
 //    reductions stay on the vector ALU (DPP inside rows of 16 lanes, lane-row swaps across them).
+//    A forward phase has one workgroup barrier (the tile's inputs go through LDS to all
+//    wavefronts), a backward phase one (the column sums of W^T delta over the eight wavefronts;
+//    every wavefront gathers the deltas of its own rows by itself), the output phase three.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
