@@ -132,7 +132,8 @@ struct PNet {
 // Per-layer table of this workgroup (32-bit words in LDS), filled once per launch.
 constexpr int kPlanInts = 32;
 enum : int {
-    PL_FLAGS = 0,   // bit 0: the workgroup has a tile of this layer; bit 1: column block 0; bit 2: row block 0
+    PL_FLAGS = 0,   // bit 0: the workgroup has a tile of this layer; bit 1: column block 0; bit 2: row block 0;
+                    // bit 3: the layer above it in which the workgroup has its next tile has the same parity
     PL_CEFF, PL_REFF, PL_R0, PL_C0, PL_S0, PL_SEND,   // (slots [S0, SEND) of a wavefront hold the tile's rows)
     PL_PF,          // forward: partials per input column = nCB of the layer below
     PL_FSTRIDE,     // forward: words between two partials of one column = n of the layer below
@@ -549,6 +550,16 @@ __device__ inline void make_plan(const PNet& net, int l, int g, float* lds) {
     TileAt at;
     if (!tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at)) return;
     pl[PL_FLAGS] = 1 | (at.cb == 0 ? 2 : 0) | (at.rb == 0 ? 4 : 0);
+    // (the backward phases of layers 2 .. L-1 use two LDS copies of their column sums by layer parity,
+    // see p_bwd_tile: does the phase this workgroup runs before this one use the same copy?)
+    if (l > 1)
+        for (int k = l + 1; k < L; ++k) {
+            TileAt above;
+            if (tile_at(net.lay[k].shape, net.lay[k].n_in, net.lay[k].n_out, g, above)) {
+                if (((k - l) & 1) == 0) pl[PL_FLAGS] |= 8;
+                break;
+            }
+        }
     pl[PL_CEFF] = at.Ceff;
     pl[PL_REFF] = at.Reff;
     pl[PL_R0] = at.r0;
@@ -739,7 +750,11 @@ __device__ __forceinline__ bool p_bwd_tile(float4 (&wr)[kSlots], const PNet& net
             }
         });
         // (two copies used in turn by the layers: this phase's only barrier lies between writing and
-        // reading, so the next phase's writes must not land where this one's readers still look)
+        // reading, so the next phase's writes must not land where this one's readers may still look;
+        // the phase after that has the next phase's barrier behind it.  A workgroup skips the layers it
+        // has no tile of: where that brings two layers of the same parity together, the second one
+        // waits for the first one's readers here - flag 8, worked out with the table)
+        if (flags & 8) lds_barrier();
         float* gred = lds + PLds::gred + (l & 1) * (kWaves * 264);
         *reinterpret_cast<float4*>(gred + wave * 264 + 4 * lane) = gacc;
         DBSN_PROF_SUB(ps, ph, 4);
