@@ -1072,31 +1072,10 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
     }
     const PLayer& LyL = net.lay[L];
     const int n0 = net.lay[1].n_in;
-    // private copy of the output layer, classes padded to a multiple of four with zero rows
-    {
-        const int nL = LyL.n_in, ncp = ((LyL.n_out + 3) >> 2) << 2;
-        for (int e = threadIdx.x; e < ncp * nL; e += kThreads) {
-            const int j = e / nL, i = e - j * nL;
-            lds[PLds::WL + e] = (j < LyL.n_out) ? LyL.W[(size_t)j * LyL.ld + i] : 0.0f;
-        }
-    }
-    if (threadIdx.x < kMaxClasses) lds[PLds::bL + threadIdx.x] = ((int)threadIdx.x < LyL.n_out) ? LyL.b[threadIdx.x] : 0.0f;
-    for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
-    for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
-    if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
-    for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1); e += kThreads)
-        reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[e / (kMaxLayers + 1)][e % (kMaxLayers + 1)];
-    if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
-    for (int l = 1; l <= kMaxLayers; ++l)
-        if (threadIdx.x < 256) make_bdst(net, l, g, threadIdx.x, lds);
-
-    for (int l = 1; l < L; ++l) {
-        const PLayer& Ly = net.lay[l];
-        TileAt at;
-        if (tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at) && at.cb == 0) {
-            for (int j = threadIdx.x; j < at.Reff; j += kThreads) lds[PLds::bias + l * kMaxTileRows + j] = Ly.b[at.r0 + j];
-        }
-    }
+    // The tiles first: their loads are the long part of starting up (all workgroups together read
+    // every weight once), and what follows until the barrier needs none of them: the tables and the
+    // cleared LDS regions are worked out while they are in flight, the small reads from memory
+    // (output layer, biases) come last.
     float4 wr[kSlots];
 #pragma unroll
     for (int s = 0; s < kSlots; ++s) wr[s] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1104,6 +1083,38 @@ __global__ __launch_bounds__(kThreads) void k_bp_dataflow(PNet net, const float*
         for (int l = 1; l < L; ++l) {
             TileGeom tg;
             if (tile_geom(net.lay[l], g, tg)) load_tile<true>(wr, tg);
+        }
+    }
+    for (int e = threadIdx.x; e < 2 * kMaxClasses; e += kThreads) lds[PLds::dLp + e] = 0.0f;
+    for (int e = threadIdx.x; e < (kMaxLayers + 1) * 256; e += kThreads) lds[PLds::xkeep + e] = 0.0f;
+    if (threadIdx.x == 0) *reinterpret_cast<int*>(lds + PLds::fail) = 0;
+    for (int e = threadIdx.x; e < 2 * (kMaxLayers + 1); e += kThreads)
+        reinterpret_cast<int*>(lds + PLds::pace)[e] = net.pace[e / (kMaxLayers + 1)][e % (kMaxLayers + 1)];
+    if ((int)threadIdx.x >= 1 && (int)threadIdx.x <= L) make_plan(net, threadIdx.x, g, lds);
+    for (int l = 1; l < L; ++l)   // (layers 2 .. L-1 have such a table; the kernel reads no other)
+        if (threadIdx.x < 256) make_bdst(net, l, g, threadIdx.x, lds);
+    // private copy of the output layer, classes padded to a multiple of four with zero rows (four
+    // elements per thread at a time, so that their loads are in flight together)
+    {
+        const int nL = LyL.n_in, ncp = ((LyL.n_out + 3) >> 2) << 2, total = ncp * nL;
+        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * kThreads) {
+            float v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int e = e0 + k * kThreads, j = e / nL, i = e - j * nL;
+                v[k] = (e < total && j < LyL.n_out) ? LyL.W[(size_t)j * LyL.ld + i] : 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (e0 + k * kThreads < total) lds[PLds::WL + e0 + k * kThreads] = v[k];
+        }
+    }
+    if (threadIdx.x < kMaxClasses) lds[PLds::bL + threadIdx.x] = ((int)threadIdx.x < LyL.n_out) ? LyL.b[threadIdx.x] : 0.0f;
+    for (int l = 1; l < L; ++l) {
+        const PLayer& Ly = net.lay[l];
+        TileAt at;
+        if (tile_at(Ly.shape, Ly.n_in, Ly.n_out, g, at) && at.cb == 0) {
+            for (int j = threadIdx.x; j < at.Reff; j += kThreads) lds[PLds::bias + l * kMaxTileRows + j] = Ly.b[at.r0 + j];
         }
     }
     __syncthreads();
