@@ -113,6 +113,20 @@ int32_t dbsn_mlp_get_deltas(dbsn_mlp* mlp, int32_t layer, float* d_host);
 /* Select DBSN_MODE_*.  */
 int32_t dbsn_mlp_set_mode(dbsn_mlp* mlp, int32_t mode);
 
+/* How the persistent kernel is launched.  Its 256 workgroups wait for each other, so all of them
+ * must get onto the chip while none can finish: a COOPERATIVE launch (default) has the driver see to
+ * that against everything else on the device, at about 18 us per call; a PLAIN launch leaves it to
+ * the situation: kernels that end by themselves only delay it, and the library keeps the training
+ * kernels of this process apart (a call on another stream than the last one first waits for that
+ * one's kernel), so what remains is another PROCESS training with this library on the same device
+ * at the same time: two such kernels can hold each other's compute units until their waits give up
+ * (reported by dbsn_mlp_status as DBSN_E_TIMEOUT, weights undefined).  Choose PLAIN when the device
+ * is this process's own and calls are short (dbsn_bp_step: 54 instead of 72 us on the 12 M-weight
+ * net, 15 instead of 33 us on 784-300-10); results are the same bit for bit.  No device work. */
+#define DBSN_LAUNCH_COOPERATIVE 0
+#define DBSN_LAUNCH_PLAIN       1
+int32_t dbsn_mlp_set_launch(dbsn_mlp* mlp, int32_t kind);
+
 /* Polls a workgroup of the persistent kernel may spend waiting for one set of partial sums before
  * it gives up (default 2^22, seconds of waiting).  Exists so that the time-out path can be
  * exercised from the host. */

@@ -14,10 +14,11 @@ LIB_PATH = os.path.join(_HERE, "libdbsn.so")
 
 OK, E_ARG, E_SHAPE, E_HIP, E_TIMEOUT = 0, -1, -2, -3, -4
 MODE_LAUNCHES, MODE_PERSISTENT = 0, 1
+LAUNCH_COOPERATIVE, LAUNCH_PLAIN = 0, 1
 
 SYMBOLS = [
     "dbsn_mlp_arena_bytes", "dbsn_mlp_init", "dbsn_mlp_free", "dbsn_mlp_set_weights", "dbsn_mlp_get_weights",
-    "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_spin_limit",
+    "dbsn_mlp_get_activations", "dbsn_mlp_get_deltas", "dbsn_mlp_set_mode", "dbsn_mlp_set_launch", "dbsn_mlp_set_spin_limit",
     "dbsn_mlp_set_pauses", "dbsn_mlp_get_pauses", "dbsn_mlp_set_variant", "dbsn_mlp_get_variant",
     "dbsn_mlp_status", "dbsn_mlp_autotune", "dbsn_deform_batch", "dbsn_deform_batch_beta", "dbsn_deform_batch_labels",
     "dbsn_bp_steps", "dbsn_bp_step", "dbsn_forward", "dbsn_classify", "dbsn_classify_static", "dbsn_count_errors", "dbsn_mean_loss", "dbsn_probe_stream", "dbsn_probe_handover",
@@ -66,6 +67,7 @@ class Lib:
         c.dbsn_mlp_get_activations.argtypes = [vp, i32, vp]
         c.dbsn_mlp_get_deltas.argtypes = [vp, i32, vp]
         c.dbsn_mlp_set_mode.argtypes = [vp, i32]
+        c.dbsn_mlp_set_launch.argtypes = [vp, i32]
         c.dbsn_mlp_set_spin_limit.argtypes = [vp, C.c_uint32]
         c.dbsn_mlp_set_pauses.argtypes = [vp, vp, vp]
         c.dbsn_mlp_get_pauses.argtypes = [vp, vp, vp]
@@ -127,6 +129,9 @@ class Lib:
 
     def mlp_set_mode(self, h, mode):
         return self.c.dbsn_mlp_set_mode(h, mode)
+
+    def mlp_set_launch(self, h, kind):
+        return self.c.dbsn_mlp_set_launch(h, kind)
 
     def mlp_set_spin_limit(self, h, polls):
         return self.c.dbsn_mlp_set_spin_limit(h, polls)
@@ -241,6 +246,9 @@ class Mlp:
 
     def set_mode(self, mode):
         self.lib.check(self.lib.mlp_set_mode(self.h, mode))
+
+    def set_launch(self, kind):
+        self.lib.check(self.lib.mlp_set_launch(self.h, kind))
 
     def status(self):
         self.lib.check(self.lib.mlp_status(self.h))

@@ -79,6 +79,7 @@ struct dbsn_mlp {
     hipStream_t stream = nullptr;
     PNet pnet{};
     int mode = DBSN_MODE_PERSISTENT;
+    int launch = DBSN_LAUNCH_COOPERATIVE;   // how the persistent kernel is launched
     uint64_t epoch = 0;        // steps run by the persistent kernel so far (its tags continue from here)
     int device = 0;
     int cus = 0;
@@ -162,7 +163,21 @@ int32_t steps_launches(dbsn_mlp* m, const float* samples, const int* labels, int
     return DBSN_OK;
 }
 
-// One cooperative launch (all kPGroups workgroups resident together) runs the n steps.
+// Two persistent kernels on the chip at once could each hold compute units the other needs for its
+// last workgroups, and wait for ever (until the spin limit).  The driver keeps cooperative launches
+// apart; plain ones are kept apart here, for this process: per device, the stream of the last
+// persistent launch is remembered, and a launch on another stream first waits for everything that
+// stream has been given so far (an event recorded on it now covers that kernel).  Same stream: in
+// order anyway, nothing to do.
+struct LastPersistent {
+    hipStream_t stream = nullptr;
+    hipEvent_t done = nullptr;
+    bool any = false;
+};
+std::mutex g_persistent_mu;
+LastPersistent g_last_persistent[kMaxDevices];
+
+// One launch (all kPGroups workgroups resident together) runs the n steps.
 int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, int label_val, int64_t n, float eta,
                          float* loss) {
     const size_t lds = sizeof(float) * (size_t)(PLds::total + kProfLdsFloats);
@@ -185,7 +200,25 @@ int32_t steps_persistent(dbsn_mlp* m, const float* samples, const int* labels, i
     unsigned base = (unsigned)m->epoch;
     unsigned seq = m->die_launches;   // launches that took tickets so far: this one's tickets start at 32 * seq per die
     void* args[] = {&net, &samples, &labels, &label_val, &nn, &eta, &loss, &base, &seq};
-    HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, m->stream));
+    {
+        std::lock_guard<std::mutex> lock(g_persistent_mu);
+        LastPersistent& last = g_last_persistent[m->device];
+        if (last.any && last.stream != m->stream) {
+            if (!last.done) HIP_TRY(hipEventCreateWithFlags(&last.done, hipEventDisableTiming));
+            if (hipEventRecord(last.done, last.stream) == hipSuccess) {
+                HIP_TRY(hipStreamWaitEvent(m->stream, last.done, 0));
+            } else {   // (that stream is gone: wait for the device instead)
+                (void)hipGetLastError();
+                HIP_TRY(hipDeviceSynchronize());
+            }
+        }
+        if (m->launch == DBSN_LAUNCH_PLAIN)
+            HIP_TRY(hipLaunchKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, m->stream));
+        else
+            HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(kPGroups), dim3(kThreads), args, (unsigned)lds, m->stream));
+        last.any = true;
+        last.stream = m->stream;
+    }
     if (net.any_local) ++m->die_launches;
     m->epoch += (uint64_t)n;
     return DBSN_OK;
@@ -403,6 +436,11 @@ int32_t dbsn_mlp_init(dbsn_mlp** out, const int32_t* sizes, int32_t n_sizes, uin
 int32_t dbsn_mlp_free(dbsn_mlp* m) {
     if (!m) return DBSN_OK;
     (void)hipStreamSynchronize(m->stream);
+    {   // (nothing of this stream is running any more: no later launch needs to wait for it)
+        std::lock_guard<std::mutex> lock(g_persistent_mu);
+        LastPersistent& last = g_last_persistent[m->device];
+        if (last.any && last.stream == m->stream) last.any = false;
+    }
     delete m;
     return DBSN_OK;
 }
@@ -411,6 +449,13 @@ int32_t dbsn_mlp_set_mode(dbsn_mlp* m, int32_t mode) {
     if (check_mlp(m)) return DBSN_E_ARG;
     if (mode != DBSN_MODE_LAUNCHES && mode != DBSN_MODE_PERSISTENT) return fail(DBSN_E_ARG, "unknown mode %d", mode);
     m->mode = mode;
+    return DBSN_OK;
+}
+
+int32_t dbsn_mlp_set_launch(dbsn_mlp* m, int32_t kind) {
+    if (check_mlp(m)) return DBSN_E_ARG;
+    if (kind != DBSN_LAUNCH_COOPERATIVE && kind != DBSN_LAUNCH_PLAIN) return fail(DBSN_E_ARG, "unknown launch kind %d", kind);
+    m->launch = kind;
     return DBSN_OK;
 }
 

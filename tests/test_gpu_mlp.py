@@ -462,6 +462,55 @@ def test_kernel_variants_agree(sizes):
         assert np.abs(l - out[0][1]).max() <= 1e-5
 
 
+def test_plain_launches_and_two_networks_on_two_streams():
+    """dbsn_mlp_set_launch(PLAIN) launches the same kernel without the driver's co-residency
+    guarantee: the floats must be the same bit for bit; and two networks of this process on two
+    streams, their calls issued alternately without waiting (so that the launches would overlap on
+    the chip if nothing kept them apart), must both come out as they do alone - the library makes a
+    call on another stream than the last persistent launch wait for that launch.  With the waits'
+    spin limit at its default a pair of kernels holding each other's compute units would end in a
+    time-out, which status() would report."""
+    torch = _torch()
+    from paper_1003_0358_amd import binding
+    nets = ([784, 1500, 1000, 500, 10], [784, 300, 10])
+    X, y = _data(96, seed=21)
+    xs, ys = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    want = []
+    for sizes in nets:       # each alone, cooperative launches
+        m = _mk(sizes, 1, seed=6)
+        for a in range(0, 96, 4):
+            m.bp_steps(xs[a:a + 4], ys[a:a + 4], 1e-3)
+        m.status()
+        want.append(m.get_params())
+        m.close()
+    assert binding.load().mlp_set_launch(None, binding.LAUNCH_PLAIN) != 0            # null handle
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ms = []
+    for sizes, st in zip(nets, streams):
+        with torch.cuda.stream(st):
+            m = _mk(sizes, 1, seed=6)
+        assert m.lib.mlp_set_launch(m.h, 7) != 0                                     # unknown kind
+        m.set_launch(binding.LAUNCH_PLAIN)
+        ms.append(m)
+    torch.cuda.synchronize()
+    for a in range(0, 96, 4):                     # 24 short calls each, alternating, nothing waited for in between
+        for m, st in zip(ms, streams):
+            st.wait_stream(torch.cuda.current_stream())    # (the inputs were made on the current stream)
+            m.bp_steps(xs[a:a + 4], ys[a:a + 4], 1e-3)
+    for m, w in zip(ms, want):
+        m.status()
+        assert np.array_equal(m.get_params(), w)
+    # back to cooperative launches on one of them, the other still plain: still kept apart
+    ms[0].set_launch(binding.LAUNCH_COOPERATIVE)
+    for a in range(0, 32, 4):
+        for m in ms:
+            m.bp_steps(xs[a:a + 4], ys[a:a + 4], 0.0)      # (eta = 0: the weights stay as they are, bit for bit)
+    for m, w in zip(ms, want):
+        m.status()
+        assert np.array_equal(m.get_params(), w)
+        m.close()
+
+
 @pytest.mark.parametrize("sizes", [[784, 1500, 1000, 500, 10], [784, 64, 10], [784, 300, 10]],
                          ids=["banded", "32-tiles", "152-tiles"])
 def test_training_beside_a_kernel_on_another_stream(sizes):
